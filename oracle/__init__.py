@@ -1,0 +1,178 @@
+"""Dodo hot-path oracle: TEST INFRASTRUCTURE, not product code.
+
+Thin numpy/ctypes front end of ``dodo_oracle.cpp`` -- the plain,
+single-threaded, double-precision CPU statement of the Dodo compression path
+(arXiv 2310.02409: Eq. 5, 6, 8, 9, 13, 14, 15 and the count rule of Sec. 2.3).
+Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this package; the HIP library never does, and nothing here imports it.
+
+Arrays are numpy: ``float32`` for fp32 data, ``uint16`` for bfloat16 bit
+patterns.  All index arrays are ``int32``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dodo_oracle.cpp")
+_LIB = os.path.join(_HERE, "libdodo_oracle.so")
+
+F32, BF16 = 0, 1
+FORCE_LAST = 1
+TOKEN_MAJOR, HEAD_MAJOR = 0, 1
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (host only).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-Wall", "-Wextra", "-ffp-contract=off",
+               _SRC, "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_nugget_count.restype = ctypes.c_int64
+        lib.oracle_nugget_count.argtypes = [ctypes.c_int64] * 3
+        lib.oracle_select_topk.restype = ctypes.c_int
+        for name in ("oracle_score", "oracle_select_threshold", "oracle_gather", "oracle_attention",
+                     "oracle_attention_rows"):
+            getattr(lib, name).restype = None
+        _lib = lib
+    return _lib
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits) arrays, got {a.dtype}")
+
+
+def _p(a):
+    return ctypes.c_void_p(a.ctypes.data) if a is not None else ctypes.c_void_p(0)
+
+
+def _c(a, dtype=None):
+    a = np.ascontiguousarray(a) if dtype is None else np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def nugget_count(n: int, num: int, den: int) -> int:
+    """k = clamp(ceil(n * num / den), 1, n); 0 for an empty context (Sec. 2.3, Eq. 7)."""
+    return int(_load().oracle_nugget_count(int(n), int(num), int(den)))
+
+
+def cu_from_lengths(lengths) -> np.ndarray:
+    cu = np.zeros(len(lengths) + 1, dtype=np.int64)
+    np.cumsum(np.asarray(lengths, dtype=np.int64), out=cu[1:])
+    assert cu[-1] < 2**31
+    return cu.astype(np.int32)
+
+
+def score(hidden: np.ndarray, w: np.ndarray, bias: float = 0.0) -> np.ndarray:
+    """Linear-head Scorer (Eq. 6 / Eq. 15) over a packed [N, d] array -> fp32 [N]."""
+    hidden, w = _c(hidden), _c(w)
+    assert hidden.ndim == 2 and w.shape == (hidden.shape[1],) and w.dtype == hidden.dtype
+    N, d = hidden.shape
+    out = np.empty(N, dtype=np.float32)
+    _load().oracle_score(_p(hidden), _p(w), ctypes.c_float(bias), _dtype_code(hidden), ctypes.c_int64(N),
+                         ctypes.c_int64(d), ctypes.c_int64(d), _p(out))
+    return out
+
+
+def select_topk(scores: np.ndarray, cu_seqlens: np.ndarray, cu_nuggets: np.ndarray, flags: int = 0) -> np.ndarray:
+    """TopK selection (Eq. 14): sequence-local, ascending indices, packed by cu_nuggets."""
+    scores = _c(scores, np.float32)
+    cu_seqlens, cu_nuggets = _c(cu_seqlens, np.int32), _c(cu_nuggets, np.int32)
+    B = len(cu_seqlens) - 1
+    out = np.empty(int(cu_nuggets[-1]), dtype=np.int32)
+    rc = _load().oracle_select_topk(_p(scores), _p(cu_seqlens), _p(cu_nuggets), ctypes.c_int32(B),
+                                    ctypes.c_uint32(flags), _p(out))
+    if rc != 0:
+        raise ValueError("nugget count exceeds sequence length")
+    return out
+
+
+def select_threshold(scores: np.ndarray, cu_seqlens: np.ndarray, lam: float):
+    """Threshold selection (Eq. 8): (alpha flags uint8 [N], kept count per sequence int32 [B])."""
+    scores, cu_seqlens = _c(scores, np.float32), _c(cu_seqlens, np.int32)
+    B = len(cu_seqlens) - 1
+    alpha = np.zeros(len(scores), dtype=np.uint8)
+    counts = np.zeros(B, dtype=np.int32)
+    _load().oracle_select_threshold(_p(scores), _p(cu_seqlens), ctypes.c_int32(B), ctypes.c_float(lam), _p(alpha),
+                                    _p(counts))
+    return alpha, counts
+
+
+def gather(K: np.ndarray, V: np.ndarray, nugget_idx: np.ndarray, cu_seqlens: np.ndarray, cu_nuggets: np.ndarray,
+           layout: int = TOKEN_MAJOR):
+    """Sub-selection (Eq. 5) of K/V rows [N, H_kv, d_h] into the nugget cache."""
+    K, V = _c(K), _c(V)
+    assert K.ndim == 3 and K.shape == V.shape and K.dtype == V.dtype
+    nugget_idx, cu_seqlens, cu_nuggets = _c(nugget_idx, np.int32), _c(cu_seqlens, np.int32), _c(cu_nuggets, np.int32)
+    _, H_kv, d_h = K.shape
+    B = len(cu_seqlens) - 1
+    Kt = int(cu_nuggets[-1])
+    shape = (Kt, H_kv, d_h) if layout == TOKEN_MAJOR else (H_kv, Kt, d_h)
+    Kn, Vn = np.zeros(shape, dtype=K.dtype), np.zeros(shape, dtype=K.dtype)
+    _load().oracle_gather(_p(K), _p(V), _dtype_code(K), _p(nugget_idx), _p(cu_seqlens), _p(cu_nuggets),
+                          ctypes.c_int32(B), ctypes.c_int64(Kt), ctypes.c_int32(H_kv), ctypes.c_int32(d_h),
+                          ctypes.c_int64(H_kv * d_h), _p(Kn), _p(Vn), ctypes.c_int(layout))
+    return Kn, Vn
+
+
+def _attn_common(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, layout):
+    Q, Kn, Vn, Kl, Vl = _c(Q), _c(Kn), _c(Vn), _c(Kl), _c(Vl)
+    assert Q.ndim == 3 and Kn.ndim == 3 and Kl.ndim == 3
+    assert Q.dtype == Kn.dtype == Vn.dtype == Kl.dtype == Vl.dtype
+    cu_q, cu_nuggets, cu_local = _c(cu_q, np.int32), _c(cu_nuggets, np.int32), _c(cu_local, np.int32)
+    _, H, d_h = Q.shape
+    H_kv = Kl.shape[1]
+    Kt = int(cu_nuggets[-1])
+    want = (Kt, H_kv, d_h) if layout == TOKEN_MAJOR else (H_kv, Kt, d_h)
+    assert Kn.shape == want and Vn.shape == want, (Kn.shape, want)
+    assert Kl.shape == Vl.shape == (int(cu_local[-1]), H_kv, d_h)
+    assert Q.shape[0] == int(cu_q[-1]) and H % H_kv == 0
+    return Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, Kt
+
+
+def attention(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float, layout: int = TOKEN_MAJOR):
+    """Nugget attention (Eq. 13 / Eq. 9) for all rows -> (O float64 [Sq,H,d_h], lse float64 [Sq,H])."""
+    Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, Kt = _attn_common(
+        Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, layout)
+    B = len(cu_q) - 1
+    O = np.zeros(Q.shape, dtype=np.float64)
+    lse = np.zeros(Q.shape[:2], dtype=np.float64)
+    _load().oracle_attention(_p(Q), _p(Kn), _p(Vn), _p(Kl), _p(Vl), _p(cu_q), _p(cu_nuggets), _p(cu_local),
+                             ctypes.c_int32(B), ctypes.c_int32(H), ctypes.c_int32(H_kv), ctypes.c_int32(d_h),
+                             ctypes.c_double(scale), _dtype_code(Q), ctypes.c_int(layout), ctypes.c_int64(Kt),
+                             _p(O), _p(lse))
+    return O, lse
+
+
+def attention_rows(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float, rows, layout: int = TOKEN_MAJOR):
+    """Nugget attention for sampled (b, h, i) triples -> (O float64 [R,d_h], lse float64 [R])."""
+    Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, Kt = _attn_common(
+        Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, layout)
+    rows = np.asarray(rows, dtype=np.int32).reshape(-1, 3)
+    rb, rh, ri = (np.ascontiguousarray(rows[:, j]) for j in range(3))
+    R = len(rows)
+    O = np.zeros((R, d_h), dtype=np.float64)
+    lse = np.zeros(R, dtype=np.float64)
+    _load().oracle_attention_rows(_p(Q), _p(Kn), _p(Vn), _p(Kl), _p(Vl), _p(cu_q), _p(cu_nuggets), _p(cu_local),
+                                  ctypes.c_int32(H), ctypes.c_int32(H_kv), ctypes.c_int32(d_h),
+                                  ctypes.c_double(scale), _dtype_code(Q), ctypes.c_int(layout), ctypes.c_int64(Kt),
+                                  ctypes.c_int64(R), _p(rb), _p(rh), _p(ri), _p(O), _p(lse))
+    return O, lse

@@ -1,0 +1,238 @@
+// Dodo hot-path oracle: TEST INFRASTRUCTURE, not product code.
+//
+// A plain, single-threaded, double-precision CPU statement of what the Dodo
+// compression path computes (arXiv 2310.02409): count -> Scorer -> TopK ->
+// sub-selection of K/V -> attention over [nuggets ; local tokens].  Every
+// function is the definition written out: no tiling, no online softmax, no
+// radix tricks, no threads.  It shares no code, header or constant with the
+// HIP library and must never be imported by it; only the tests, the smoke
+// check and the benchmark's cpu_baseline leg may load it.
+//
+// Element types: 0 = IEEE fp32, 1 = bfloat16 stored as uint16 (upper half of
+// an fp32).  Both widen to double exactly.
+//
+// Pins (see tests/test_oracle_*.py): every function below is pinned by closed
+// forms, brute force and library cross-checks; none is "parity unpinned".
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+
+namespace {
+
+constexpr int kF32 = 0;
+constexpr int kBF16 = 1;
+constexpr uint32_t kForceLast = 1u;
+constexpr int kTokenMajor = 0;  // cache[token][head][channel]
+constexpr int kHeadMajor = 1;   // cache[head][token][channel]
+
+inline size_t elem_size(int dtype) { return dtype == kF32 ? 4 : 2; }
+
+inline double load(const void* base, int dtype, int64_t i) {
+  if (dtype == kF32) {
+    return static_cast<double>(static_cast<const float*>(base)[i]);
+  }
+  uint32_t bits = static_cast<uint32_t>(static_cast<const uint16_t*>(base)[i]) << 16;
+  float f;
+  std::memcpy(&f, &bits, 4);
+  return static_cast<double>(f);
+}
+
+// "a has a strictly higher score than b" with NaN placed below everything.
+inline bool higher(float a, float b) {
+  if (std::isnan(a)) return false;
+  if (std::isnan(b)) return true;
+  return a > b;  // -0.0f == +0.0f here, as required
+}
+
+struct AttnArgs {
+  const void *Q, *Kn, *Vn, *Kl, *Vl;
+  const int32_t *cu_q, *cu_nug, *cu_local;
+  int32_t H, H_kv, d_h;
+  double scale;
+  int dtype, layout;
+  int64_t Kt;  // total nugget rows (needed for the head-major cache)
+};
+
+inline int64_t cache_off(const AttnArgs& a, int64_t tok, int32_t kvh) {
+  if (a.layout == kTokenMajor) return (tok * a.H_kv + kvh) * a.d_h;
+  return (static_cast<int64_t>(kvh) * a.Kt + tok) * a.d_h;
+}
+
+// One query row of Eq. 13 (compressor mode) / Eq. 9 (mixed resolution):
+// softmax over every nugget of the sequence followed by the local rows the
+// causal rule admits, then the weighted mean of the matching V rows.
+void attention_row(const AttnArgs& a, int32_t b, int32_t h, int32_t i, double* o, double* lse) {
+  const int32_t dh = a.d_h;
+  const int32_t kvh = h / (a.H / a.H_kv);
+  const int64_t q_b = a.cu_q[b + 1] - a.cu_q[b];
+  const int64_t k_b = a.cu_nug[b + 1] - a.cu_nug[b];
+  const int64_t m_b = a.cu_local[b + 1] - a.cu_local[b];
+  // bottom-right aligned causal rule: local row j is visible iff j <= m_b - q_b + i
+  int64_t n_local = m_b - q_b + i + 1;
+  if (n_local < 0) n_local = 0;
+  if (n_local > m_b) n_local = m_b;
+  const int64_t n_vis = k_b + n_local;
+  for (int32_t c = 0; c < dh; ++c) o[c] = 0.0;
+  if (n_vis == 0) {
+    *lse = -std::numeric_limits<double>::infinity();
+    return;
+  }
+  const int64_t qoff = ((a.cu_q[b] + static_cast<int64_t>(i)) * a.H + h) * dh;
+  std::vector<double> logit(n_vis);
+  std::vector<int64_t> koff(n_vis);
+  std::vector<char> from_local(n_vis);
+  for (int64_t j = 0; j < n_vis; ++j) {
+    if (j < k_b) {
+      koff[j] = cache_off(a, a.cu_nug[b] + j, kvh);
+      from_local[j] = 0;
+    } else {
+      koff[j] = ((a.cu_local[b] + (j - k_b)) * a.H_kv + kvh) * dh;
+      from_local[j] = 1;
+    }
+    const void* kbase = from_local[j] ? a.Kl : a.Kn;
+    double dot = 0.0;
+    for (int32_t c = 0; c < dh; ++c) dot += load(a.Q, a.dtype, qoff + c) * load(kbase, a.dtype, koff[j] + c);
+    logit[j] = a.scale * dot;
+  }
+  double M = logit[0];
+  for (int64_t j = 1; j < n_vis; ++j) M = std::max(M, logit[j]);
+  double denom = 0.0;
+  for (int64_t j = 0; j < n_vis; ++j) {
+    const double p = std::exp(logit[j] - M);
+    denom += p;
+    const void* vbase = from_local[j] ? a.Vl : a.Vn;
+    for (int32_t c = 0; c < dh; ++c) o[c] += p * load(vbase, a.dtype, koff[j] + c);
+  }
+  for (int32_t c = 0; c < dh; ++c) o[c] /= denom;
+  *lse = M + std::log(denom);
+}
+
+}  // namespace
+
+extern "C" {
+
+// Nugget count for a context of n tokens at keep-fraction num/den, i.e. the
+// paper's k = ceil(n / r) with r = den/num (Sec. 2.3), clamped to 1 <= k <= n
+// (Eq. 7).  Integer arithmetic throughout.
+int64_t oracle_nugget_count(int64_t n, int64_t num, int64_t den) {
+  if (n <= 0) return 0;
+  int64_t k = (n * num + den - 1) / den;
+  if (k < 1) k = 1;
+  if (k > n) k = n;
+  return k;
+}
+
+// Scorer as a linear head (Eq. 6 / Eq. 15): s[t] = sum_c x[t,c] * w[c] + bias,
+// summed left to right in double, rounded once to fp32; -0 is emitted as +0.
+void oracle_score(const void* hidden, const void* w, float bias, int dtype, int64_t N, int64_t d,
+                  int64_t row_stride, float* scores) {
+  for (int64_t t = 0; t < N; ++t) {
+    double acc = 0.0;
+    for (int64_t c = 0; c < d; ++c) acc += load(hidden, dtype, t * row_stride + c) * load(w, dtype, c);
+    acc += static_cast<double>(bias);
+    float s = static_cast<float>(acc);
+    if (s == 0.0f) s = 0.0f;  // canonical zero
+    scores[t] = s;
+  }
+}
+
+// TopK selection (Eq. 14): per sequence, the k_b tokens with the highest score,
+// ties won by the lower index, emitted in ascending position order.  With the
+// force-last flag (footnote to Eq. 14) the final token of the sequence is
+// always one of the k_b and the remaining k_b - 1 are chosen among the others.
+// Returns 0, or -1 if some k_b exceeds its n_b.
+int oracle_select_topk(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
+                       uint32_t flags, int32_t* nugget_idx) {
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t n = cu_seqlens[b + 1] - cu_seqlens[b];
+    const int64_t k = cu_nuggets[b + 1] - cu_nuggets[b];
+    if (k > n || k < 0) return -1;
+    if (k == 0) continue;
+    const float* s = scores + cu_seqlens[b];
+    int32_t* out = nugget_idx + cu_nuggets[b];
+    const bool force = (flags & kForceLast) != 0;
+    const int64_t n_free = force ? n - 1 : n;  // tokens competing on score
+    const int64_t k_free = force ? k - 1 : k;
+    std::vector<int32_t> order(n_free);
+    for (int64_t i = 0; i < n_free; ++i) order[i] = static_cast<int32_t>(i);
+    // stable: equal scores keep ascending index order
+    std::stable_sort(order.begin(), order.end(), [s](int32_t x, int32_t y) { return higher(s[x], s[y]); });
+    std::vector<int32_t> chosen(order.begin(), order.begin() + k_free);
+    if (force) chosen.push_back(static_cast<int32_t>(n - 1));
+    std::sort(chosen.begin(), chosen.end());
+    for (int64_t j = 0; j < k; ++j) out[j] = chosen[j];
+  }
+  return 0;
+}
+
+// Threshold selection (Eq. 8): alpha_i = 1{s_i > Lambda}; writes the flags and
+// returns through counts[b] how many tokens each sequence keeps.
+void oracle_select_threshold(const float* scores, const int32_t* cu_seqlens, int32_t B, float lambda,
+                             uint8_t* alpha, int32_t* counts) {
+  for (int32_t b = 0; b < B; ++b) {
+    int32_t c = 0;
+    for (int64_t t = cu_seqlens[b]; t < cu_seqlens[b + 1]; ++t) {
+      alpha[t] = scores[t] > lambda ? 1 : 0;
+      c += alpha[t];
+    }
+    counts[b] = c;
+  }
+}
+
+// Sub-selection (Eq. 5): nuggets are the chosen tokens' own K and V rows,
+// copied bit for bit into the compact cache.
+void oracle_gather(const void* K, const void* V, int dtype, const int32_t* nugget_idx, const int32_t* cu_seqlens,
+                   const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t H_kv, int32_t d_h,
+                   int64_t token_stride, void* Kn, void* Vn, int layout) {
+  const size_t es = elem_size(dtype);
+  const size_t head_bytes = static_cast<size_t>(d_h) * es;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t k = cu_nuggets[b + 1] - cu_nuggets[b];
+    for (int64_t j = 0; j < k; ++j) {
+      const int64_t src_tok = cu_seqlens[b] + nugget_idx[cu_nuggets[b] + j];
+      const int64_t dst_tok = cu_nuggets[b] + j;
+      for (int32_t h = 0; h < H_kv; ++h) {
+        const size_t src = (static_cast<size_t>(src_tok) * token_stride + static_cast<size_t>(h) * d_h) * es;
+        const size_t dst = (layout == kTokenMajor)
+                               ? (static_cast<size_t>(dst_tok) * H_kv + h) * head_bytes
+                               : (static_cast<size_t>(h) * Kt + dst_tok) * head_bytes;
+        std::memcpy(static_cast<char*>(Kn) + dst, static_cast<const char*>(K) + src, head_bytes);
+        std::memcpy(static_cast<char*>(Vn) + dst, static_cast<const char*>(V) + src, head_bytes);
+      }
+    }
+  }
+}
+
+// Nugget attention for every query row of every sequence and head.
+// O is [sum q_b, H, d_h] in double, lse is [sum q_b, H] in double.
+void oracle_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                      const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local, int32_t B, int32_t H,
+                      int32_t H_kv, int32_t d_h, double scale, int dtype, int layout, int64_t Kt, double* O,
+                      double* lse) {
+  AttnArgs a{Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, scale, dtype, layout, Kt};
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t q_b = cu_q[b + 1] - cu_q[b];
+    for (int32_t i = 0; i < q_b; ++i) {
+      for (int32_t h = 0; h < H; ++h) {
+        const int64_t row = (static_cast<int64_t>(cu_q[b]) + i) * H + h;
+        attention_row(a, b, h, i, O + row * d_h, lse + row);
+      }
+    }
+  }
+}
+
+// The same definition for a list of sampled (sequence, head, query row)
+// triples; O_rows is [nrows, d_h], lse_rows is [nrows].
+void oracle_attention_rows(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                           const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local, int32_t H,
+                           int32_t H_kv, int32_t d_h, double scale, int dtype, int layout, int64_t Kt,
+                           int64_t nrows, const int32_t* row_b, const int32_t* row_h, const int32_t* row_i,
+                           double* O_rows, double* lse_rows) {
+  AttnArgs a{Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, scale, dtype, layout, Kt};
+  for (int64_t r = 0; r < nrows; ++r) attention_row(a, row_b[r], row_h[r], row_i[r], O_rows + r * d_h, lse_rows + r);
+}
+
+}  // extern "C"
