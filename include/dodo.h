@@ -1,0 +1,143 @@
+/*
+ * dodo.h -- C ABI of the Dodo hot path on MI355X (gfx950).
+ *
+ * Dodo (arXiv 2310.02409) compresses a context of n tokens into k << n
+ * "nuggets": a Scorer rates every token (Eq. 6 / Eq. 15), TopK keeps the k best
+ * per sequence (Eq. 14), the chosen tokens' own hidden states -- for attention,
+ * their K and V rows -- are kept at every layer (Eq. 5, Eq. 7), and later
+ * tokens attend over [nuggets ; recent uncompressed tokens] (Eq. 9, Eq. 13).
+ * The calls below are those four steps.
+ *
+ * Conventions shared by every call
+ *  - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *    never allocates, frees or keeps them.  Inputs are const and must not
+ *    alias outputs.  Workspaces are caller-owned device memory too.
+ *  - Ragged batches are packed: sequence b owns rows cu[b] .. cu[b+1]-1 of a
+ *    [total, ...] tensor; cu_* are DEVICE int32 arrays of B+1 non-decreasing
+ *    entries starting at 0 (their contents are trusted, not validated).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it and return; they never synchronise.
+ *  - Return value: DODO_OK or a negative DODO_ERR_* code.  Everything that can
+ *    be checked without touching the device is checked first, so invalid
+ *    arguments are rejected before any launch (and on hosts with no GPU).
+ *  - Data pointers must be 16-byte aligned; row strides must keep rows
+ *    16-byte aligned.
+ */
+#ifndef DODO_H_
+#define DODO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DODO_VERSION 100 /* major*10000 + minor*100 + patch */
+
+/* status codes */
+#define DODO_OK 0
+#define DODO_ERR_INVALID_ARG (-1)         /* null pointer, negative size, k > n, H % H_kv != 0, bad flag/layout */
+#define DODO_ERR_UNSUPPORTED (-2)         /* dtype / head_dim / alignment outside the supported set */
+#define DODO_ERR_WORKSPACE_TOO_SMALL (-3) /* ws_bytes below what the *_workspace_bytes query returns */
+#define DODO_ERR_HIP (-4)                 /* a HIP runtime call failed (launch error, no device) */
+
+/* element types of hidden states / Q / K / V (scores are always fp32) */
+#define DODO_DTYPE_F32 0
+#define DODO_DTYPE_BF16 1
+
+/* dodo_select_topk flags */
+#define DODO_TOPK_FORCE_LAST 1u /* the last token of each sequence is always selected (footnote to Eq. 14) */
+
+/* nugget-cache layouts (local K/V, Q and O are always token-major) */
+#define DODO_LAYOUT_TOKEN_MAJOR 0 /* [Kt, H_kv, d_h] */
+#define DODO_LAYOUT_HEAD_MAJOR 1  /* [H_kv, Kt, d_h] */
+
+/* Library version (DODO_VERSION of the build). Host only. */
+int dodo_version(void);
+
+/* Static, human-readable text for a status code; for DODO_ERR_HIP the text of
+ * the most recent HIP error seen by the calling thread. Host only. */
+const char* dodo_status_string(int status);
+
+/*
+ * Nugget count of an n-token context at keep-fraction num/den, i.e. the
+ * paper's k = ceil(n / r) with compression ratio r = den/num (Sec. 2.3),
+ * clamped to 1 <= k <= n (Eq. 7); 0 when n <= 0.  Pure host integer arithmetic:
+ * callers build cu_nuggets with it, so no device read-back is ever needed.
+ * Returns -1 if num <= 0 or den <= 0.
+ */
+int64_t dodo_nugget_count(int64_t n, int64_t num, int64_t den);
+
+/*
+ * Scorer as a linear head (Eq. 6 / Eq. 15): scores[t] = sum_c hidden[t,c]*w[c] + bias
+ * for t in [0, N).  hidden is [N, d] with `row_stride` elements between rows
+ * (>= d), w is [d], both of `dtype`; products and sums are fp32; scores is
+ * fp32 [N], with -0 written as +0.  d must be a multiple of 8.  The result is
+ * run-to-run deterministic.  N == 0 is a no-op.
+ */
+int dodo_score(const void* hidden, const void* w, float bias, int dtype, int64_t N, int32_t d, int64_t row_stride,
+               float* scores, void* stream);
+
+/* Bytes of device workspace dodo_select_topk needs for B sequences of at most max_n tokens (may be 0). */
+size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n);
+
+/*
+ * TopK selection (Eq. 14).  For each sequence b, with n_b = cu_seqlens[b+1] -
+ * cu_seqlens[b] and k_b = cu_nuggets[b+1] - cu_nuggets[b] (0 <= k_b <= n_b),
+ * writes to nugget_idx[cu_nuggets[b] ..] the sequence-local indices of the k_b
+ * tokens with the highest score, in ascending order.  Equal scores: the lower
+ * index wins.  NaN ranks below -inf; -0 equals +0.  With DODO_TOPK_FORCE_LAST
+ * token n_b-1 is always selected and the other k_b-1 are the best of the rest.
+ * Only integer comparisons on the score bits are used: the result is unique
+ * and bit-exact.  max_n / max_k are host-side upper bounds on n_b / k_b
+ * (0 < max_k <= max_n); a sequence longer than max_n is left unprocessed.
+ * ws may be NULL when the workspace query returns 0.  B == 0 is a no-op.
+ */
+int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
+                     int32_t max_n, int32_t max_k, uint32_t flags, int32_t* nugget_idx, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/*
+ * Sub-selection (Eq. 5): packs the chosen tokens' K and V rows into the compact
+ * nugget cache, bit for bit.  K, V are [N, H_kv, d_h] with `token_stride`
+ * elements between tokens (>= H_kv*d_h); nugget_idx holds sequence-local
+ * indices as written by dodo_select_topk; Kt = cu_nuggets[B] is the total
+ * nugget count (host value).  Output Kn, Vn: [Kt, H_kv, d_h] (token-major) or
+ * [H_kv, Kt, d_h] (head-major), contiguous.  Kt == 0 is a no-op.
+ */
+int dodo_gather_nuggets(const void* K, const void* V, int dtype, const int32_t* nugget_idx,
+                        const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t H_kv,
+                        int32_t d_h, int64_t token_stride, void* Kn, void* Vn, int layout, void* stream);
+
+/* Bytes of device workspace dodo_nugget_attention needs for these bounds (may be 0). */
+size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, int32_t max_k,
+                                             int32_t max_local, int dtype);
+
+/*
+ * Nugget attention (Eq. 13 compressor mode; Eq. 9 mixed resolution).  For
+ * sequence b with q_b query rows, k_b nuggets and m_b local rows, query row i
+ * of head h attends, with softmax(softmax_scale * q.k) in natural base, over
+ * all k_b nuggets followed by local rows j <= m_b - q_b + i (causal mask
+ * aligned to the bottom right: the local buffer ends with the query block's
+ * own K/V).  A row that sees nothing outputs 0 and lse = -inf.
+ *   Q  [sum q_b, H, d_h]       Kl, Vl [sum m_b, H_kv, d_h]   (token-major)
+ *   Kn, Vn nugget cache in `layout`, Kt = cu_nuggets[B] rows in total
+ *   O  [sum q_b, H, d_h] of `dtype`;  lse (optional, may be NULL) fp32 [sum q_b, H]
+ * Query head h reads KV head h / (H / H_kv).  max_q / max_k / max_local are
+ * host-side upper bounds on q_b / k_b / m_b.  Arithmetic: bf16 inputs are
+ * multiplied on the matrix cores with fp32 accumulation when max_q >= 16
+ * (query-block kernel); smaller max_q and all fp32 inputs use the bandwidth-
+ * bound split-K kernel with a fixed-order combine.  Both are deterministic.
+ * Supported: d_h in {64, 128} for the split-K kernel, d_h = 128 for the block kernel.
+ */
+int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                          const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local, int32_t B,
+                          int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local,
+                          int64_t Kt, float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws,
+                          size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DODO_H_ */

@@ -1,0 +1,14 @@
+"""Dodo hot path on MI355X: thin Python binding of the C-ABI library libdodo.so.
+
+The functions below carry the names of the C entry points declared in
+``include/dodo.h`` and only marshal arguments (pointers, sizes, the current
+HIP stream); every step of the path runs in the library's HIP kernels.  PyTorch
+is used for device memory and streams only.  There is no CPU fallback: if the
+library has not been built, importing this package raises.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, FORCE_LAST, HEAD_MAJOR, TOKEN_MAJOR, DodoError, LIB_PATH,
+    dodo_gather_nuggets, dodo_nugget_attention, dodo_nugget_attention_workspace_bytes, dodo_nugget_count,
+    dodo_score, dodo_select_topk, dodo_select_topk_workspace_bytes, dodo_status_string, dodo_version,
+    cu_nuggets_from_lengths, lib,
+)

@@ -1,0 +1,196 @@
+"""ctypes binding of libdodo.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdodo.so")
+
+F32, BF16 = 0, 1
+FORCE_LAST = 1
+TOKEN_MAJOR, HEAD_MAJOR = 0, 1
+
+
+class DodoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where} failed: {status} ({dodo_status_string(status)})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no fallback path.")
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, u32, vp, sz, f32 = (ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t,
+                                  ctypes.c_float)
+    L.dodo_version.restype = ctypes.c_int
+    L.dodo_version.argtypes = []
+    L.dodo_status_string.restype = ctypes.c_char_p
+    L.dodo_status_string.argtypes = [ctypes.c_int]
+    L.dodo_nugget_count.restype = i64
+    L.dodo_nugget_count.argtypes = [i64, i64, i64]
+    L.dodo_score.restype = ctypes.c_int
+    L.dodo_score.argtypes = [vp, vp, f32, ctypes.c_int, i64, i32, i64, vp, vp]
+    L.dodo_select_topk_workspace_bytes.restype = sz
+    L.dodo_select_topk_workspace_bytes.argtypes = [i32, i32]
+    L.dodo_select_topk.restype = ctypes.c_int
+    L.dodo_select_topk.argtypes = [vp, vp, vp, i32, i32, i32, u32, vp, vp, sz, vp]
+    L.dodo_gather_nuggets.restype = ctypes.c_int
+    L.dodo_gather_nuggets.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i64, i32, i32, i64, vp, vp, ctypes.c_int,
+                                      vp]
+    L.dodo_nugget_attention_workspace_bytes.restype = sz
+    L.dodo_nugget_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, ctypes.c_int]
+    L.dodo_nugget_attention.restype = ctypes.c_int
+    L.dodo_nugget_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
+                                        ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    return L
+
+
+lib = _load()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"dodo takes float32 or bfloat16 tensors, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise DodoError(rc, where)
+
+
+def _dev(*ts: Optional[torch.Tensor]) -> None:
+    for t in ts:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("dodo tensors must be contiguous device tensors")
+
+
+def dodo_version() -> int:
+    return int(lib.dodo_version())
+
+
+def dodo_status_string(status: int) -> str:
+    return lib.dodo_status_string(int(status)).decode()
+
+
+def dodo_nugget_count(n: int, num: int, den: int) -> int:
+    return int(lib.dodo_nugget_count(int(n), int(num), int(den)))
+
+
+def cu_nuggets_from_lengths(seq_lens: Sequence[int], num: int, den: int, device) -> Tuple[torch.Tensor, list]:
+    """Host-side prefix sums of dodo_nugget_count over the batch, uploaded as int32."""
+    ks = [dodo_nugget_count(n, num, den) for n in seq_lens]
+    cu = [0]
+    for k in ks:
+        cu.append(cu[-1] + k)
+    return torch.tensor(cu, dtype=torch.int32, device=device), ks
+
+
+def dodo_score(hidden: torch.Tensor, w: torch.Tensor, bias: float = 0.0,
+               scores: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores[t] = hidden[t] . w + bias (fp32 [N]) for packed hidden [N, d]."""
+    _dev(hidden, w, scores)
+    N, d = hidden.shape
+    assert w.shape == (d,) and w.dtype == hidden.dtype
+    if scores is None:
+        scores = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    assert scores.dtype == torch.float32 and scores.numel() == N
+    _check(lib.dodo_score(_ptr(hidden), _ptr(w), float(bias), _dtype_code(hidden), N, d, hidden.stride(0),
+                          _ptr(scores), _stream()), "dodo_score")
+    return scores
+
+
+def dodo_select_topk_workspace_bytes(B: int, max_n: int) -> int:
+    return int(lib.dodo_select_topk_workspace_bytes(B, max_n))
+
+
+def dodo_select_topk(scores: torch.Tensor, cu_seqlens: torch.Tensor, cu_nuggets: torch.Tensor, max_n: int, max_k: int,
+                     total_nuggets: int, flags: int = 0, nugget_idx: Optional[torch.Tensor] = None,
+                     ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Sequence-local, ascending indices of each sequence's top-k scores, packed by cu_nuggets (int32 [Kt])."""
+    _dev(scores, cu_seqlens, cu_nuggets, nugget_idx, ws)
+    assert scores.dtype == torch.float32 and cu_seqlens.dtype == torch.int32 and cu_nuggets.dtype == torch.int32
+    B = cu_seqlens.numel() - 1
+    assert cu_nuggets.numel() == B + 1
+    if nugget_idx is None:
+        nugget_idx = torch.empty(total_nuggets, dtype=torch.int32, device=scores.device)
+    assert nugget_idx.dtype == torch.int32 and nugget_idx.numel() >= total_nuggets
+    need = dodo_select_topk_workspace_bytes(B, max_n)
+    if need and ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=scores.device)
+    _check(lib.dodo_select_topk(_ptr(scores), _ptr(cu_seqlens), _ptr(cu_nuggets), B, max_n, max_k, flags,
+                                _ptr(nugget_idx), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "dodo_select_topk")
+    return nugget_idx
+
+
+def dodo_gather_nuggets(K: torch.Tensor, V: torch.Tensor, nugget_idx: torch.Tensor, cu_seqlens: torch.Tensor,
+                        cu_nuggets: torch.Tensor, total_nuggets: int, layout: int = TOKEN_MAJOR,
+                        Kn: Optional[torch.Tensor] = None, Vn: Optional[torch.Tensor] = None):
+    """Packs the chosen rows of K, V [N, H_kv, d_h] into the nugget cache."""
+    _dev(K, V, nugget_idx, cu_seqlens, cu_nuggets, Kn, Vn)
+    _, H_kv, d_h = K.shape
+    assert V.shape == K.shape and V.dtype == K.dtype
+    B = cu_seqlens.numel() - 1
+    shape = (total_nuggets, H_kv, d_h) if layout == TOKEN_MAJOR else (H_kv, total_nuggets, d_h)
+    if Kn is None:
+        Kn = torch.empty(shape, dtype=K.dtype, device=K.device)
+    if Vn is None:
+        Vn = torch.empty(shape, dtype=K.dtype, device=K.device)
+    assert tuple(Kn.shape) == shape and tuple(Vn.shape) == shape
+    _check(lib.dodo_gather_nuggets(_ptr(K), _ptr(V), _dtype_code(K), _ptr(nugget_idx), _ptr(cu_seqlens),
+                                   _ptr(cu_nuggets), B, total_nuggets, H_kv, d_h, K.stride(0), _ptr(Kn), _ptr(Vn),
+                                   layout, _stream()), "dodo_gather_nuggets")
+    return Kn, Vn
+
+
+def dodo_nugget_attention_workspace_bytes(B: int, H: int, d_h: int, max_q: int, max_k: int, max_local: int,
+                                          dtype: int) -> int:
+    return int(lib.dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, dtype))
+
+
+def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, Kl: torch.Tensor, Vl: torch.Tensor,
+                          cu_q: torch.Tensor, cu_nuggets: torch.Tensor, cu_local: torch.Tensor, max_q: int,
+                          max_k: int, max_local: int, softmax_scale: Optional[float] = None,
+                          layout: int = TOKEN_MAJOR, O: Optional[torch.Tensor] = None,
+                          lse: Optional[torch.Tensor] = None, want_lse: bool = False,
+                          ws: Optional[torch.Tensor] = None):
+    """Attention of Q [Sq, H, d_h] over [nuggets ; causally visible local rows]; returns (O, lse or None)."""
+    _dev(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, O, lse, ws)
+    Sq, H, d_h = Q.shape
+    H_kv = Kl.shape[1]
+    Kt = Kn.shape[0] if layout == TOKEN_MAJOR else Kn.shape[1]
+    B = cu_q.numel() - 1
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d_h)
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None and want_lse:
+        lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
+    code = _dtype_code(Q)
+    need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, code)
+    if need and ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    _check(lib.dodo_nugget_attention(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(Kl), _ptr(Vl), _ptr(cu_q), _ptr(cu_nuggets),
+                                     _ptr(cu_local), B, H, H_kv, d_h, max_q, max_k, max_local, Kt,
+                                     float(softmax_scale), code, layout, _ptr(O), _ptr(lse), _ptr(ws),
+                                     0 if ws is None else ws.numel(), _stream()), "dodo_nugget_attention")
+    return O, lse

@@ -1,0 +1,64 @@
+// dodo_nugget_attention: argument checks and dispatch between the MFMA
+// query-block kernel and the bandwidth-bound split-K kernel.
+#include "dodo_attn.h"
+
+namespace dodo {
+namespace {
+
+constexpr int kBlockKernelMinQ = 16;
+
+bool use_block_kernel(int dtype, int32_t d_h, int32_t max_q) {
+  return dtype == DODO_DTYPE_BF16 && d_h == 128 && max_q >= kBlockKernelMinQ;
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, int32_t max_k,
+                                                        int32_t max_local, int dtype) {
+  using namespace dodo;
+  if (B <= 0 || H <= 0 || d_h <= 0 || max_q <= 0 || max_k < 0 || max_local < 0) return 0;
+  if (use_block_kernel(dtype, d_h, max_q)) return 0;
+  return splitk_workspace_bytes(B, H, d_h, max_q, splitk_count(B, H, max_q, max_k, max_local));
+}
+
+extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                                     const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local,
+                                     int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
+                                     int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout,
+                                     void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  using namespace dodo;
+  if (B < 0 || H <= 0 || H_kv <= 0 || d_h <= 0 || max_q < 0 || max_k < 0 || max_local < 0 || Kt < 0)
+    return DODO_ERR_INVALID_ARG;
+  if (H % H_kv != 0) return DODO_ERR_INVALID_ARG;
+  if (layout != DODO_LAYOUT_TOKEN_MAJOR && layout != DODO_LAYOUT_HEAD_MAJOR) return DODO_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return DODO_ERR_INVALID_ARG;
+  if (B == 0 || max_q == 0) return DODO_OK;
+  if (!Q || !O || !cu_q || !cu_nuggets || !cu_local) return DODO_ERR_INVALID_ARG;
+  if (max_k > 0 && (!Kn || !Vn)) return DODO_ERR_INVALID_ARG;
+  if (max_local > 0 && (!Kl || !Vl)) return DODO_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
+  if (d_h != 64 && d_h != 128) return DODO_ERR_UNSUPPORTED;
+  if (!aligned16(Q) || !aligned16(O) || !aligned16(Kn) || !aligned16(Vn) || !aligned16(Kl) || !aligned16(Vl))
+    return DODO_ERR_UNSUPPORTED;
+  const size_t need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, dtype);
+  if (need > 0 && (!ws || ws_bytes < need)) return DODO_ERR_WORKSPACE_TOO_SMALL;
+
+  AttnParams p;
+  p.Q = Q; p.Kn = Kn; p.Vn = Vn; p.Kl = Kl; p.Vl = Vl;
+  p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.cu_local = cu_local;
+  p.B = B; p.H = H; p.H_kv = H_kv; p.d_h = d_h; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
+  if (layout == DODO_LAYOUT_TOKEN_MAJOR) {
+    p.nug_tok_stride = static_cast<int64_t>(H_kv) * d_h;
+    p.nug_head_stride = d_h;
+  } else {
+    p.nug_tok_stride = d_h;
+    p.nug_head_stride = Kt * d_h;
+  }
+  p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  p.dtype = dtype;
+  p.O = O; p.lse = lse; p.ws = ws;
+  p.stream = static_cast<hipStream_t>(stream);
+  if (use_block_kernel(dtype, d_h, max_q)) return launch_block_attention(p);
+  return launch_splitk_attention(p);
+}

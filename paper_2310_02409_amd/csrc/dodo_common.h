@@ -1,0 +1,63 @@
+// Internal helpers shared by the HIP translation units of libdodo (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dodo.h"
+
+namespace dodo {
+
+constexpr int kWave = 64;
+
+// Records the HIP error text for dodo_status_string and maps it to DODO_ERR_HIP.
+int record_hip_error(hipError_t e);
+
+#define DODO_HIP_TRY(expr)                                      \
+  do {                                                          \
+    hipError_t e_ = (expr);                                     \
+    if (e_ != hipSuccess) return ::dodo::record_hip_error(e_);  \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int elem_bytes(int dtype) { return dtype == DODO_DTYPE_F32 ? 4 : 2; }
+inline bool dtype_ok(int dtype) { return dtype == DODO_DTYPE_F32 || dtype == DODO_DTYPE_BF16; }
+
+// Checks the launch that was just enqueued.
+inline int launch_status() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DODO_OK : record_hip_error(e);
+}
+
+// bf16 <-> fp32 on raw bits (bf16 is the upper half of an fp32).
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+// round-to-nearest-even fp32 -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// 16-byte global load / store with the non-temporal hint (streamed once, no reuse)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
+  u32x4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, static_cast<u32x4_t*>(p));
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// number of set bits of `mask` strictly below this lane
+__device__ __forceinline__ int popc_below_lane(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+}  // namespace dodo

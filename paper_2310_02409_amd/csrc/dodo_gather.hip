@@ -1,0 +1,96 @@
+// dodo_gather_nuggets: sub-selection of the chosen tokens' K and V rows into
+// the compact nugget cache (Eq. 5 of the Dodo paper: nuggets are existing token
+// states, re-used rather than recomputed).
+//
+// Pure HBM copy: one workgroup per destination row moves the row's K and V
+// (H_kv*d_h elements each, 8 KiB for LLaMA-7B in bf16) with 16-byte loads that
+// are all issued before the first store.  The destination row's sequence is
+// found by a binary search over cu_nuggets, so nothing is read back to the host.
+#include "dodo_common.h"
+
+namespace dodo {
+namespace {
+
+constexpr int kGatherThreads = 256;
+constexpr int kMaxVec = 4;  // 16-byte vectors per thread per tensor held in registers at once
+
+template <bool HEAD_MAJOR>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const int32_t* __restrict__ nugget_idx,
+    const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt,
+    int vec_per_head, int vec_per_row, int64_t token_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
+  const int64_t dst_tok = blockIdx.x;
+  // sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1]
+  int lo = 0, hi = B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu_nuggets[mid] <= dst_tok) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
+  const uint4* ksrc = K + src_tok * token_stride_vec;
+  const uint4* vsrc = V + src_tok * token_stride_vec;
+
+  for (int c0 = threadIdx.x; c0 < vec_per_row; c0 += kGatherThreads * kMaxVec) {
+    uint4 kk[kMaxVec], vv[kMaxVec];
+#pragma unroll
+    for (int u = 0; u < kMaxVec; ++u) {
+      const int c = c0 + u * kGatherThreads;
+      if (c < vec_per_row) {
+        kk[u] = load16_stream(ksrc + c);
+        vv[u] = load16_stream(vsrc + c);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kMaxVec; ++u) {
+      const int c = c0 + u * kGatherThreads;
+      if (c < vec_per_row) {
+        int64_t dst;
+        if (HEAD_MAJOR) {
+          const int h = c / vec_per_head;
+          dst = (static_cast<int64_t>(h) * Kt + dst_tok) * vec_per_head + (c - h * vec_per_head);
+        } else {
+          dst = dst_tok * vec_per_row + c;
+        }
+        store16_stream(Kn + dst, kk[u]);
+        store16_stream(Vn + dst, vv[u]);
+      }
+    }
+  }
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" int dodo_gather_nuggets(const void* K, const void* V, int dtype, const int32_t* nugget_idx,
+                                   const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt,
+                                   int32_t H_kv, int32_t d_h, int64_t token_stride, void* Kn, void* Vn, int layout,
+                                   void* stream) {
+  using namespace dodo;
+  if (B < 0 || Kt < 0 || H_kv <= 0 || d_h <= 0) return DODO_ERR_INVALID_ARG;
+  if (token_stride < static_cast<int64_t>(H_kv) * d_h) return DODO_ERR_INVALID_ARG;
+  if (layout != DODO_LAYOUT_TOKEN_MAJOR && layout != DODO_LAYOUT_HEAD_MAJOR) return DODO_ERR_INVALID_ARG;
+  if (Kt == 0 || B == 0) return DODO_OK;
+  if (!K || !V || !nugget_idx || !cu_seqlens || !cu_nuggets || !Kn || !Vn) return DODO_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
+  if (Kt > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
+  const int es = elem_bytes(dtype);
+  if ((static_cast<int64_t>(d_h) * es) % 16 != 0 || (token_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(Kn) || !aligned16(Vn)) return DODO_ERR_UNSUPPORTED;
+
+  const int vec_per_head = d_h * es / 16;
+  const int vec_per_row = vec_per_head * H_kv;
+  const int64_t stride_vec = token_stride * es / 16;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid(static_cast<unsigned>(Kt)), block(kGatherThreads);
+  if (layout == DODO_LAYOUT_HEAD_MAJOR) {
+    hipLaunchKernelGGL(gather_kernel<true>, grid, block, 0, s, static_cast<const uint4*>(K),
+                       static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
+                       vec_per_row, stride_vec, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
+  } else {
+    hipLaunchKernelGGL(gather_kernel<false>, grid, block, 0, s, static_cast<const uint4*>(K),
+                       static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
+                       vec_per_row, stride_vec, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
+  }
+  return launch_status();
+}

@@ -1,0 +1,203 @@
+// dodo_select_topk: per-sequence TopK of the scorer output (Eq. 14 of the Dodo
+// paper) plus the ordered, segmented compaction that writes the nugget index
+// lists.  Integer work only, so the result is unique and bit-exact:
+//   1. every fp32 score becomes an order-preserving uint32 key (NaN lowest,
+//      -0 == +0), staged in LDS when the sequence fits (<= 36864 tokens);
+//   2. a 4-pass, 8-bit MSB radix select finds the key T of the k-th best token
+//      and how many tokens equal to T are still needed;
+//   3. a stable compaction emits, in ascending position order, every token
+//      with key > T and the first `need` tokens with key == T (lowest index
+//      wins ties).
+// One workgroup per sequence; histograms use LDS integer atomics with a
+// wavefront-level pre-aggregation so that heavy ties do not serialise.
+#include "dodo_common.h"
+
+namespace dodo {
+namespace {
+
+constexpr int kStagedMaxKeys = 36 * 1024;  // 144 KiB of the 160 KiB LDS
+
+__device__ __forceinline__ uint32_t order_key(float s) {
+  uint32_t u = __float_as_uint(s);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;  // NaN ranks below everything
+  if (u == 0x80000000u) u = 0u;                    // -0 == +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <int THREADS, bool STAGED>
+__global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __restrict__ scores,
+                                                              const int32_t* __restrict__ cu_seqlens,
+                                                              const int32_t* __restrict__ cu_nuggets, uint32_t flags,
+                                                              int max_n, int32_t* __restrict__ nugget_idx) {
+  constexpr int kWaves = THREADS / kWave;
+  extern __shared__ uint32_t keys_lds[];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t s_prefix, s_remaining;
+  __shared__ int wave_gt[kWaves], wave_eq[kWaves];
+
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  const int seq0 = cu_seqlens[b];
+  const int n = cu_seqlens[b + 1] - seq0;
+  const int nug0 = cu_nuggets[b];
+  int k = cu_nuggets[b + 1] - nug0;
+  if (k <= 0 || n <= 0 || n > max_n) return;  // uniform over the workgroup
+  if (k > n) k = n;
+  const bool force = (flags & DODO_TOPK_FORCE_LAST) != 0;
+  const int n_free = force ? n - 1 : n;  // tokens that compete on score
+  const int k_free = force ? k - 1 : k;
+  const float* s = scores + seq0;
+  int32_t* out = nugget_idx + nug0;
+
+  if (k_free > 0) {
+    if (STAGED) {
+      for (int i = tid; i < n_free; i += THREADS) keys_lds[i] = order_key(s[i]);
+      __syncthreads();
+    }
+    auto key_at = [&](int i) -> uint32_t { return STAGED ? keys_lds[i] : order_key(s[i]); };
+
+    // ---- radix select: key of the k_free-th best token ----
+    uint32_t prefix = 0, mask = 0, remaining = static_cast<uint32_t>(k_free);
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      for (int i = tid; i < 256; i += THREADS) hist[i] = 0;
+      __syncthreads();
+      for (int i0 = wave * kWave; i0 < n_free; i0 += THREADS) {
+        const int i = i0 + lane;
+        const uint32_t key = (i < n_free) ? key_at(i) : 0u;
+        bool part = (i < n_free) && ((key & mask) == prefix);
+        const uint32_t digit = (key >> shift) & 255u;
+        // two rounds of wavefront aggregation absorb the hot bins (ties, shared exponents)
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+          const uint64_t act = __ballot(part);
+          if (act == 0) break;
+          const int leader = __ffsll(static_cast<long long>(act)) - 1;
+          const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
+          const bool same = part && digit == d0;
+          const uint64_t mm = __ballot(same);
+          if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
+          part = part && !same;
+        }
+        if (part) atomicAdd(&hist[digit], 1u);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        // lane l owns bins 4l..4l+3; inclusive suffix sum over lanes
+        const uint32_t b0 = hist[4 * lane], b1 = hist[4 * lane + 1], b2 = hist[4 * lane + 2], b3 = hist[4 * lane + 3];
+        uint32_t suf = b0 + b1 + b2 + b3;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+          const uint32_t t = __shfl_down(suf, off, kWave);
+          if (lane + off < kWave) suf += t;
+        }
+        const uint64_t ge = __ballot(suf >= remaining);  // non-empty: suf(lane 0) = #candidates >= remaining
+        const int L = 63 - __clzll(static_cast<long long>(ge));
+        if (lane == L) {
+          uint32_t above = suf - (b0 + b1 + b2 + b3);  // candidates in bins above this lane's
+          int dsel;
+          if (above + b3 >= remaining) {
+            dsel = 3;
+          } else if (above + b3 + b2 >= remaining) {
+            dsel = 2;
+            above += b3;
+          } else if (above + b3 + b2 + b1 >= remaining) {
+            dsel = 1;
+            above += b3 + b2;
+          } else {
+            dsel = 0;
+            above += b3 + b2 + b1;
+          }
+          s_prefix = prefix | (static_cast<uint32_t>(4 * L + dsel) << shift);
+          s_remaining = remaining - above;
+        }
+      }
+      __syncthreads();
+      prefix = s_prefix;
+      remaining = s_remaining;
+      mask |= 255u << shift;
+    }
+    const uint32_t T = prefix;                        // key of the k_free-th best token
+    const int need_eq = static_cast<int>(remaining);  // tokens equal to T still to take, lowest index first
+
+    // ---- stable compaction over contiguous per-wavefront ranges ----
+    const int per_wave = ((n_free + kWaves * kWave - 1) / (kWaves * kWave)) * kWave;
+    const int start = wave * per_wave;
+    const int end = min(start + per_wave, n_free);
+    int cnt_gt = 0, cnt_eq = 0;
+    for (int i0 = start; i0 < end; i0 += kWave) {
+      const int i = i0 + lane;
+      const uint32_t key = (i < end) ? key_at(i) : 0u;
+      cnt_gt += __popcll(__ballot(i < end && key > T));
+      cnt_eq += __popcll(__ballot(i < end && key == T));
+    }
+    if (lane == 0) {
+      wave_gt[wave] = cnt_gt;
+      wave_eq[wave] = cnt_eq;
+    }
+    __syncthreads();
+    int eq_base = 0, out_base = 0;
+    for (int w = 0; w < wave; ++w) {
+      const int e = wave_eq[w];
+      out_base += wave_gt[w] + max(0, min(e, need_eq - eq_base));
+      eq_base += e;
+    }
+    for (int i0 = start; i0 < end; i0 += kWave) {
+      const int i = i0 + lane;
+      const uint32_t key = (i < end) ? key_at(i) : 0u;
+      const bool is_eq = i < end && key == T;
+      const uint64_t eq_mask = __ballot(is_eq);
+      const bool sel = (i < end && key > T) || (is_eq && eq_base + popc_below_lane(eq_mask) < need_eq);
+      const uint64_t sel_mask = __ballot(sel);
+      const int pos = out_base + popc_below_lane(sel_mask);
+      if (sel && pos < k_free) out[pos] = i;  // pos < k_free always holds; the test keeps a logic slip in bounds
+      eq_base += __popcll(eq_mask);
+      out_base += __popcll(sel_mask);
+    }
+  }
+  if (force && tid == 0) out[k - 1] = n - 1;
+}
+
+template <int THREADS>
+int launch_select(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int32_t max_n,
+                  uint32_t flags, int32_t* nugget_idx, hipStream_t stream) {
+  if (max_n <= kStagedMaxKeys) {
+    const size_t lds = static_cast<size_t>(max_n) * sizeof(uint32_t);
+    auto kern = select_topk_kernel<THREADS, true>;
+    if (lds > 48 * 1024) {
+      DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       static_cast<int>(lds)));
+    }
+    hipLaunchKernelGGL(kern, dim3(B), dim3(THREADS), lds, stream, scores, cu_seqlens, cu_nuggets, flags, max_n,
+                       nugget_idx);
+  } else {
+    hipLaunchKernelGGL((select_topk_kernel<THREADS, false>), dim3(B), dim3(THREADS), 0, stream, scores, cu_seqlens,
+                       cu_nuggets, flags, max_n, nugget_idx);
+  }
+  return launch_status();
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n) {
+  (void)B;
+  (void)max_n;
+  return 0;  // keys live in LDS (or are re-read from the score array); no global scratch
+}
+
+extern "C" int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
+                                int32_t max_n, int32_t max_k, uint32_t flags, int32_t* nugget_idx, void* ws,
+                                size_t ws_bytes, void* stream) {
+  using namespace dodo;
+  (void)ws;
+  (void)ws_bytes;
+  if (B < 0) return DODO_ERR_INVALID_ARG;
+  if (B == 0) return DODO_OK;
+  if (!scores || !cu_seqlens || !cu_nuggets || !nugget_idx) return DODO_ERR_INVALID_ARG;
+  if (max_n <= 0 || max_k <= 0 || max_k > max_n) return DODO_ERR_INVALID_ARG;
+  if (flags & ~DODO_TOPK_FORCE_LAST) return DODO_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (max_n <= 4096) return launch_select<256>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
+  return launch_select<1024>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
+}

@@ -1,0 +1,124 @@
+"""GPU parity: dodo_nugget_attention (split-K and MFMA query-block kernels) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from gpu_util import check_attention, check_lse, default_scale, dev, make_attention_case
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def D():
+    import paper_2310_02409_amd as D
+    return D
+
+
+def _run(D, devt, q_lens, k_lens, m_lens, scale, layout=0, want_lse=True):
+    return D.dodo_nugget_attention(devt["Q"], devt["Kn"], devt["Vn"], devt["Kl"], devt["Vl"], devt["cu_q"],
+                                   devt["cu_nuggets"], devt["cu_local"], max(q_lens), max(k_lens), max(m_lens),
+                                   scale, layout, want_lse=want_lse)
+
+
+def _full_check(D, seed, q_lens, k_lens, m_lens, H, H_kv, d_h, dtype, scale=None):
+    host, devt = make_attention_case(seed, q_lens, k_lens, m_lens, H, H_kv, d_h, dtype, dev())
+    scale = default_scale(d_h) if scale is None else scale
+    O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
+                                      host["cu_nuggets"], host["cu_local"], scale)
+    O, lse = _run(D, devt, q_lens, k_lens, m_lens, scale)
+    err = check_attention(O, O_ref, dtype)
+    check_lse(lse, lse_ref, dtype)
+    return err
+
+
+# ---------------------------------------------------------------- split-K kernel (decode, fp32, small q)
+@pytest.mark.parametrize("dtype,H,H_kv,d_h", [
+    (torch.float32, 4, 4, 64), (torch.bfloat16, 32, 32, 128), (torch.bfloat16, 8, 2, 128),
+    (torch.bfloat16, 4, 4, 64), (torch.float32, 4, 2, 128),
+])
+def test_decode_ragged(D, dtype, H, H_kv, d_h):
+    k_lens = [205, 410, 333, 1, 0]
+    m_lens = [257, 257, 40, 3, 5]
+    _full_check(D, 400, [1] * 5, k_lens, m_lens, H, H_kv, d_h, dtype)
+
+
+def test_decode_split_k_paths(D):
+    # few (sequence, head) pairs and many rows: the split count goes above 1 and the combine kernel runs
+    assert D.dodo_nugget_attention_workspace_bytes(2, 2, 128, 1, 3277, 1089, D.BF16) > 0
+    _full_check(D, 401, [1, 1], [3277, 1500], [1089, 1025], 2, 2, 128, torch.bfloat16)
+    _full_check(D, 402, [1], [2000], [300], 2, 1, 64, torch.float32)
+
+
+def test_tiny_fp32_config_block_through_split_k_kernel(D):
+    # workload 1: 32 causal query rows, 16 earlier local rows, 52 nuggets, 4 heads x 64, fp32
+    _full_check(D, 403, [32], [52], [48], 4, 4, 64, torch.float32)
+    _full_check(D, 404, [7, 3], [10, 0], [7, 9], 2, 2, 128, torch.float32)
+
+
+def test_rows_that_see_nothing(D):
+    # no nuggets and a local buffer shorter than the query block: the first rows have an empty visible set
+    _full_check(D, 405, [4], [0], [2], 2, 2, 64, torch.float32)
+    _full_check(D, 406, [40], [0], [20], 2, 2, 128, torch.bfloat16)
+
+
+# ---------------------------------------------------------------- MFMA query-block kernel
+@pytest.mark.parametrize("q_lens,k_lens,m_lens,H,H_kv", [
+    ([128], [64], [128], 2, 2),
+    ([512, 512], [410, 410], [640, 640], 4, 4),       # workload-2 shape, fewer heads
+    ([100, 37, 256, 16], [13, 200, 0, 77], [150, 37, 300, 16], 4, 2),  # ragged, GQA, partial tiles
+    ([300], [103], [300], 3, 1),                      # tau = 0 (compressor mode), q not a tile multiple
+    ([64, 200], [500, 9], [0, 100], 2, 2),            # nuggets only; local shorter than the block
+])
+def test_block_attention_bf16(D, q_lens, k_lens, m_lens, H, H_kv):
+    _full_check(D, 410, q_lens, k_lens, m_lens, H, H_kv, 128, torch.bfloat16)
+
+
+def test_block_attention_scale_argument_and_head_major_cache(D):
+    q_lens, k_lens, m_lens = [130, 64], [90, 31], [200, 64]
+    host, devt = make_attention_case(411, q_lens, k_lens, m_lens, 4, 2, 128, torch.bfloat16, dev())
+    for scale in (0.05, 0.2):
+        O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
+                                          host["cu_nuggets"], host["cu_local"], scale)
+        O, lse = _run(D, devt, q_lens, k_lens, m_lens, scale)
+        check_attention(O, O_ref, torch.bfloat16)
+        check_lse(lse, lse_ref, torch.bfloat16)
+        hm = dict(devt)
+        hm["Kn"] = devt["Kn"].permute(1, 0, 2).contiguous()
+        hm["Vn"] = devt["Vn"].permute(1, 0, 2).contiguous()
+        O2, _ = _run(D, hm, q_lens, k_lens, m_lens, scale, layout=1)
+        assert torch.equal(O, O2)
+
+
+def test_block_kernel_row_equals_decode_kernel_row(D):
+    # the same query row through both kernels (block: q rows at once; split-K: one row, truncated local buffer)
+    q, k, tau = 48, 100, 20
+    host, devt = make_attention_case(412, [q], [k], [tau + q], 4, 4, 128, torch.bfloat16, dev())
+    scale = default_scale(128)
+    O_blk, _ = _run(D, devt, [q], [k], [tau + q], scale)
+    for i in (0, 17, 47):
+        m_i = tau + i + 1
+        d1 = dict(devt)
+        d1["Q"] = devt["Q"][i:i + 1].contiguous()
+        d1["Kl"], d1["Vl"] = devt["Kl"][:m_i].contiguous(), devt["Vl"][:m_i].contiguous()
+        d1["cu_q"] = W.cumulative([1], dev())
+        d1["cu_local"] = W.cumulative([m_i], dev())
+        O_dec, _ = _run(D, d1, [1], [k], [m_i], scale)
+        assert torch.max(torch.abs(O_dec[0].float() - O_blk[i].float())) <= 2e-2
+
+
+def test_attention_is_deterministic(D):
+    q_lens, k_lens, m_lens = [256], [410], [384]
+    _, devt = make_attention_case(413, q_lens, k_lens, m_lens, 8, 8, 128, torch.bfloat16, dev())
+    first, _ = _run(D, devt, q_lens, k_lens, m_lens, 0.088)
+    first = first.clone()
+    for _ in range(20):
+        O, _ = _run(D, devt, q_lens, k_lens, m_lens, 0.088)
+        assert torch.equal(O, first)
+    _, devd = make_attention_case(414, [1] * 4, [3000] * 4, [500] * 4, 2, 2, 128, torch.bfloat16, dev())
+    first, _ = _run(D, devd, [1] * 4, [3000] * 4, [500] * 4, 0.088)
+    first = first.clone()
+    for _ in range(20):
+        O, _ = _run(D, devd, [1] * 4, [3000] * 4, [500] * 4, 0.088)
+        assert torch.equal(O, first)

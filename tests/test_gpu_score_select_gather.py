@@ -1,0 +1,159 @@
+"""GPU parity: dodo_score, dodo_select_topk, dodo_gather_nuggets against the oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from gpu_util import dev, oracle_counts
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def D():
+    import paper_2310_02409_amd as D
+    return D
+
+
+# ---------------------------------------------------------------- scorer
+@pytest.mark.parametrize("dtype,N,d", [
+    (torch.float32, 512, 256), (torch.bfloat16, 1000, 4096), (torch.bfloat16, 77, 5120),
+    (torch.float32, 33, 4096), (torch.bfloat16, 5, 8), (torch.bfloat16, 4097, 520), (torch.float32, 130, 8200),
+])
+def test_score_matches_oracle(D, dtype, N, d):
+    x = W.normal(100, 0, (N, d), 1.0, dtype)
+    w = W.normal(100, 1, (d,), d ** -0.5, dtype)
+    ref = oracle.score(W.to_numpy(x), W.to_numpy(w), 0.125)
+    got = D.dodo_score(x.to(dev()), w.to(dev()), 0.125).cpu().numpy()
+    # fp32 accumulation of d products of magnitude ~ |x||w|: error << 1e-5 (1 + |s|)
+    assert np.all(np.abs(got - ref) <= 1e-5 * (1 + np.abs(ref))), np.max(np.abs(got - ref))
+
+
+def test_score_exact_arithmetic_inputs_are_bit_exact(D):
+    for dtype in (torch.float32, torch.bfloat16):
+        x, w = W.exact_arithmetic_inputs(7, 2048, 4096, dtype)
+        ref = oracle.score(W.to_numpy(x), W.to_numpy(w))
+        got = D.dodo_score(x.to(dev()), w.to(dev())).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+def test_score_is_deterministic_and_respects_row_stride(D):
+    x = W.normal(101, 0, (300, 1024), 1.0, torch.bfloat16).to(dev())
+    w = W.normal(101, 1, (512,), 0.05, torch.bfloat16).to(dev())
+    view = x[:, :512]  # row stride 1024, d = 512
+    scores = torch.empty(300, dtype=torch.float32, device=dev())
+    rc = D.lib.dodo_score(view.data_ptr(), w.data_ptr(), 0.0, D.BF16, 300, 512, 1024, scores.data_ptr(),
+                          torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    ref = oracle.score(W.to_numpy(view.contiguous()), W.to_numpy(w))
+    assert np.all(np.abs(scores.cpu().numpy() - ref) <= 1e-5 * (1 + np.abs(ref)))
+    first = scores.clone()
+    for _ in range(20):
+        D.lib.dodo_score(view.data_ptr(), w.data_ptr(), 0.0, D.BF16, 300, 512, 1024, scores.data_ptr(),
+                         torch.cuda.current_stream().cuda_stream)
+        assert torch.equal(scores, first)
+
+
+# ---------------------------------------------------------------- select
+def _select_both(D, scores_np, n_lens, k_lens, flags=0):
+    cu_s, cu_k = oracle.cu_from_lengths(n_lens), oracle.cu_from_lengths(k_lens)
+    ref = oracle.select_topk(scores_np, cu_s, cu_k, flags)
+    got = D.dodo_select_topk(torch.from_numpy(scores_np).to(dev()), torch.from_numpy(cu_s).to(dev()),
+                             torch.from_numpy(cu_k).to(dev()), max(n_lens), max(max(k_lens), 1), int(cu_k[-1]),
+                             flags).cpu().numpy()
+    assert np.array_equal(got, ref)
+    return got
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("n_lens,den", [
+    ([512], 10), ([4096] * 8, 10), ([2048] * 16, 20), ([1, 2, 3, 64, 65, 127, 128, 129, 4095, 4097, 5000], 10),
+    ([32768, 32768], 10), ([40000, 37000], 10), ([100, 0, 300], 3), ([8192, 4096, 6000], 20),
+])
+def test_select_bit_exact_gaussian_and_quantised(D, n_lens, den, flags):
+    k_lens = [oracle.nugget_count(n, 1, den) for n in n_lens]
+    s = W.normal(200 + den, len(n_lens), (sum(n_lens),), 1.0, torch.float32)
+    _select_both(D, s.numpy(), n_lens, k_lens, flags)
+    _select_both(D, W.quantise16(s).numpy(), n_lens, k_lens, flags)  # heavy ties: winners decided by index
+
+
+def test_select_specials_and_degenerate_counts(D):
+    s = W.normal(210, 0, (3000,), 1.0, torch.float32).numpy().copy()
+    s[::7] = np.nan
+    s[3::11] = np.inf
+    s[5::13] = -np.inf
+    s[1::17] = 0.0
+    s[2::19] = -0.0
+    for k in (1, 2, 150, 1500, 2999, 3000):
+        for flags in (0, 1):
+            _select_both(D, s, [3000], [k], flags)
+    const = np.full(5000, -3.25, np.float32)
+    assert list(_select_both(D, const, [5000], [500])) == list(range(500))
+    # k_b = 0 for some sequences, k_b = n_b for others
+    _select_both(D, s, [1000, 1000, 1000], [0, 1000, 17])
+
+
+def test_select_on_gpu_scores_matches_oracle_select_on_the_same_array(D):
+    # shared-array rule: the oracle selects on the scores the GPU scorer produced, and vice versa
+    wl = W.config(2, scale_down=4)
+    t = W.make_inputs(wl, which=["hidden", "w"])
+    s_gpu = D.dodo_score(t["hidden"].to(dev()), t["w"].to(dev())).cpu().numpy()
+    k_lens, _ = oracle_counts(wl.seq_lens, wl.keep_num, wl.keep_den)
+    _select_both(D, s_gpu, wl.seq_lens, k_lens, 1)
+    s_or = oracle.score(W.to_numpy(t["hidden"]), W.to_numpy(t["w"]))
+    _select_both(D, s_or, wl.seq_lens, k_lens, 1)
+
+
+def test_exact_arithmetic_raw_inputs_to_indices_bit_exact(D):
+    # scores are exact in any summation order, so scorer + select must agree end to end, ties and all
+    n_lens = [3000, 1234]
+    x, w = W.exact_arithmetic_inputs(9, sum(n_lens), 1024, torch.bfloat16)
+    k_lens, cu_k = oracle_counts(n_lens, 1, 10)
+    cu_s = oracle.cu_from_lengths(n_lens)
+    ref = oracle.select_topk(oracle.score(W.to_numpy(x), W.to_numpy(w)), cu_s, cu_k)
+    s_gpu = D.dodo_score(x.to(dev()), w.to(dev()))
+    got = D.dodo_select_topk(s_gpu, torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()), max(n_lens),
+                             max(k_lens), int(cu_k[-1]))
+    assert np.array_equal(got.cpu().numpy(), ref)
+
+
+def test_select_is_deterministic(D):
+    n_lens = [32768, 20000]
+    k_lens, cu_k = oracle_counts(n_lens, 1, 10)
+    s = W.quantise16(W.normal(220, 0, (sum(n_lens),), 1.0, torch.float32)).to(dev())
+    cu_s = torch.from_numpy(oracle.cu_from_lengths(n_lens)).to(dev())
+    cu_kd = torch.from_numpy(cu_k).to(dev())
+    first = D.dodo_select_topk(s, cu_s, cu_kd, max(n_lens), max(k_lens), int(cu_k[-1])).clone()
+    for _ in range(100):
+        assert torch.equal(D.dodo_select_topk(s, cu_s, cu_kd, max(n_lens), max(k_lens), int(cu_k[-1])), first)
+
+
+# ---------------------------------------------------------------- gather
+@pytest.mark.parametrize("dtype,H_kv,d_h", [(torch.bfloat16, 32, 128), (torch.float32, 4, 64), (torch.bfloat16, 3, 64),
+                                            (torch.bfloat16, 40, 128)])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_gather_bit_exact(D, dtype, H_kv, d_h, layout):
+    n_lens = [700, 1, 0, 333]
+    N = sum(n_lens)
+    K = W.normal(300, 0, (N, H_kv, d_h), 1.0, dtype)
+    V = W.normal(300, 1, (N, H_kv, d_h), 1.0, dtype)
+    k_lens, cu_k = oracle_counts(n_lens, 1, 5)
+    cu_s = oracle.cu_from_lengths(n_lens)
+    s = W.normal(300, 2, (N,), 1.0, torch.float32).numpy()
+    idx = oracle.select_topk(s, cu_s, cu_k)
+    Kn_ref, Vn_ref = oracle.gather(W.to_numpy(K), W.to_numpy(V), idx, cu_s, cu_k, layout)
+    Kn, Vn = D.dodo_gather_nuggets(K.to(dev()), V.to(dev()), torch.from_numpy(idx).to(dev()),
+                                   torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()),
+                                   int(cu_k[-1]), layout)
+    assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)
+
+
+def test_gather_ratio_one_is_identity(D):
+    n_lens = [129, 64]
+    K = W.normal(301, 0, (sum(n_lens), 8, 128), 1.0, torch.bfloat16).to(dev())
+    V = W.normal(301, 1, (sum(n_lens), 8, 128), 1.0, torch.bfloat16).to(dev())
+    cu = torch.from_numpy(oracle.cu_from_lengths(n_lens)).to(dev())
+    idx = torch.cat([torch.arange(n, dtype=torch.int32) for n in n_lens]).to(dev())
+    Kn, Vn = D.dodo_gather_nuggets(K, V, idx, cu, cu, sum(n_lens))
+    assert torch.equal(Kn, K) and torch.equal(Vn, V)
