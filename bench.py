@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dodo hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of the LLaMA-7B-shaped
+prefill workload (bf16, batch 8, 4096 context tokens per sequence, 10x
+compression, 512-token query block after 128 local tokens):
+
+    dodo_score -> dodo_select_topk -> dodo_gather_nuggets
+      -> dodo_nugget_attention (512-row query block, MFMA kernel)
+      -> dodo_nugget_attention (one decode token per sequence, split-K kernel)
+
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line:
+whole-step query tokens/s, the per-kernel durations measured with events on
+the launch stream inside the timed region, the roofline of the dominant
+kernel, and the oracle timed on the host cores on a bounded sample of the same
+workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="workload id (2 = LLaMA-7B prefill, the metric's config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-events", action="store_true", help="no per-kernel events inside the timed region")
+    return ap.parse_args()
+
+
+def algorithmic_work(wl, ks, E):
+    """Algorithmic bytes / flop per launch (what the method itself must move or compute)."""
+    N, d, B = wl.N, wl.d_model, wl.B
+    Hd = wl.H_kv * wl.d_h
+    Kt = sum(ks)
+    Sq = sum(wl.q_lens)
+    vis_pairs = sum(sum(k + (m - q + i + 1) for i in range(q)) for k, m, q in zip(ks, wl.local_lens, wl.q_lens))
+    out = {
+        "score": {"bytes": N * d * E + d * E + 4 * N, "flop": 2 * N * d},
+        "select": {"bytes": 4 * N + 4 * Kt + 8 * (B + 1), "flop": 0},
+        "gather": {"bytes": 2 * (2 * Kt * Hd * E) + 4 * Kt, "flop": 0},
+        "attn_block": {"bytes": E * (2 * Sq * wl.H * wl.d_h + 2 * sum(k + m for k, m in zip(ks, wl.local_lens)) * Hd),
+                       "flop": 4 * wl.d_h * wl.H * vis_pairs},
+    }
+    dec_rows = sum(k + m + 1 for k, m in zip(ks, wl.local_lens))
+    out["attn_decode"] = {"bytes": E * (2 * B * wl.H * wl.d_h + 2 * dec_rows * Hd), "flop": 4 * wl.d_h * wl.H * dec_rows}
+    return out
+
+
+def cpu_baseline(wl, host, ks, scale):
+    """Times the oracle, as it stands, on sequence 0 of the batch (all sequences have the same shape):
+    score + select + gather of its context and attention for all its query tokens, all heads."""
+    import numpy as np
+    import oracle
+    n0, q0, m0, k0 = wl.seq_lens[0], wl.q_lens[0], wl.local_lens[0], ks[0]
+    cu_s, cu_k = oracle.cu_from_lengths([n0]), oracle.cu_from_lengths([k0])
+    cu_q, cu_m = oracle.cu_from_lengths([q0]), oracle.cu_from_lengths([m0])
+    t0 = time.perf_counter()
+    s = oracle.score(host["hidden"][:n0], host["w"])
+    idx = oracle.select_topk(s, cu_s, cu_k, oracle.FORCE_LAST)
+    Kn, Vn = oracle.gather(host["K"][:n0], host["V"][:n0], idx, cu_s, cu_k)
+    t1 = time.perf_counter()
+    oracle.attention(host["Q"][:q0], Kn, Vn, host["Kl"][:m0], host["Vl"][:m0], cu_q, cu_k, cu_m, scale)
+    oracle.attention(host["Qd"][:1], Kn, Vn, host["Kld"][:m0 + 1], host["Vld"][:m0 + 1], oracle.cu_from_lengths([1]),
+                     cu_k, oracle.cu_from_lengths([m0 + 1]), scale)
+    t2 = time.perf_counter()
+    total = t2 - t0
+    return {"value": (q0 + 1) / total, "unit": "query tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"sequence 0 of {wl.B} (n={n0}, k={k0}, q={q0}+1 decode token, all {wl.H} heads): "
+                      f"score+select+gather {t1 - t0:.2f} s, attention {t2 - t1:.2f} s; "
+                      "per-sequence cost is identical, so tokens/s carries over to the whole batch"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2310_02409_amd as D
+    import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    wl = W.config(args.workload)
+    E = 2 if wl.dtype == torch.bfloat16 else 4
+    g = W.make_inputs(wl, dev)
+    B = wl.B
+    # decode sub-step: one new token per sequence; its local buffer is the prefill's plus the token itself
+    dec_local = [m + 1 for m in wl.local_lens]
+    g["Qd"] = W.normal(wl.seed, 10, (B, wl.H, wl.d_h), 1.0, wl.dtype, dev)
+    g["Kld"] = W.normal(wl.seed, 11, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+    g["Vld"] = W.normal(wl.seed, 12, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+    cu_qd, cu_ld = W.cumulative([1] * B, dev), W.cumulative(dec_local, dev)
+    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
+    Kt, max_n, max_k = sum(ks), max(wl.seq_lens), max(ks)
+    max_q, max_m = max(wl.q_lens), max(wl.local_lens)
+    scale = wl.d_h ** -0.5
+
+    # every output and workspace is allocated once, outside the timed region
+    scores = torch.empty(wl.N, dtype=torch.float32, device=dev)
+    idx = torch.empty(Kt, dtype=torch.int32, device=dev)
+    Kn = torch.empty((Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
+    Vn = torch.empty_like(Kn)
+    O = torch.empty_like(g["Q"])
+    Od = torch.empty_like(g["Qd"])
+    ws_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max_k, max(dec_local), D.BF16 if E == 2 else D.F32)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    names = ["score", "select", "gather", "attn_block", "attn_decode"]
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        D.dodo_score(g["hidden"], g["w"], 0.0, scores)
+        if events is not None:
+            events[1].record()
+        D.dodo_select_topk(scores, g["cu_seqlens"], cu_k, max_n, max_k, Kt, D.FORCE_LAST, idx)
+        if events is not None:
+            events[2].record()
+        D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
+        if events is not None:
+            events[3].record()
+        D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k, max_m,
+                                scale, D.TOKEN_MAJOR, O)
+        if events is not None:
+            events[4].record()
+        D.dodo_nugget_attention(g["Qd"], Kn, Vn, g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1, max_k, max(dec_local),
+                                scale, D.TOKEN_MAJOR, Od, ws=ws)
+        if events is not None:
+            events[5].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = None
+    if not args.no_events:
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(None if ev is None else ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    q_tokens = sum(wl.q_lens) + B
+    value = q_tokens / (ms_per_step * 1e-3)
+
+    work = algorithmic_work(wl, ks, E)
+    kernels = {}
+    if ev is not None:
+        for j, name in enumerate(names):
+            us = sorted(e[j].elapsed_time(e[j + 1]) * 1e3 for e in ev)
+            avg = sum(us) / len(us)
+            kernels[name] = {"avg_us": round(avg, 2), "median_us": round(us[len(us) // 2], 2), "min_us": round(us[0], 2),
+                             "GBps": round(work[name]["bytes"] / avg * 1e-3, 1),
+                             "TFLOPs": round(work[name]["flop"] / avg * 1e-6, 2)}
+        kernels["attn_block"]["query_tokens_per_s"] = round(sum(wl.q_lens) / kernels["attn_block"]["avg_us"] * 1e6)
+        kernels["attn_decode"]["query_tokens_per_s"] = round(B / kernels["attn_decode"]["avg_us"] * 1e6)
+        tg = kernels["select"]["avg_us"] + kernels["gather"]["avg_us"]
+        kernels["topk_plus_gather_GBps"] = round((work["select"]["bytes"] + work["gather"]["bytes"]) / tg * 1e-3, 1)
+        dom = max(names, key=lambda n: kernels[n]["avg_us"])
+        if dom in ("attn_block",):
+            ach = work[dom]["flop"] / kernels[dom]["avg_us"] * 1e-6
+            roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+        else:
+            ach = work[dom]["bytes"] / kernels[dom]["avg_us"] * 1e-3
+            roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):  # HBM bytes per launch from the committed counter runs, if recorded for this kernel
+            roof["traffic"] = json.load(open(tpath)).get(wl.name, {}).get(dom)
+    else:
+        roof = None
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        host = {k: W.to_numpy(v) for k, v in g.items() if k in ("hidden", "w", "K", "V", "Q", "Kl", "Vl")}
+        n0, m0 = wl.seq_lens[0], wl.local_lens[0]
+        host = {k: (v[:n0] if k in ("hidden", "K", "V") else v) for k, v in host.items()}
+        host["Qd"], host["Kld"], host["Vld"] = (W.to_numpy(g[k][:m0 + 1]) for k in ("Qd", "Kld", "Vld"))
+        cpu = cpu_baseline(wl, host, ks, scale)
+        cpu["value"] = round(cpu["value"], 2)
+
+    line = {
+        "metric": "nugget-attention query tokens/s (whole hot-path step: score+TopK+gather+block attention+decode token)",
+        "value": round(value, 1), "unit": "query tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if E == 2 else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "context": wl.seq_lens[0] if len(set(wl.seq_lens)) == 1 else "ragged",
+                   "nuggets_per_seq": ks[0], "query_block": max_q, "local_tokens": wl.tau[0], "d_model": wl.d_model,
+                   "heads": wl.H, "head_dim": wl.d_h, "layers": 1, "decode_tokens_per_seq": 1},
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
