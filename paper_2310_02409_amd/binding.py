@@ -22,12 +22,12 @@ class DodoError(RuntimeError):
         super().__init__(f"{where} failed: {status} ({dodo_status_string(status)})")
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(LIB_PATH):
+def _load(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            f"{path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
             "There is no fallback path.")
-    L = ctypes.CDLL(LIB_PATH)
+    L = ctypes.CDLL(path)
     i32, i64, u32, vp, sz, f32 = (ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t,
                                   ctypes.c_float)
     L.dodo_version.restype = ctypes.c_int

@@ -167,21 +167,38 @@ __global__ __launch_bounds__(kThreads, 2) void block_attention_kernel(
     const char* kbuf = lds + (tile & 1) * kTileBytes;
     const char* vbuf = lds + (2 + (tile & 1)) * kTileBytes;
 
-    // ---- S^T = K Q^T : two 32-key blocks ----
+    // ---- S^T = K Q^T : two 32-key blocks; all 16 K fragments are requested before the first MFMA ----
+    bf16x8 kf[2][kDH / 16];
+#pragma unroll
+    for (int ds = 0; ds < kDH / 16; ++ds)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        kf[kb][ds] =
+            *reinterpret_cast<const bf16x8*>(kbuf + kb * 32 * kRowBytes + k_row_off + (((2 * ds + g) ^ k_sw) << 4));
     floatx16 acc_s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
 #pragma unroll
-    for (int ds = 0; ds < kDH / 16; ++ds) {
+    for (int ds = 0; ds < kDH / 16; ++ds)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 a =
-            *reinterpret_cast<const bf16x8*>(kbuf + kb * 32 * kRowBytes + k_row_off + (((2 * ds + g) ^ k_sw) << 4));
-        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ds], acc_s[kb], 0, 0, 0);
-      }
-    }
+      for (int kb = 0; kb < 2; ++kb)
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ds], qf[ds], acc_s[kb], 0, 0, 0);
+
+    // ---- V^T fragments for the whole tile are requested now and land while the softmax runs ----
+    // slot 8g+4e+r of k-step t <-> key 16t + 8e + 4g + r
+    shortx4 vf[4][kDH / 32][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int cb = 0; cb < kDH / 32; ++cb)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int r = 16 * t + 8 * e + v_r;
+          const char* p = vbuf + r * kRowBytes + ((cb ^ (r & 3)) << 6) + v_in;
+          vf[t][cb][e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
+        }
 
     // ---- online softmax (base 2); accumulator v of block kb <-> key 32kb + 8(v/4) + 4g + v%4 ----
     float tmax = kNegInf;
@@ -235,19 +252,12 @@ __global__ __launch_bounds__(kThreads, 2) void block_attention_kernel(
     }
     l_run += psum;
 
-    // ---- O^T += V^T P^T : slot 8g+4e+r of k-step t <-> key 16t + 8e + 4g + r ----
+    // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
       for (int cb = 0; cb < kDH / 32; ++cb) {
-        shortx4 a[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int r = 16 * t + 8 * e + v_r;
-          const char* p = vbuf + r * kRowBytes + ((cb ^ (r & 3)) << 6) + v_in;
-          a[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
-        }
-        const shortx8 a8 = __builtin_shufflevector(a[0], a[1], 0, 1, 2, 3, 4, 5, 6, 7);
+        const shortx8 a8 = __builtin_shufflevector(vf[t][cb][0], vf[t][cb][1], 0, 1, 2, 3, 4, 5, 6, 7);
         acc_o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pf[t], acc_o[cb], 0, 0, 0);
       }
     }
