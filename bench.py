@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--workload", type=int, default=2, help="workload id (2 = LLaMA-7B prefill, the metric's config)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-events", action="store_true", help="no per-kernel events inside the timed region")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference for the HBM traffic counters)")
     return ap.parse_args()
 
 
@@ -143,6 +145,14 @@ def main():
                                 scale, D.TOKEN_MAJOR, Od, ws=ws)
         if events is not None:
             events[5].record()
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -1,0 +1,117 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol include/dodo.h declares, and
+rejects bad arguments before touching a device (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dodo.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2310_02409_amd as D
+    return D.lib
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dodo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_functions()
+    assert {"dodo_score", "dodo_select_topk", "dodo_gather_nuggets", "dodo_nugget_attention", "dodo_nugget_count",
+            "dodo_version", "dodo_status_string", "dodo_select_topk_workspace_bytes",
+            "dodo_nugget_attention_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
+
+
+def test_version_and_status_strings():
+    import paper_2310_02409_amd as D
+    assert D.dodo_version() == 100
+    assert D.dodo_status_string(0) == "ok"
+    assert "invalid" in D.dodo_status_string(-1)
+    assert "unsupported" in D.dodo_status_string(-2)
+    assert "workspace" in D.dodo_status_string(-3)
+    assert D.dodo_status_string(-99) == "unknown status"
+
+
+def test_nugget_count_matches_the_papers_worked_sizes():
+    import paper_2310_02409_amd as D
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "nugget_counts.txt"))
+            if l.strip() and not l.startswith("#")]
+    for n, r, k in rows:
+        assert D.dodo_nugget_count(int(n), 1, int(r)) == int(k)
+    assert [D.dodo_nugget_count(n, 1, 10) for n in (512, 4096, 32768)] == [52, 410, 3277]
+    assert D.dodo_nugget_count(8192, 1, 20) == 410 and D.dodo_nugget_count(2048, 1, 20) == 103
+    assert D.dodo_nugget_count(0, 1, 10) == 0 and D.dodo_nugget_count(5, 1, 100) == 1
+    assert D.dodo_nugget_count(7, 1, 1) == 7 and D.dodo_nugget_count(7, 3, 1) == 7
+    assert D.dodo_nugget_count(10, 0, 5) == -1 and D.dodo_nugget_count(10, 1, 0) == -1
+    assert D.dodo_nugget_count(2 ** 62, 1, 10) == (2 ** 62 + 9) // 10
+
+
+def test_nugget_count_agrees_with_the_oracle_everywhere():
+    import oracle
+    import paper_2310_02409_amd as D
+    for n in list(range(0, 300)) + [4095, 4096, 4097, 8191, 32768, 10 ** 7]:
+        for num, den in [(1, 10), (1, 20), (1, 5), (1, 1), (3, 7), (7, 100)]:
+            assert D.dodo_nugget_count(n, num, den) == oracle.nugget_count(n, num, den)
+
+
+P = 0x1000  # any non-null, 16-byte aligned fake pointer: validation must fail before it is used
+
+
+def test_score_argument_validation(lib):
+    assert lib.dodo_score(0, P, 0.0, 1, 8, 64, 64, P, 0) == -1          # null hidden
+    assert lib.dodo_score(P, P, 0.0, 1, -1, 64, 64, P, 0) == -1         # negative N
+    assert lib.dodo_score(P, P, 0.0, 1, 8, 64, 32, P, 0) == -1          # stride < d
+    assert lib.dodo_score(P, P, 0.0, 7, 8, 64, 64, P, 0) == -2          # dtype
+    assert lib.dodo_score(P, P, 0.0, 1, 8, 60, 64, P, 0) == -2          # d not a multiple of 8
+    assert lib.dodo_score(P + 2, P, 0.0, 1, 8, 64, 64, P, 0) == -2      # misaligned
+    assert lib.dodo_score(0, 0, 0.0, 1, 0, 64, 64, 0, 0) == 0           # N == 0 is a no-op
+
+
+def test_select_argument_validation(lib):
+    assert lib.dodo_select_topk(0, P, P, 2, 10, 5, 0, P, 0, 0, 0) == -1
+    assert lib.dodo_select_topk(P, P, P, 2, 10, 11, 0, P, 0, 0, 0) == -1  # max_k > max_n
+    assert lib.dodo_select_topk(P, P, P, 2, 10, 0, 0, P, 0, 0, 0) == -1   # max_k == 0
+    assert lib.dodo_select_topk(P, P, P, 2, 10, 5, 6, P, 0, 0, 0) == -1   # unknown flag bits
+    assert lib.dodo_select_topk(P, P, P, -1, 10, 5, 0, P, 0, 0, 0) == -1
+    assert lib.dodo_select_topk(0, 0, 0, 0, 10, 5, 0, 0, 0, 0, 0) == 0    # B == 0 is a no-op
+    assert lib.dodo_select_topk_workspace_bytes(8, 4096) == 0
+
+
+def test_gather_argument_validation(lib):
+    assert lib.dodo_gather_nuggets(0, P, 1, P, P, P, 2, 10, 4, 64, 256, P, P, 0, 0) == -1
+    assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 10, 4, 64, 100, P, P, 0, 0) == -1   # stride < H_kv*d_h
+    assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 10, 4, 64, 256, P, P, 2, 0) == -1   # layout
+    assert lib.dodo_gather_nuggets(P, P, 5, P, P, P, 2, 10, 4, 64, 256, P, P, 0, 0) == -2   # dtype
+    assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 10, 4, 60, 240, P, P, 0, 0) == -2   # row not 16-byte multiple
+    assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 0, 4, 64, 256, P, P, 0, 0) == 0     # no nuggets: no-op
+
+
+def test_attention_argument_validation(lib):
+    def call(Q=P, Kn=P, Vn=P, Kl=P, Vl=P, B=2, H=8, H_kv=8, d_h=128, max_q=64, max_k=10, max_local=64, Kt=20,
+             scale=0.1, dtype=1, layout=0, O=P, ws=0, ws_bytes=0):
+        return lib.dodo_nugget_attention(Q, Kn, Vn, Kl, Vl, P, P, P, B, H, H_kv, d_h, max_q, max_k, max_local, Kt, scale,
+                                         dtype, layout, O, 0, ws, ws_bytes, 0)
+    assert call(Q=0) == -1
+    assert call(H=8, H_kv=3) == -1
+    assert call(layout=3) == -1
+    assert call(scale=float("nan")) == -1
+    assert call(Kn=0) == -1                       # nuggets expected but no cache
+    assert call(dtype=4) == -2
+    assert call(d_h=96) == -2
+    assert call(Q=P + 4) == -2
+    assert call(B=0) == 0 and call(max_q=0) == 0  # nothing to do
+    # decode shape with few (sequence, head) pairs needs a split-K workspace
+    need = lib.dodo_nugget_attention_workspace_bytes(2, 2, 128, 1, 3277, 1089, 1)
+    assert need > 0
+    assert call(B=2, H=2, H_kv=2, max_q=1, max_k=3277, max_local=1089, ws=0, ws_bytes=0) == -3
+    assert call(B=2, H=2, H_kv=2, max_q=1, max_k=3277, max_local=1089, ws=P, ws_bytes=need - 1) == -3
+    assert lib.dodo_nugget_attention_workspace_bytes(8, 32, 128, 512, 410, 640, 1) == 0

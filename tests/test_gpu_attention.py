@@ -122,3 +122,12 @@ def test_attention_is_deterministic(D):
     for _ in range(20):
         O, _ = _run(D, devd, [1] * 4, [3000] * 4, [500] * 4, 0.088)
         assert torch.equal(O, first)
+
+
+@pytest.mark.parametrize("scale", [8.0, -0.09, 0.0])
+def test_block_attention_exact_fallback_paths(D, scale):
+    # 8-wavefront kernel: a huge scale spreads the logits far beyond the fixed per-row exponent offset
+    # (rows fall back to the running-maximum loop); non-positive scales take that loop from the start
+    _full_check(D, 415, [300, 130], [200, 64], [364, 130], 2, 2, 128, torch.bfloat16, scale=scale)
+    # 4-wavefront kernel (short query block) with the same scales
+    _full_check(D, 416, [100], [70], [120], 2, 1, 128, torch.bfloat16, scale=scale)
