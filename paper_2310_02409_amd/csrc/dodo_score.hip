@@ -1,9 +1,10 @@
 // dodo_score: the Scorer as a linear head d -> 1 (Eq. 6 / Eq. 15 of the Dodo paper).
 //
 // HBM-bound GEMV: every hidden row is read once, 16 bytes per lane per load,
-// one wavefront per row with several loads in flight; the weight vector is
-// staged once per workgroup in LDS as fp32.  The 64-lane reduction has a fixed
-// order, so the scores are run-to-run deterministic.
+// one wavefront per row with several loads in flight (and, for widths that
+// split evenly, the next batch of loads in flight while the current one is
+// reduced); the weight vector is staged once per workgroup in LDS as fp32.
+// Summation order is fixed, so the scores are run-to-run deterministic.
 #include "dodo_common.h"
 
 namespace dodo {
@@ -17,15 +18,17 @@ struct Elems;
 template <>
 struct Elems<DODO_DTYPE_BF16> {
   static constexpr int kPerLoad = 8;
+  // w points at 8 consecutive fp32 weights, 16-byte aligned
   __device__ static __forceinline__ float dot(const uint4& v, const float* w) {
-    float a = bf16_lo(v.x) * w[0];
-    a = fmaf(bf16_hi(v.x), w[1], a);
-    a = fmaf(bf16_lo(v.y), w[2], a);
-    a = fmaf(bf16_hi(v.y), w[3], a);
-    a = fmaf(bf16_lo(v.z), w[4], a);
-    a = fmaf(bf16_hi(v.z), w[5], a);
-    a = fmaf(bf16_lo(v.w), w[6], a);
-    a = fmaf(bf16_hi(v.w), w[7], a);
+    const float4 w0 = *reinterpret_cast<const float4*>(w), w1 = *reinterpret_cast<const float4*>(w + 4);
+    float a = bf16_lo(v.x) * w0.x;
+    a = fmaf(bf16_hi(v.x), w0.y, a);
+    a = fmaf(bf16_lo(v.y), w0.z, a);
+    a = fmaf(bf16_hi(v.y), w0.w, a);
+    a = fmaf(bf16_lo(v.z), w1.x, a);
+    a = fmaf(bf16_hi(v.z), w1.y, a);
+    a = fmaf(bf16_lo(v.w), w1.z, a);
+    a = fmaf(bf16_hi(v.w), w1.w, a);
     return a;
   }
   __device__ static __forceinline__ float load_one(const void* p, int64_t i) {
@@ -35,11 +38,13 @@ struct Elems<DODO_DTYPE_BF16> {
 template <>
 struct Elems<DODO_DTYPE_F32> {
   static constexpr int kPerLoad = 4;
+  // w points at 4 consecutive fp32 weights, 16-byte aligned
   __device__ static __forceinline__ float dot(const uint4& v, const float* w) {
-    float a = __uint_as_float(v.x) * w[0];
-    a = fmaf(__uint_as_float(v.y), w[1], a);
-    a = fmaf(__uint_as_float(v.z), w[2], a);
-    a = fmaf(__uint_as_float(v.w), w[3], a);
+    const float4 w0 = *reinterpret_cast<const float4*>(w);
+    float a = __uint_as_float(v.x) * w0.x;
+    a = fmaf(__uint_as_float(v.y), w0.y, a);
+    a = fmaf(__uint_as_float(v.z), w0.z, a);
+    a = fmaf(__uint_as_float(v.w), w0.w, a);
     return a;
   }
   __device__ static __forceinline__ float load_one(const void* p, int64_t i) {
@@ -61,7 +66,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
   using E = Elems<DTYPE>;
   constexpr int kEPL = E::kPerLoad;     // elements per 16-byte load
   constexpr int kChunk = kWave * kEPL;  // elements one wave-wide load covers
-  extern __shared__ float w_lds[];
+  extern __shared__ __attribute__((aligned(16))) float w_lds[];
   for (int c = threadIdx.x; c < d; c += kScoreThreads) w_lds[c] = E::load_one(w, c);
   __syncthreads();
 
@@ -98,6 +103,131 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
   }
 }
 
+// Software-pipelined variant for widths that split evenly: d == nb * PB * (64 lanes * elements per
+// load).  A row is read in nb batches of PB wave-wide 16-byte loads; the loads of the next batch
+// (same row, or the wavefront's next row) are in flight while the current one is multiplied and
+// reduced.  Same summation order per row as the generic kernel.
+// SINGLE: the whole row is one batch (nb == 1); the weight fragments are then loop-invariant and
+// stay in registers.
+template <int DTYPE, int PB, bool SINGLE>
+__global__ __launch_bounds__(kScoreThreads) void score_pipelined_kernel(const void* __restrict__ hidden,
+                                                                        const void* __restrict__ w, float bias,
+                                                                        int64_t N, int d, int nb_arg,
+                                                                        int64_t row_stride,
+                                                                        float* __restrict__ scores) {
+  const int nb = SINGLE ? 1 : nb_arg;
+  using E = Elems<DTYPE>;
+  constexpr int kEPL = E::kPerLoad;
+  constexpr int kChunk = kWave * kEPL;
+  extern __shared__ __attribute__((aligned(16))) float w_lds[];
+  for (int c = threadIdx.x; c < d; c += kScoreThreads) w_lds[c] = E::load_one(w, c);
+  __syncthreads();
+
+  const int lane = lane_id();
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kScoreThreads / kWave) + threadIdx.x / kWave;
+  const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (kScoreThreads / kWave);
+  const size_t esz = DTYPE == DODO_DTYPE_F32 ? 4 : 2;
+  const int lane_c = lane * kEPL;
+
+  auto load_batch = [&](uint4 (&v)[PB], int64_t row, int bi) {
+    const char* rp = static_cast<const char*>(hidden) + (static_cast<size_t>(row) * row_stride + bi * PB * kChunk + lane_c) * esz;
+#pragma unroll
+    for (int u = 0; u < PB; ++u) v[u] = load16_stream(rp + static_cast<size_t>(u * kChunk) * esz);
+  };
+
+  float acc = 0.f;
+  auto consume = [&](const uint4 (&v)[PB], int64_t row, int bi) {
+    float part[PB];
+#pragma unroll
+    for (int u = 0; u < PB; ++u) part[u] = E::dot(v[u], &w_lds[((SINGLE ? 0 : bi) * PB + u) * kChunk + lane_c]);
+#pragma unroll
+    for (int u = 0; u < PB; ++u) acc += part[u];
+    if (bi == nb - 1) {  // the row is complete
+      const float s = wave_sum(acc) + bias;
+      if (lane == 0) scores[row] = (s == 0.f) ? 0.f : s;  // -0 -> +0
+      acc = 0.f;
+    }
+  };
+  auto advance = [&](int64_t& row, int& bi) {
+    if (++bi == nb) {
+      bi = 0;
+      row += nwaves;
+    }
+  };
+
+  // Two register buffers used alternately, so that no copy has to wait for the loads in flight.
+  // Loads are issued unconditionally (past the end they re-read the last row and are discarded):
+  // a branch around them would make the compiler wait for every outstanding load at the merge.
+  auto load_clamped = [&](uint4 (&v)[PB], int64_t row, int bi) { load_batch(v, row < N ? row : N - 1, bi); };
+  uint4 buf_a[PB], buf_b[PB];
+  int64_t row_a = wave, row_b = wave;
+  int bi_a = 0, bi_b = 0;
+  advance(row_b, bi_b);  // b runs one batch ahead of a
+  load_clamped(buf_a, row_a, bi_a);
+  while (row_a < N) {
+    load_clamped(buf_b, row_b, bi_b);
+    __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the arithmetic
+    consume(buf_a, row_a, bi_a);
+    advance(row_a, bi_a);
+    advance(row_a, bi_a);  // a now names the batch after b
+    load_clamped(buf_a, row_a, bi_a);
+    __builtin_amdgcn_sched_barrier(0);
+    if (row_b < N) consume(buf_b, row_b, bi_b);
+    advance(row_b, bi_b);
+    advance(row_b, bi_b);
+  }
+}
+
+// Workgroups of `kernel` that fit on the device at once (all resident: the kernels stride over the
+// rows, so a grid larger than this would run in uneven rounds).
+template <typename K>
+int resident_blocks(K kernel, size_t lds) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 1024;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kScoreThreads, lds) != hipSuccess || per_cu <= 0)
+    per_cu = 2;
+  return cus * per_cu;
+}
+
+template <int DTYPE, int PB>
+void launch_pipelined(const void* hidden, const void* w, float bias, int64_t N, int d, int nb, int64_t row_stride,
+                      float* scores, unsigned blocks, size_t lds, hipStream_t s) {
+  if (nb == 1) {
+    const int cap = resident_blocks(score_pipelined_kernel<DTYPE, PB, true>, lds);
+    if (blocks > static_cast<unsigned>(cap)) blocks = cap;
+    hipLaunchKernelGGL((score_pipelined_kernel<DTYPE, PB, true>), dim3(blocks), dim3(kScoreThreads), lds, s, hidden, w,
+                       bias, N, d, nb, row_stride, scores);
+  } else {
+    const int cap = resident_blocks(score_pipelined_kernel<DTYPE, PB, false>, lds);
+    if (blocks > static_cast<unsigned>(cap)) blocks = cap;
+    hipLaunchKernelGGL((score_pipelined_kernel<DTYPE, PB, false>), dim3(blocks), dim3(kScoreThreads), lds, s, hidden, w,
+                       bias, N, d, nb, row_stride, scores);
+  }
+}
+
+template <int DTYPE>
+bool try_pipelined(const void* hidden, const void* w, float bias, int64_t N, int d, int64_t row_stride, float* scores,
+                   unsigned blocks, size_t lds, hipStream_t s) {
+  constexpr int kChunk = kWave * Elems<DTYPE>::kPerLoad;
+  if (d % kChunk != 0) return false;
+  const int chunks = d / kChunk;
+  const int nb = (chunks + kUnroll - 1) / kUnroll;
+  if (chunks % nb != 0) return false;
+  const int pb = chunks / nb;
+  switch (pb) {
+    case 1: launch_pipelined<DTYPE, 1>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 2: launch_pipelined<DTYPE, 2>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 3: launch_pipelined<DTYPE, 3>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 4: launch_pipelined<DTYPE, 4>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 5: launch_pipelined<DTYPE, 5>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 6: launch_pipelined<DTYPE, 6>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 7: launch_pipelined<DTYPE, 7>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 8: launch_pipelined<DTYPE, 8>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    default: return false;
+  }
+}
+
 }  // namespace
 }  // namespace dodo
 
@@ -114,16 +244,23 @@ extern "C" int dodo_score(const void* hidden, const void* w, float bias, int dty
 
   const int waves_per_block = kScoreThreads / kWave;
   int64_t blocks = (N + waves_per_block - 1) / waves_per_block;
-  const int64_t cap = 256 * 4;  // 4 workgroups per CU keep >100 KB of loads in flight per CU
+  const int64_t cap = 256 * 8;  // upper bound; each kernel trims it to what is resident at once
   if (blocks > cap) blocks = cap;
   const size_t lds = static_cast<size_t>(d) * sizeof(float);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // widths that split evenly into batches of wave-wide loads (4096, 5120, 8192, ...) take the pipelined kernel
+  const unsigned nblk = static_cast<unsigned>(blocks);
+  if (dtype == DODO_DTYPE_BF16 ? try_pipelined<DODO_DTYPE_BF16>(hidden, w, bias, N, d, row_stride, scores, nblk, lds, s)
+                               : try_pipelined<DODO_DTYPE_F32>(hidden, w, bias, N, d, row_stride, scores, nblk, lds, s))
+    return launch_status();
   if (dtype == DODO_DTYPE_BF16) {
-    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_BF16>, dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
-                       s, hidden, w, bias, N, d, row_stride, scores);
+    const int64_t fit = resident_blocks(score_kernel<DODO_DTYPE_BF16>, lds);
+    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_BF16>, dim3(static_cast<unsigned>(blocks < fit ? blocks : fit)),
+                       dim3(kScoreThreads), lds, s, hidden, w, bias, N, d, row_stride, scores);
   } else {
-    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_F32>, dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds, s,
-                       hidden, w, bias, N, d, row_stride, scores);
+    const int64_t fit = resident_blocks(score_kernel<DODO_DTYPE_F32>, lds);
+    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_F32>, dim3(static_cast<unsigned>(blocks < fit ? blocks : fit)),
+                       dim3(kScoreThreads), lds, s, hidden, w, bias, N, d, row_stride, scores);
   }
   return launch_status();
 }
