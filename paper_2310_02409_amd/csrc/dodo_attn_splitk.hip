@@ -13,7 +13,6 @@
 namespace dodo {
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kRowsInFlight = 4;  // rows a group loads before it starts the arithmetic
 constexpr float kNegInf = -__builtin_inff();
 
@@ -41,7 +40,7 @@ __device__ __forceinline__ float exp2_guard(float x) { return __builtin_amdgcn_e
 template <int DH>
 __host__ __device__ constexpr int partial_floats() { return DH + 2; }
 
-template <int DTYPE, int DH>
+template <int DTYPE, int DH, int kThreads>
 __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const void* __restrict__ Q, const void* __restrict__ Kn, const void* __restrict__ Vn,
     const void* __restrict__ Kl, const void* __restrict__ Vl, const int32_t* __restrict__ cu_q,
@@ -98,25 +97,16 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     bool valid[kRowsInFlight];
 #pragma unroll
     for (int u = 0; u < kRowsInFlight; ++u) {
-      const int j = j0 + u * kGroups + g;
-      valid[u] = j < r1;
-      if (valid[u]) {
-        const char *kp, *vp;
-        if (j < k_b) {
-          const int64_t off = (static_cast<int64_t>(k0 + j) * nug_tok_stride + nug_base) * kEs;
-          kp = static_cast<const char*>(Kn) + off;
-          vp = static_cast<const char*>(Vn) + off;
-        } else {
-          const int64_t off = (static_cast<int64_t>(l0 + j - k_b) * H_kv * DH + loc_base) * kEs;
-          kp = static_cast<const char*>(Kl) + off;
-          vp = static_cast<const char*>(Vl) + off;
-        }
-        kv[u] = load16_stream(kp);
-        vv[u] = load16_stream(vp);
-      } else {
-        kv[u] = make_uint4(0, 0, 0, 0);
-        vv[u] = make_uint4(0, 0, 0, 0);
-      }
+      // loads are unconditional (rows past the end re-read the last row of the range and are
+      // discarded): a branch around them would serialise the loads behind a full wait
+      const int jr = j0 + u * kGroups + g;
+      valid[u] = jr < r1;
+      const int j = valid[u] ? jr : r1 - 1;
+      const bool nug = j < k_b;
+      const int64_t off = nug ? (static_cast<int64_t>(k0 + j) * nug_tok_stride + nug_base) * kEs
+                              : (static_cast<int64_t>(l0 + j - k_b) * H_kv * DH + loc_base) * kEs;
+      kv[u] = load16_stream(static_cast<const char*>(nug ? Kn : Kl) + off);
+      vv[u] = load16_stream(static_cast<const char*>(nug ? Vn : Vl) + off);
     }
     float logit[kRowsInFlight];
     float mx = m;
@@ -227,10 +217,20 @@ __global__ __launch_bounds__(DH) void splitk_combine_kernel(const float* __restr
 template <int DTYPE, int DH>
 int launch_t(const AttnParams& p, int nsplit) {
   const int64_t rows = static_cast<int64_t>(p.B) * p.max_q * p.H;
-  hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH>), dim3(static_cast<unsigned>(rows * nsplit)), dim3(kThreads),
-                     0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.cu_local, p.H, p.H_kv, p.max_q,
-                     nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
-                     static_cast<float*>(p.ws));
+  // few workgroups (about one per CU) with many rows each: 16 wavefronts per workgroup keep enough
+  // loads in flight; otherwise 4 wavefronts and several workgroups per CU
+  const bool wide = rows * nsplit <= 512 && static_cast<int64_t>(p.max_k) + p.max_local >= 512;
+  if (wide) {
+    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024>), dim3(static_cast<unsigned>(rows * nsplit)),
+                       dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.cu_local, p.H,
+                       p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
+                       static_cast<float*>(p.ws));
+  } else {
+    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256>), dim3(static_cast<unsigned>(rows * nsplit)),
+                       dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.cu_local, p.H,
+                       p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
+                       static_cast<float*>(p.ws));
+  }
   int rc = launch_status();
   if (rc != DODO_OK || nsplit == 1) return rc;
   hipLaunchKernelGGL((splitk_combine_kernel<DTYPE, DH>), dim3(static_cast<unsigned>(rows)), dim3(DH), 0, p.stream,
@@ -243,8 +243,8 @@ int launch_t(const AttnParams& p, int nsplit) {
 int splitk_count(int32_t B, int32_t H, int32_t max_q, int32_t max_k, int32_t max_local) {
   const int64_t base = static_cast<int64_t>(B) * H * max_q;  // workgroups without splitting
   const int64_t rows = static_cast<int64_t>(max_k) + max_local;
-  const int64_t want = (1024 + base - 1) / base;           // aim at >= 4 workgroups per CU
-  const int64_t room = rows / 128 > 0 ? rows / 128 : 1;    // keep >= 128 rows per split
+  const int64_t want = (256 + base - 1) / base;            // aim at >= one (wide) workgroup per CU
+  const int64_t room = rows / 256 > 0 ? rows / 256 : 1;    // keep >= 256 rows per split
   int64_t n = want < room ? want : room;
   if (n < 1) n = 1;
   if (n > 64) n = 64;
