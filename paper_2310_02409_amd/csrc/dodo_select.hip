@@ -51,7 +51,21 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
 
   if (k_free > 0) {
     if (STAGED) {
-      for (int i = tid; i < n_free; i += THREADS) keys_lds[i] = order_key(s[i]);
+      // batches of 8 loads in flight per thread: one global-memory latency per batch, not per key
+      constexpr int kBatch = 8;
+      for (int i0 = tid; i0 < n_free; i0 += THREADS * kBatch) {
+        float v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int i = i0 + u * THREADS;
+          v[u] = s[i < n_free ? i : n_free - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int i = i0 + u * THREADS;
+          if (i < n_free) keys_lds[i] = order_key(v[u]);
+        }
+      }
       __syncthreads();
     }
     auto key_at = [&](int i) -> uint32_t { return STAGED ? keys_lds[i] : order_key(s[i]); };
@@ -62,24 +76,37 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
       const int shift = 24 - 8 * pass;
       for (int i = tid; i < 256; i += THREADS) hist[i] = 0;
       __syncthreads();
-      for (int i0 = wave * kWave; i0 < n_free; i0 += THREADS) {
-        const int i = i0 + lane;
-        const uint32_t key = (i < n_free) ? key_at(i) : 0u;
-        bool part = (i < n_free) && ((key & mask) == prefix);
-        const uint32_t digit = (key >> shift) & 255u;
+      // four independent 64-key chunks per iteration, so that their dependency chains overlap
+      constexpr int kChunks = 4;
+      for (int i0 = wave * kWave * kChunks; i0 < n_free; i0 += THREADS * kChunks) {
+        uint32_t digit[kChunks];
+        bool part[kChunks];
+#pragma unroll
+        for (int u = 0; u < kChunks; ++u) {
+          const int i = i0 + u * kWave + lane;
+          const uint32_t key = (i < n_free) ? key_at(i) : 0u;
+          part[u] = (i < n_free) && ((key & mask) == prefix);
+          digit[u] = (key >> shift) & 255u;
+        }
         // two rounds of wavefront aggregation absorb the hot bins (ties, shared exponents)
 #pragma unroll
         for (int round = 0; round < 2; ++round) {
-          const uint64_t act = __ballot(part);
-          if (act == 0) break;
-          const int leader = __ffsll(static_cast<long long>(act)) - 1;
-          const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
-          const bool same = part && digit == d0;
-          const uint64_t mm = __ballot(same);
-          if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
-          part = part && !same;
+#pragma unroll
+          for (int u = 0; u < kChunks; ++u) {
+            const uint64_t act = __ballot(part[u]);
+            if (act != 0) {
+              const int leader = __ffsll(static_cast<long long>(act)) - 1;
+              const uint32_t d0 = __builtin_amdgcn_readlane(digit[u], leader);
+              const bool same = part[u] && digit[u] == d0;
+              const uint64_t mm = __ballot(same);
+              if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
+              part[u] = part[u] && !same;
+            }
+          }
         }
-        if (part) atomicAdd(&hist[digit], 1u);
+#pragma unroll
+        for (int u = 0; u < kChunks; ++u)
+          if (part[u]) atomicAdd(&hist[digit[u]], 1u);
       }
       __syncthreads();
       if (wave == 0) {
@@ -198,6 +225,8 @@ extern "C" int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, 
   if (max_n <= 0 || max_k <= 0 || max_k > max_n) return DODO_ERR_INVALID_ARG;
   if (flags & ~DODO_TOPK_FORCE_LAST) return DODO_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (max_n <= 4096) return launch_select<256>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
+  // about four keys per thread: the kernel is latency-bound (few barriers matter more than lanes)
+  if (max_n <= 1024) return launch_select<256>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
+  if (max_n <= 2048) return launch_select<512>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
   return launch_select<1024>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
 }
