@@ -24,6 +24,8 @@
 // separated by workgroup barriers: while one group issues the 32 MFMAs of
 // "PV(t-1), then S(t)", the other does the softmax of its tile.  Small query
 // blocks (<= 128 rows) use a plain 4-wavefront kernel.
+#include <type_traits>
+
 #include "dodo_attn.h"
 
 namespace dodo {
@@ -145,41 +147,40 @@ __device__ __forceinline__ void softmax_tile(floatx16 (&acc)[2], int limit, int 
 // Softmax update with a fixed exponent offset per row (used by the two-group kernel): the offset
 // m_off is the row maximum of the first tile the row sees and is never moved afterwards, so the
 // output accumulators are not rescaled -- O = sum(p v) / sum(p) does not depend on the offset.
-// Needs scale_log2e > 0 (the maximum is taken on the raw logits).  Sets `bail` if a logit exceeds
-// the offset by more than 2^64, in which case the caller redoes the rows with softmax_tile.
+// Only P is produced here: the row sums come out of the matrix pipe (an extra V^T "channel" of
+// ones, see compute_pv), and an overflow of the fixed offset shows up as a non-finite row sum at
+// the end, in which case the caller redoes the rows with softmax_tile.  Needs scale_log2e > 0.
 template <bool MASK>
 __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int g, float scale_log2e, float& m_off,
-                                              float& l_run, bool& bail, bf16x8 (&pf)[4]) {
-  float tmax = kNegInf;
+                                              bf16x8 (&pf)[4]) {
+  if (MASK) {
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (MASK) {
+      for (int v = 0; v < 16; ++v) {
         const int key = 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
         acc[kb][v] = (key < limit) ? acc[kb][v] : kNegInf;
       }
-      tmax = fmaxf(tmax, acc[kb][v]);
-    }
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-  const float t2 = tmax * scale_log2e;
-  m_off = (m_off == kNegInf) ? t2 : m_off;  // rows without an offset have all-zero accumulators
-  bail = bail || (t2 > m_off + 64.f);
+  }
+  if (__any(m_off == kNegInf)) {  // some row of this wavefront has no offset yet (first visible tile)
+    float tmax = kNegInf;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, acc[kb][v]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    m_off = (m_off == kNegInf) ? tmax * scale_log2e : m_off;  // such rows have all-zero accumulators
+  }
   const float neg = (m_off == kNegInf) ? 0.f : -m_off;
-  float psum = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       floatx8 p;
 #pragma unroll
-      for (int v = 0; v < 8; ++v) {
-        p[v] = exp2_hw(fmaf(acc[kb][8 * half + v], scale_log2e, neg));
-        psum += p[v];
-      }
+      for (int v = 0; v < 8; ++v) p[v] = exp2_hw(fmaf(acc[kb][8 * half + v], scale_log2e, neg));
       pf[2 * kb + half] = __builtin_convertvector(p, bf16x8);  // hardware RNE pack
     }
-  l_run += psum;
 }
 
 // NW = 4: plain loop, two workgroups per CU.  NW = 8: two groups of four wavefronts in
@@ -272,6 +273,9 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     return ti;
   };
 
+  // the first tile is requested before anything else, so that it is not queued behind the Q rows
+  if (n_tiles > 0) issue_tile(0);
+
   // Q^T fragments: lane (j, g) holds Q[my_i][16*ds + 8*g .. +8) for ds = 0..7
   bf16x8 qf[kDH / 16];
   {
@@ -300,7 +304,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
 
   // Fragments are requested kAhead MFMAs before their use; the scheduling barriers keep the
   // compiler from hoisting every LDS read of a tile to the front (which would not fit in registers).
-  constexpr int kAhead = 4;
+  constexpr int kAhead = 6;
   // S^T = K Q^T of one tile: K fragment s = 2*ds + kb is row 32kb + j, 16 bytes at the swizzled piece 2ds + g
   auto compute_s = [&](int tile, floatx16 (&acc_s)[2]) {
     const char* kbuf = lds + (2 * (tile % kStages)) * kTileBytes + k_row_off;
@@ -322,8 +326,16 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // O^T += V^T P^T of one tile: V^T fragment s = 4*t + cb; slot 8g+4e+r of k-step t <-> key 16t + 8e + 4g + r
-  auto compute_pv = [&](int tile, const bf16x8 (&pf)[4]) {
+  // O^T += V^T P^T of one tile: V^T fragment s = 4*t + cb; slot 8g+4e+r of k-step t <-> key 16t + 8e + 4g + r.
+  // With ROW_SUMS the products are also multiplied with a 33rd block of V^T whose only non-zero
+  // row is all ones: its accumulator row 0 (lane j, g = 0, register 0) collects sum_k P[k][query].
+  floatx16 acc_l;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc_l[v] = 0.f;
+  const bf16x8 ones_frag = __builtin_bit_cast(
+      bf16x8, j == 0 ? make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u) : make_uint4(0, 0, 0, 0));
+  auto compute_pv = [&](int tile, const bf16x8 (&pf)[4], auto row_sums_tag) {
+    constexpr bool ROW_SUMS = decltype(row_sums_tag)::value;
     const char* vbuf = lds + (2 * (tile % kStages) + 1) * kTileBytes + v_in;
     auto read_vt = [&](int s) -> bf16x8 {
       const int t = s >> 2, cb = s & 3;
@@ -344,15 +356,17 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       const bf16x8 cur = vf[s % kAhead];
       if (s + kAhead < 16) vf[s % kAhead] = read_vt(s + kAhead);
       acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
+      if (ROW_SUMS && (s & 3) == 3)
+        acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s >> 2], acc_l, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
   bool bail = false;
   auto softmax_fast = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
     if (ti.need_mask) {
-      softmax_fixed<true>(acc_s, ti.limit, g, scale_log2e, m_run, l_run, bail, pf);
+      softmax_fixed<true>(acc_s, ti.limit, g, scale_log2e, m_run, pf);
     } else {
-      softmax_fixed<false>(acc_s, kBN, g, scale_log2e, m_run, l_run, bail, pf);
+      softmax_fixed<false>(acc_s, kBN, g, scale_log2e, m_run, pf);
     }
   };
   auto softmax = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
@@ -365,7 +379,6 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
 
   if constexpr (NW == 4) {
     // ---- plain loop: one barrier per tile, next tile in flight ----
-    if (n_tiles > 0) issue_tile(0);
     for (int tile = 0; tile < n_tiles; ++tile) {
       __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the tile has landed
       __syncthreads();                      // everyone's part has landed; the other stage is free
@@ -376,7 +389,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       bf16x8 pf[4];
       compute_s(tile, acc_s);
       softmax(ti, acc_s, pf);
-      compute_pv(tile, pf);
+      compute_pv(tile, pf, std::false_type{});
     }
   } else {
     // ---- two groups of four wavefronts, half a tile apart ----
@@ -392,15 +405,15 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     bf16x8 pf[4];
     if (n_tiles > 0) {
 #pragma unroll
-      for (int t = 0; t < kStages; ++t) issue_tile(t);
-      __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kLoadsPerTile));  // tile 0 landed (3 younger tiles in flight)
+      for (int t = 1; t < kStages; ++t) issue_tile(t);
+      __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kLoadsPerTile));  // tile 0 (and Q) landed, 3 younger tiles in flight
     }
     __syncthreads();
     // One iteration = phases 2t and 2t+1.  The two groups run separate copies of the loop (same
     // number of barriers) so that each copy is straight-line code for the compiler.
     auto mfma_phase = [&](int t) {  // PV(t-1), then S(t)
       __builtin_amdgcn_s_setprio(1);
-      if (t >= 1 && tile_info(t - 1).visible) compute_pv(t - 1, pf);
+      if (t >= 1 && tile_info(t - 1).visible) compute_pv(t - 1, pf, std::true_type{});
       if (t < n_tiles && tile_info(t).visible) compute_s(t, acc_s);
       __builtin_amdgcn_s_setprio(0);
     };
@@ -437,6 +450,10 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
           end_odd_phase(t);
         }
       }
+      // row sums: lane (j, g = 0) holds them in register 0 of the ones-block accumulator
+      l_run = (g == 0) ? acc_l[0] : 0.f;
+      const float l_row = l_run + __shfl_xor(l_run, 32, kWave);
+      bail = !(l_row - l_row == 0.f);  // +inf or NaN: some logit overflowed the row's fixed offset
     } else {
       bail = n_tiles > 0;
     }
@@ -458,7 +475,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
         if (ti.visible) {
           compute_s(tile, acc_s);
           softmax(ti, acc_s, pf);
-          compute_pv(tile, pf);
+          compute_pv(tile, pf, std::false_type{});
         }
         __syncthreads();
       }
@@ -467,24 +484,37 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   __builtin_amdgcn_s_waitcnt(0x0f70);  // drain the look-ahead loads before the wavefront ends
 
   // ---- epilogue: lane (j, g) holds channels 32cb + 8(v/4) + 4g + v%4 of query row my_i ----
+  // The 32 x 128 block of a wavefront goes through LDS (free by now) so that O is written with
+  // full 256-byte rows, 16 bytes per lane; 16-byte pieces are XOR-swizzled with the row to keep
+  // both the 8-byte writes and the 16-byte reads free of bank conflicts.
+  if (NW == 4) __syncthreads();  // every wavefront is done with the K/V stages
   const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-  if (row_ok) {
+  {
     const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
-    uint16_t* op = O + (static_cast<int64_t>(q0 + my_i) * H + h) * kDH;
+    char* obuf = lds + wave * (32 * kRowBytes);
 #pragma unroll
     for (int cb = 0; cb < kDH / 32; ++cb)
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        const int c = 32 * cb + 8 * vq + 4 * g;
+        const int piece = 4 * cb + vq;  // 16-byte piece of the row: channels 8*piece .. 8*piece+7; g picks the half
         uint2 out;
         out.x = pack2_bf16(acc_o[cb][4 * vq + 0] * inv, acc_o[cb][4 * vq + 1] * inv);
         out.y = pack2_bf16(acc_o[cb][4 * vq + 2] * inv, acc_o[cb][4 * vq + 3] * inv);
-        *reinterpret_cast<uint2*>(op + c) = out;
+        *reinterpret_cast<uint2*>(obuf + j * kRowBytes + ((piece ^ (j & 15)) << 4) + 8 * g) = out;
       }
-    if (lse != nullptr && g == 0) {
-      lse[static_cast<int64_t>(q0 + my_i) * H + h] =
-          (l_tot > 0.f) ? (m_run + __log2f(l_tot)) * 0.6931471805599453f : kNegInf;
+    __builtin_amdgcn_wave_barrier();
+    const int n_rows = min(32, q_b - w_i0);  // valid rows of this wavefront (may be <= 0)
+    uint16_t* obase = O + (static_cast<int64_t>(q0 + w_i0) * H + h) * kDH;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = 4 * it + (lane >> 4), piece = lane & 15;
+      const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * kRowBytes + ((piece ^ (row & 15)) << 4));
+      if (row < n_rows) *reinterpret_cast<uint4*>(obase + static_cast<int64_t>(row) * H * kDH + piece * 8) = val;
     }
+  }
+  if (row_ok && lse != nullptr && g == 0) {
+    lse[static_cast<int64_t>(q0 + my_i) * H + h] =
+        (l_tot > 0.f) ? (m_run + __log2f(l_tot)) * 0.6931471805599453f : kNegInf;
   }
 }
 
