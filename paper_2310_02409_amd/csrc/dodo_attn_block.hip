@@ -95,6 +95,15 @@ struct TileLoader {
       dma16(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
   }
+  // 64 rows in the K arrangement only (used for the query rows)
+  __device__ __forceinline__ void issue_rows(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const int row = row0 + 4 * u;
+      const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
+      dma16(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+    }
+  }
 };
 
 // Online-softmax update of one 32-row block for one 64-key tile.  acc holds the raw
@@ -207,9 +216,13 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // stage s: K at 2s, V at 2s+1 (tiles of 16 KiB)
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void*)lds));
 
-  // heaviest query blocks (largest causal extent) are scheduled first
-  const int bh = blockIdx.x % (B * H);
-  const int qblk = n_qblocks - 1 - blockIdx.x / (B * H);
+  // Workgroups are handed to the 8 XCDs round-robin, each XCD has an L2 of its own: the query
+  // blocks of one (sequence, head) go to one XCD back to back (heaviest first), so that they
+  // start together and share the K/V tiles in that L2.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int bh = (slot / n_qblocks) * 8 + xcd;
+  const int qblk = n_qblocks - 1 - slot % n_qblocks;
+  if (bh >= B * H) return;
   const int b = bh / H, h = bh % H;
   const int q0 = cu_q[b], q_b = cu_q[b + 1] - q0;
   const int i0 = qblk * kBM;
@@ -273,19 +286,43 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     return ti;
   };
 
-  // the first tile is requested before anything else, so that it is not queued behind the Q rows
-  if (n_tiles > 0) issue_tile(0);
-
-  // Q^T fragments: lane (j, g) holds Q[my_i][16*ds + 8*g .. +8) for ds = 0..7
+  // Prologue.  The first tile is requested before anything else; the workgroup's query rows follow,
+  // through LDS like a K tile (whole rows per request; a lane fetching its own row from global
+  // memory would touch 32 rows per instruction), into the stages that tiles 1.. (NW = 4) or 2..
+  // (NW = 8) use later.  Q^T fragments: lane (j, g) holds Q[my_i][16*ds + 8*g .. +8) for ds = 0..7.
+  // Rows past the end of the sequence re-read its last row; nothing of them is stored.
+  constexpr int kLoadsPerTile = TileLoader<NW>::kPerWave * 2;
+  constexpr int kQSlot0 = NW == 8 ? 4 : 2;  // first 16 KiB slot of the query rows
   bf16x8 qf[kDH / 16];
-  {
-    const uint16_t* qp = Q + (static_cast<int64_t>(q0 + (row_ok ? my_i : 0)) * H + h) * kDH + 8 * g;
+  if (n_tiles > 0) {
+    issue_tile(0);
 #pragma unroll
-    for (int ds = 0; ds < kDH / 16; ++ds) {
-      const shortx8 raw = *reinterpret_cast<const shortx8*>(qp + 16 * ds);
-      const shortx8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[ds] = __builtin_bit_cast(bf16x8, row_ok ? raw : zero);
+    for (int c = 0; c < kBM / kBN; ++c) {
+      const int r0 = i0 + kBN * c;
+      const int64_t base_row = q0 + min(r0, q_b - 1);
+      loader.issue_rows(Q + (base_row * H + h) * kDH, static_cast<uint32_t>(H) * kRowBytes, max(1, min(kBN, q_b - r0)),
+                        lds_base + (kQSlot0 + c) * kTileBytes);
     }
+    if (NW == 8) {
+      issue_tile(1);
+      __builtin_amdgcn_s_waitcnt(0x0f70 | kLoadsPerTile);  // tile 0 and Q landed, tile 1 in flight
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+    }
+    __syncthreads();
+    const char* qbuf = lds + kQSlot0 * kTileBytes + (wave * 32 + j) * kRowBytes;
+#pragma unroll
+    for (int ds = 0; ds < kDH / 16; ++ds)
+      qf[ds] = *reinterpret_cast<const bf16x8*>(qbuf + (((2 * ds + g) ^ (j & 15)) << 4));
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragments are in registers
+    if (NW == 8) {
+      __syncthreads();  // everyone has its fragments: the stages are free again
+      issue_tile(2);
+      issue_tile(3);
+    }
+  } else {
+#pragma unroll
+    for (int ds = 0; ds < kDH / 16; ++ds) qf[ds] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
   }
 
   floatx16 acc_o[kDH / 32];
@@ -379,6 +416,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
 
   if constexpr (NW == 4) {
     // ---- plain loop: one barrier per tile, next tile in flight ----
+    // (the first barrier also tells that every wavefront has taken its Q fragments out of stage 1)
     for (int tile = 0; tile < n_tiles; ++tile) {
       __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the tile has landed
       __syncthreads();                      // everyone's part has landed; the other stage is free
@@ -399,16 +437,9 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     // pipe while the other runs VALU work.  Tile t is read during phases 2t .. 2t+3 and sits in
     // stage t % 4; tile t+4 is requested at the start of phase 2t+4 and has to be visible at the
     // barrier that ends phase 2t+7.
-    constexpr int kLoadsPerTile = TileLoader<NW>::kPerWave * 2;
     const int grp = wave >> 2;
     floatx16 acc_s[2];
     bf16x8 pf[4];
-    if (n_tiles > 0) {
-#pragma unroll
-      for (int t = 1; t < kStages; ++t) issue_tile(t);
-      __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kLoadsPerTile));  // tile 0 (and Q) landed, 3 younger tiles in flight
-    }
-    __syncthreads();
     // One iteration = phases 2t and 2t+1.  The two groups run separate copies of the loop (same
     // number of barriers) so that each copy is straight-line code for the compiler.
     auto mfma_phase = [&](int t) {  // PV(t-1), then S(t)
@@ -522,7 +553,7 @@ template <int NW>
 int launch_nw(const AttnParams& p) {
   using Cfg = BlockCfg<NW>;
   const int n_qblocks = (p.max_q + Cfg::kBM - 1) / Cfg::kBM;
-  const int64_t grid = static_cast<int64_t>(p.B) * p.H * n_qblocks;
+  const int64_t grid = (static_cast<int64_t>(p.B) * p.H + 7) / 8 * 8 * n_qblocks;
   if (grid > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
   auto kern = block_attention_kernel<NW>;
   if (Cfg::kLdsBytes > 64 * 1024) {
@@ -542,7 +573,8 @@ int launch_nw(const AttnParams& p) {
 int launch_block_attention(const AttnParams& p) {
   if (p.dtype != DODO_DTYPE_BF16 || p.d_h != kDH) return DODO_ERR_UNSUPPORTED;
   // the K/V row offsets inside one tile are kept in 32 bits
-  if (p.nug_tok_stride * 2 * kBN > 0x7fffffffLL || static_cast<int64_t>(p.H_kv) * kDH * 2 * kBN > 0x7fffffffLL)
+  if (p.nug_tok_stride * 2 * kBN > 0x7fffffffLL || static_cast<int64_t>(p.H_kv) * kDH * 2 * kBN > 0x7fffffffLL ||
+      static_cast<int64_t>(p.H) * kDH * 2 * kBN > 0x7fffffffLL)
     return DODO_ERR_UNSUPPORTED;
   if (p.max_q > 128) return launch_nw<8>(p);
   return launch_nw<4>(p);
