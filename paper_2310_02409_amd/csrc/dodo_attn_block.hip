@@ -343,14 +343,14 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   // compiler from hoisting every LDS read of a tile to the front (which would not fit in registers).
   constexpr int kAhead = 6;
   // S^T = K Q^T of one tile: K fragment s = 2*ds + kb is row 32kb + j, 16 bytes at the swizzled piece 2ds + g
-  auto compute_s = [&](int tile, floatx16 (&acc_s)[2]) {
+  auto read_k = [&](int tile, int s) -> bf16x8 {
     const char* kbuf = lds + (2 * (tile % kStages)) * kTileBytes + k_row_off;
-    auto read_k = [&](int s) -> bf16x8 {
-      return *reinterpret_cast<const bf16x8*>(kbuf + (s & 1) * 32 * kRowBytes + ((((s >> 1) * 2 + g) ^ k_sw) << 4));
-    };
+    return *reinterpret_cast<const bf16x8*>(kbuf + (s & 1) * 32 * kRowBytes + ((((s >> 1) * 2 + g) ^ k_sw) << 4));
+  };
+  auto compute_s = [&](int tile, floatx16 (&acc_s)[2]) {
     bf16x8 kf[kAhead];
 #pragma unroll
-    for (int s = 0; s < kAhead; ++s) kf[s] = read_k(s);
+    for (int s = 0; s < kAhead; ++s) kf[s] = read_k(tile, s);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       const bf16x8 cur = kf[s % kAhead];
-      if (s + kAhead < 16) kf[s % kAhead] = read_k(s + kAhead);
+      if (s + kAhead < 16) kf[s % kAhead] = read_k(tile, s + kAhead);
       acc_s[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[s >> 1], acc_s[s & 1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -371,30 +371,27 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   for (int v = 0; v < 16; ++v) acc_l[v] = 0.f;
   const bf16x8 ones_frag = __builtin_bit_cast(
       bf16x8, j == 0 ? make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u) : make_uint4(0, 0, 0, 0));
-  auto compute_pv = [&](int tile, const bf16x8 (&pf)[4], auto row_sums_tag) {
-    constexpr bool ROW_SUMS = decltype(row_sums_tag)::value;
+  auto read_vt = [&](int tile, int s) -> bf16x8 {
     const char* vbuf = lds + (2 * (tile % kStages) + 1) * kTileBytes + v_in;
-    auto read_vt = [&](int s) -> bf16x8 {
-      const int t = s >> 2, cb = s & 3;
-      shortx4 a[2];
+    const int t = s >> 2, cb = s & 3;
+    shortx4 a[2];
 #pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int r = 16 * t + 8 * e + v_r;
-        const char* p = vbuf + r * kRowBytes + ((cb ^ (r & 3)) << 6);
-        a[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
-      }
-      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a[0], a[1], 0, 1, 2, 3, 4, 5, 6, 7));
-    };
+    for (int e = 0; e < 2; ++e) {
+      const int r = 16 * t + 8 * e + v_r;
+      const char* p = vbuf + r * kRowBytes + ((cb ^ (r & 3)) << 6);
+      a[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
+    }
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a[0], a[1], 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto compute_pv = [&](int tile, const bf16x8 (&pf)[4]) {
     bf16x8 vf[kAhead];
 #pragma unroll
-    for (int s = 0; s < kAhead; ++s) vf[s] = read_vt(s);
+    for (int s = 0; s < kAhead; ++s) vf[s] = read_vt(tile, s);
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       const bf16x8 cur = vf[s % kAhead];
-      if (s + kAhead < 16) vf[s % kAhead] = read_vt(s + kAhead);
+      if (s + kAhead < 16) vf[s % kAhead] = read_vt(tile, s + kAhead);
       acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
-      if (ROW_SUMS && (s & 3) == 3)
-        acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s >> 2], acc_l, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -427,7 +424,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       bf16x8 pf[4];
       compute_s(tile, acc_s);
       softmax(ti, acc_s, pf);
-      compute_pv(tile, pf, std::false_type{});
+      compute_pv(tile, pf);
     }
   } else {
     // ---- two groups of four wavefronts, half a tile apart ----
@@ -442,17 +439,44 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     bf16x8 pf[4];
     // One iteration = phases 2t and 2t+1.  The two groups run separate copies of the loop (same
     // number of barriers) so that each copy is straight-line code for the compiler.
-    auto mfma_phase = [&](int t) {  // PV(t-1), then S(t)
-      __builtin_amdgcn_s_setprio(1);
-      if (t >= 1 && tile_info(t - 1).visible) compute_pv(t - 1, pf, std::true_type{});
-      if (t < n_tiles && tile_info(t).visible) compute_s(t, acc_s);
-      __builtin_amdgcn_s_setprio(0);
-    };
-    auto valu_phase = [&](int t) {  // softmax of tile t
-      if (t >= 0 && t < n_tiles) {
-        const TileInfo ti = tile_info(t);
-        if (ti.visible) softmax_fast(ti, acc_s, pf);
+    // The MFMA phase is one software pipeline over 32 fragments (16 of V^T, then 16 of K), each
+    // requested kAhead MFMAs before its use into a ring of registers: slot i of the phase lives
+    // in ring[i % kAhead].  The first kAhead fragments of V^T are requested at the end of the
+    // softmax phase before, so no MFMA phase starts by waiting for LDS.  A tile that is invisible
+    // to a wavefront (above the causal diagonal) is followed by invisible tiles only.
+    bf16x8 ring[kAhead];
+    auto pv_steps = [&](int t, auto k_prefetch_tag) {  // PV(t-1); requests the first K fragments of tile t
+      constexpr bool K_PREFETCH = decltype(k_prefetch_tag)::value;
+#pragma unroll
+      for (int s = 0; s < 16; ++s) {
+        const bf16x8 cur = ring[s % kAhead];
+        if (s + kAhead < 16) {
+          ring[s % kAhead] = read_vt(t - 1, s + kAhead);
+        } else if (K_PREFETCH) {
+          ring[s % kAhead] = read_k(t, s + kAhead - 16);
+        }
+        acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
+        if ((s & 3) == 3) acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s >> 2], acc_l, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
+    };
+    auto s_steps = [&](int t) {  // S(t); its first kAhead fragments are in the ring already
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
+#pragma unroll
+      for (int s = 0; s < 16; ++s) {
+        const bf16x8 cur = ring[(16 + s) % kAhead];
+        if (s + kAhead < 16) ring[(16 + s) % kAhead] = read_k(t, s + kAhead);
+        acc_s[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[s >> 1], acc_s[s & 1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto valu_work = [&](int t) {  // softmax of tile t, then the first V^T fragments for PV(t)
+      softmax_fast(tile_info(t), acc_s, pf);
+#pragma unroll
+      for (int s = 0; s < kAhead; ++s) ring[s] = read_vt(t, s);
     };
     auto end_odd_phase = [&](int t) {  // ends phase 2t+1: tile t+1 must have landed
       // younger tiles in flight: 2 while the prologue's loads are pending, else 1
@@ -464,22 +488,53 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       __syncthreads();
     };
     if (n_tiles > 0 && scale_log2e > 0.f) {
+      // Tiles [0, n_vis) are visible to this wavefront.  Iteration t is one of four kinds, so that
+      // each loop body is straight-line code: 0 = S(0) only, 1 = PV(t-1) and S(t) (the steady
+      // state), 2 = PV(n_vis-1) only, 3 = nothing but the barriers the other wavefronts count on.
+      const int n_vis = n_nug_tiles + min(n_loc_tiles, (w_hi + kBN - 1) / kBN);
+      auto iteration = [&](int t, auto grp_tag, auto kind_tag) {
+        constexpr int GRP = decltype(grp_tag)::value, KIND = decltype(kind_tag)::value;
+        if (t >= 2) issue_tile(t + 2);
+        if (GRP == 1) {
+          if (KIND == 1 || KIND == 2) valu_work(t - 1);
+          __syncthreads();
+        }
+        __builtin_amdgcn_s_setprio(1);
+        if (KIND == 0) {
+#pragma unroll
+          for (int s = 0; s < kAhead; ++s) ring[(16 + s) % kAhead] = read_k(t, s);
+          s_steps(t);
+        } else if (KIND == 1) {
+          pv_steps(t, std::true_type{});
+          s_steps(t);
+        } else if (KIND == 2) {
+          pv_steps(t, std::false_type{});
+        }
+        __builtin_amdgcn_s_setprio(0);
+        if (GRP == 0) {
+          __syncthreads();
+          if (KIND == 0 || KIND == 1) valu_work(t);
+        }
+        end_odd_phase(t);
+      };
+      auto run = [&](auto grp_tag) {
+        using K0 = std::integral_constant<int, 0>;
+        using K1 = std::integral_constant<int, 1>;
+        using K2 = std::integral_constant<int, 2>;
+        using K3 = std::integral_constant<int, 3>;
+        int t = 0;
+        if (n_vis > 0) {
+          iteration(0, grp_tag, K0{});
+          for (t = 1; t < n_vis; ++t) iteration(t, grp_tag, K1{});
+          iteration(t, grp_tag, K2{});
+          ++t;
+        }
+        for (; t <= n_tiles; ++t) iteration(t, grp_tag, K3{});
+      };
       if (grp == 0) {
-        for (int t = 0; t <= n_tiles; ++t) {
-          if (t >= 2) issue_tile(t + 2);
-          mfma_phase(t);
-          __syncthreads();
-          valu_phase(t);
-          end_odd_phase(t);
-        }
+        run(std::integral_constant<int, 0>{});
       } else {
-        for (int t = 0; t <= n_tiles; ++t) {
-          if (t >= 2) issue_tile(t + 2);
-          valu_phase(t - 1);
-          __syncthreads();
-          mfma_phase(t);
-          end_odd_phase(t);
-        }
+        run(std::integral_constant<int, 1>{});
       }
       // row sums: lane (j, g = 0) holds them in register 0 of the ones-block accumulator
       l_run = (g == 0) ? acc_l[0] : 0.f;
@@ -506,7 +561,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
         if (ti.visible) {
           compute_s(tile, acc_s);
           softmax(ti, acc_s, pf);
-          compute_pv(tile, pf, std::false_type{});
+          compute_pv(tile, pf);
         }
         __syncthreads();
       }
