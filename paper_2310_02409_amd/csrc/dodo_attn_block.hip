@@ -95,7 +95,15 @@ struct TileLoader {
       dma16(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
   }
-  // 64 rows in the K arrangement only (used for the query rows)
+  // 64 rows in the V arrangement only
+  __device__ __forceinline__ void issue_rows_v(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const uint32_t roff = static_cast<uint32_t>(min(row0 + 4 * u, cnt - 1)) * stride_bytes;
+      dma16(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+    }
+  }
+  // 64 rows in the K arrangement only (also used for the query rows)
   __device__ __forceinline__ void issue_rows(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
@@ -156,12 +164,11 @@ __device__ __forceinline__ void softmax_tile(floatx16 (&acc)[2], int limit, int 
 // Softmax update with a fixed exponent offset per row (used by the two-group kernel): the offset
 // m_off is the row maximum of the first tile the row sees and is never moved afterwards, so the
 // output accumulators are not rescaled -- O = sum(p v) / sum(p) does not depend on the offset.
-// Only P is produced here: the row sums come out of the matrix pipe (an extra V^T "channel" of
-// ones, see compute_pv), and an overflow of the fixed offset shows up as a non-finite row sum at
-// the end, in which case the caller redoes the rows with softmax_tile.  Needs scale_log2e > 0.
+// An overflow of the fixed offset shows up as a non-finite row sum at the end, in which case the
+// caller redoes the rows with softmax_tile.  Needs scale_log2e > 0.
 template <bool MASK>
 __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int g, float scale_log2e, float& m_off,
-                                              bf16x8 (&pf)[4]) {
+                                              float& l_run, bf16x8 (&pf)[4]) {
   if (MASK) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -181,6 +188,7 @@ __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int
     m_off = (m_off == kNegInf) ? tmax * scale_log2e : m_off;  // such rows have all-zero accumulators
   }
   const float neg = (m_off == kNegInf) ? 0.f : -m_off;
+  float psum[2] = {0.f, 0.f};
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -188,8 +196,10 @@ __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int
       floatx8 p;
 #pragma unroll
       for (int v = 0; v < 8; ++v) p[v] = exp2_hw(fmaf(acc[kb][8 * half + v], scale_log2e, neg));
+      psum[kb] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
       pf[2 * kb + half] = __builtin_convertvector(p, bf16x8);  // hardware RNE pack
     }
+  l_run += psum[0] + psum[1];
 }
 
 // NW = 4: plain loop, two workgroups per CU.  NW = 8: two groups of four wavefronts in
@@ -364,13 +374,6 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     }
   };
   // O^T += V^T P^T of one tile: V^T fragment s = 4*t + cb; slot 8g+4e+r of k-step t <-> key 16t + 8e + 4g + r.
-  // With ROW_SUMS the products are also multiplied with a 33rd block of V^T whose only non-zero
-  // row is all ones: its accumulator row 0 (lane j, g = 0, register 0) collects sum_k P[k][query].
-  floatx16 acc_l;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc_l[v] = 0.f;
-  const bf16x8 ones_frag = __builtin_bit_cast(
-      bf16x8, j == 0 ? make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u) : make_uint4(0, 0, 0, 0));
   auto read_vt = [&](int tile, int s) -> bf16x8 {
     const char* vbuf = lds + (2 * (tile % kStages) + 1) * kTileBytes + v_in;
     const int t = s >> 2, cb = s & 3;
@@ -398,9 +401,9 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   bool bail = false;
   auto softmax_fast = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
     if (ti.need_mask) {
-      softmax_fixed<true>(acc_s, ti.limit, g, scale_log2e, m_run, pf);
+      softmax_fixed<true>(acc_s, ti.limit, g, scale_log2e, m_run, l_run, pf);
     } else {
-      softmax_fixed<false>(acc_s, kBN, g, scale_log2e, m_run, pf);
+      softmax_fixed<false>(acc_s, kBN, g, scale_log2e, m_run, l_run, pf);
     }
   };
   auto softmax = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
@@ -432,8 +435,8 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     // (32 MFMAs) and in odd phases 2t+1 the softmax of tile t; group 1 does the softmax of tile
     // t-1 in phase 2t and the MFMAs in phase 2t+1, so in every phase one group feeds the matrix
     // pipe while the other runs VALU work.  Tile t is read during phases 2t .. 2t+3 and sits in
-    // stage t % 4; tile t+4 is requested at the start of phase 2t+4 and has to be visible at the
-    // barrier that ends phase 2t+7.
+    // stage t % 4; tile t+4 is requested during phases 2t+4 (K) and 2t+5 (V) and has to be visible
+    // at the barrier that ends phase 2t+7.
     const int grp = wave >> 2;
     floatx16 acc_s[2];
     bf16x8 pf[4];
@@ -456,7 +459,6 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
           ring[s % kAhead] = read_k(t, s + kAhead - 16);
         }
         acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
-        if ((s & 3) == 3) acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s >> 2], acc_l, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
     };
@@ -478,8 +480,30 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
 #pragma unroll
       for (int s = 0; s < kAhead; ++s) ring[s] = read_vt(t, s);
     };
+    // In the loop a wavefront requests tiles where it would otherwise idle at a barrier, after its
+    // softmax: a request can take hundreds of cycles to issue when the memory pipeline is backed
+    // up.  The wavefronts of group 1 bring K of tile t+2 (during phase 2t), those of group 0 its V
+    // (during phase 2t+1), four requests per wavefront as in the prologue's split.
+    TileLoader<4> half_loader;
+    half_loader.init(wave & 3, lane);
+    auto issue_half = [&](int tile, auto v_tag) {
+      constexpr bool IS_V = decltype(v_tag)::value;
+      const int stage = tile % kStages;
+      const int tl = min(tile, n_tiles - 1);
+      const bool nug = tl < n_nug_tiles;
+      const int base = nug ? tl * kBN : (tl - n_nug_tiles) * kBN;
+      const int cnt = min(kBN, (nug ? k_b : wg_vis) - base);
+      const int64_t stride = nug ? nug_tok_stride : loc_stride;
+      if (IS_V) {
+        half_loader.issue_rows_v((nug ? nugV : locV) + base * stride, static_cast<uint32_t>(stride) * 2u, cnt,
+                                 lds_base + (2 * stage + 1) * kTileBytes);
+      } else {
+        half_loader.issue_rows((nug ? nugK : locK) + base * stride, static_cast<uint32_t>(stride) * 2u, cnt,
+                               lds_base + (2 * stage) * kTileBytes);
+      }
+    };
     auto end_odd_phase = [&](int t) {  // ends phase 2t+1: tile t+1 must have landed
-      // younger tiles in flight: 2 while the prologue's loads are pending, else 1
+      // younger requests of this wavefront in flight: two tiles' worth while the prologue's are pending, else one
       if (t == 0) {
         __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * kLoadsPerTile));
       } else {
@@ -494,8 +518,8 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       const int n_vis = n_nug_tiles + min(n_loc_tiles, (w_hi + kBN - 1) / kBN);
       auto iteration = [&](int t, auto grp_tag, auto kind_tag) {
         constexpr int GRP = decltype(grp_tag)::value, KIND = decltype(kind_tag)::value;
-        if (t >= 2) issue_tile(t + 2);
         if (GRP == 1) {
+          if (t >= 2) issue_half(t + 2, std::false_type{});
           if (KIND == 1 || KIND == 2) valu_work(t - 1);
           __syncthreads();
         }
@@ -513,6 +537,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
         __builtin_amdgcn_s_setprio(0);
         if (GRP == 0) {
           __syncthreads();
+          if (t >= 2) issue_half(t + 2, std::true_type{});
           if (KIND == 0 || KIND == 1) valu_work(t);
         }
         end_odd_phase(t);
@@ -536,8 +561,6 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       } else {
         run(std::integral_constant<int, 1>{});
       }
-      // row sums: lane (j, g = 0) holds them in register 0 of the ones-block accumulator
-      l_run = (g == 0) ? acc_l[0] : 0.f;
       const float l_row = l_run + __shfl_xor(l_run, 32, kWave);
       bail = !(l_row - l_row == 0.f);  // +inf or NaN: some logit overflowed the row's fixed offset
     } else {
