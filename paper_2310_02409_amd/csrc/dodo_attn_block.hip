@@ -166,7 +166,7 @@ __device__ __forceinline__ void softmax_tile(floatx16 (&acc)[2], int limit, int 
 // output accumulators are not rescaled -- O = sum(p v) / sum(p) does not depend on the offset.
 // An overflow of the fixed offset shows up as a non-finite row sum at the end, in which case the
 // caller redoes the rows with softmax_tile.  Needs scale_log2e > 0.
-template <bool MASK>
+template <bool MASK, bool SUMS>
 __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int g, float scale_log2e, float& m_off,
                                               float& l_run, bf16x8 (&pf)[4]) {
   if (MASK) {
@@ -196,10 +196,10 @@ __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int
       floatx8 p;
 #pragma unroll
       for (int v = 0; v < 8; ++v) p[v] = exp2_hw(fmaf(acc[kb][8 * half + v], scale_log2e, neg));
-      psum[kb] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+      if (SUMS) psum[kb] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
       pf[2 * kb + half] = __builtin_convertvector(p, bf16x8);  // hardware RNE pack
     }
-  l_run += psum[0] + psum[1];
+  if (SUMS) l_run += psum[0] + psum[1];
 }
 
 // NW = 4: plain loop, two workgroups per CU.  NW = 8: two groups of four wavefronts in
@@ -213,12 +213,13 @@ struct BlockCfg {
   static constexpr int kMinBlocks = NW == 4 ? 2 : 1;
 };
 
+// One query block (kBM rows) of one (sequence, head); called by the whole workgroup.
 template <int NW>
-__global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) void block_attention_kernel(
+__device__ __forceinline__ void attend_query_block(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
-    const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ cu_local, int B, int H, int H_kv,
-    int n_qblocks, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
+    const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ cu_local, int H, int H_kv, int bh, int qblk,
+    int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse) {
   using Cfg = BlockCfg<NW>;
   constexpr int kBM = Cfg::kBM;
@@ -226,13 +227,6 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // stage s: K at 2s, V at 2s+1 (tiles of 16 KiB)
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void*)lds));
 
-  // Workgroups are handed to the 8 XCDs round-robin, each XCD has an L2 of its own: the query
-  // blocks of one (sequence, head) go to one XCD back to back (heaviest first), so that they
-  // start together and share the K/V tiles in that L2.
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int bh = (slot / n_qblocks) * 8 + xcd;
-  const int qblk = n_qblocks - 1 - slot % n_qblocks;
-  if (bh >= B * H) return;
   const int b = bh / H, h = bh % H;
   const int q0 = cu_q[b], q_b = cu_q[b + 1] - q0;
   const int i0 = qblk * kBM;
@@ -374,6 +368,16 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     }
   };
   // O^T += V^T P^T of one tile: V^T fragment s = 4*t + cb; slot 8g+4e+r of k-step t <-> key 16t + 8e + 4g + r.
+  // The two-group kernel takes the row sums of P from the matrix pipe as well, which has slack
+  // there while the softmax phase has none: P^T is also multiplied with a 33rd block of V^T whose
+  // only non-zero row is all ones, so accumulator row 0 of that block (lane j, g = 0, register 0)
+  // collects sum_k P[k][query] -- of the bf16-rounded P, exactly what O^T is accumulated from.
+  constexpr bool kOnesBlock = true;
+  floatx16 acc_l;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc_l[v] = 0.f;
+  const bf16x8 ones_frag = __builtin_bit_cast(
+      bf16x8, j == 0 ? make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u) : make_uint4(0, 0, 0, 0));
   auto read_vt = [&](int tile, int s) -> bf16x8 {
     const char* vbuf = lds + (2 * (tile % kStages) + 1) * kTileBytes + v_in;
     const int t = s >> 2, cb = s & 3;
@@ -401,9 +405,9 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   bool bail = false;
   auto softmax_fast = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
     if (ti.need_mask) {
-      softmax_fixed<true>(acc_s, ti.limit, g, scale_log2e, m_run, l_run, pf);
+      softmax_fixed<true, !kOnesBlock>(acc_s, ti.limit, g, scale_log2e, m_run, l_run, pf);
     } else {
-      softmax_fixed<false>(acc_s, kBN, g, scale_log2e, m_run, l_run, pf);
+      softmax_fixed<false, !kOnesBlock>(acc_s, kBN, g, scale_log2e, m_run, l_run, pf);
     }
   };
   auto softmax = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
@@ -459,6 +463,8 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
           ring[s % kAhead] = read_k(t, s + kAhead - 16);
         }
         acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
+        if (kOnesBlock && (s & 3) == 3)
+          acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s >> 2], acc_l, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
     };
@@ -561,6 +567,7 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       } else {
         run(std::integral_constant<int, 1>{});
       }
+      if (kOnesBlock) l_run = (g == 0) ? acc_l[0] : 0.f;
       const float l_row = l_run + __shfl_xor(l_run, 32, kWave);
       bail = !(l_row - l_row == 0.f);  // +inf or NaN: some logit overflowed the row's fixed offset
     } else {
@@ -627,11 +634,49 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   }
 }
 
+// Workgroups are handed to the 8 XCDs round-robin, each XCD has an L2 of its own: the query blocks
+// of one (sequence, head) go to one XCD back to back (heaviest first), so that they start together
+// and share the K/V tiles in that L2.  With pair != 0 a workgroup takes two query blocks, one
+// after the other: block i from the end and block i from the start, so that under the causal mask
+// all workgroups carry the same load (new workgroups are handed out in order, and a compute unit
+// that finishes early is not refilled before the ones ahead of it in that order).
+template <int NW>
+__global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) void block_attention_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
+    const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
+    const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ cu_local, int B, int H, int H_kv,
+    int n_qblocks, int pair, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
+    uint16_t* __restrict__ O, float* __restrict__ lse) {
+  const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int bh = (slot / n_groups) * 8 + xcd;
+  const int first = n_qblocks - 1 - slot % n_groups;
+  if (bh >= B * H) return;
+  attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh, first, nug_tok_stride,
+                         nug_head_stride, scale_log2e, O, lse);
+  const int second = n_qblocks - 1 - first;
+  if (pair && second != first) {
+    __syncthreads();  // the first block's use of LDS is over
+    attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh, second, nug_tok_stride,
+                           nug_head_stride, scale_log2e, O, lse);
+  }
+}
+
+int compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+  return cus;
+}
+
 template <int NW>
 int launch_nw(const AttnParams& p) {
   using Cfg = BlockCfg<NW>;
   const int n_qblocks = (p.max_q + Cfg::kBM - 1) / Cfg::kBM;
-  const int64_t grid = (static_cast<int64_t>(p.B) * p.H + 7) / 8 * 8 * n_qblocks;
+  // pairs of query blocks per workgroup, if that still leaves a workgroup for every compute unit
+  const int64_t bh8 = (static_cast<int64_t>(p.B) * p.H + 7) / 8 * 8;
+  const int pair = (n_qblocks >= 2 && bh8 * ((n_qblocks + 1) / 2) >= compute_units()) ? 1 : 0;
+  const int64_t grid = bh8 * (pair ? (n_qblocks + 1) / 2 : n_qblocks);
   if (grid > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
   auto kern = block_attention_kernel<NW>;
   if (Cfg::kLdsBytes > 64 * 1024) {
@@ -641,7 +686,7 @@ int launch_nw(const AttnParams& p) {
   hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(Cfg::kThreads), Cfg::kLdsBytes, p.stream,
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
-                     static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.cu_local, p.B, p.H, p.H_kv, n_qblocks,
+                     static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.cu_local, p.B, p.H, p.H_kv, n_qblocks, pair,
                      p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, static_cast<uint16_t*>(p.O), p.lse);
   return launch_status();
 }
