@@ -650,8 +650,11 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int bh = (slot / n_groups) * 8 + xcd;
-  const int first = n_qblocks - 1 - slot % n_groups;
+  int first = n_qblocks - 1 - slot % n_groups;
   if (bh >= B * H) return;
+  // every other workgroup starts with its light block, so that the bursts of first loads (Q and
+  // the first tiles, which nothing hides) do not come from all compute units at the same time
+  if (pair && ((slot / n_groups) & 1)) first = n_qblocks - 1 - first;
   attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh, first, nug_tok_stride,
                          nug_head_stride, scale_log2e, O, lse);
   const int second = n_qblocks - 1 - first;
