@@ -4,7 +4,9 @@
 //   1. every fp32 score becomes an order-preserving uint32 key (NaN lowest,
 //      -0 == +0), staged in LDS when the sequence fits (<= 36864 tokens);
 //   2. a 4-pass, 8-bit MSB radix select finds the key T of the k-th best token
-//      and how many tokens equal to T are still needed;
+//      and how many tokens equal to T are still needed; after the first pass
+//      the tokens that share the chosen top byte are collected in a list (if
+//      they are few enough), so that the other three passes touch only those;
 //   3. a stable compaction emits, in ascending position order, every token
 //      with key > T and the first `need` tokens with key == T (lowest index
 //      wins ties).
@@ -15,7 +17,8 @@
 namespace dodo {
 namespace {
 
-constexpr int kStagedMaxKeys = 36 * 1024;  // 144 KiB of the 160 KiB LDS
+constexpr int kStagedMaxKeys = 34 * 1024;  // 136 KiB of the 160 KiB LDS
+constexpr int kCandCap = 8192;             // candidate list after the first pass: 16-bit positions, 16 KiB
 
 __device__ __forceinline__ uint32_t order_key(float s) {
   uint32_t u = __float_as_uint(s);
@@ -30,9 +33,9 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
                                                               const int32_t* __restrict__ cu_nuggets, uint32_t flags,
                                                               int max_n, int32_t* __restrict__ nugget_idx) {
   constexpr int kWaves = THREADS / kWave;
-  extern __shared__ uint32_t keys_lds[];
+  extern __shared__ uint32_t keys_lds[];  // max_n keys, then kCandCap 16-bit positions (STAGED only)
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_remaining;
+  __shared__ uint32_t s_prefix, s_remaining, s_cand;
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
 
   const int b = blockIdx.x;
@@ -71,21 +74,23 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
     auto key_at = [&](int i) -> uint32_t { return STAGED ? keys_lds[i] : order_key(s[i]); };
 
     // ---- radix select: key of the k_free-th best token ----
+    // One pass: histogram of the pass's digit over the items that still match the prefix, then the
+    // digit that holds the `remaining`-th largest.  An item is a token (first pass, or no list) or
+    // an entry of the candidate list.
     uint32_t prefix = 0, mask = 0, remaining = static_cast<uint32_t>(k_free);
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
+    auto radix_pass = [&](int shift, int n_items, auto item_key) {
       for (int i = tid; i < 256; i += THREADS) hist[i] = 0;
       __syncthreads();
-      // four independent 64-key chunks per iteration, so that their dependency chains overlap
+      // four independent 64-item chunks per iteration, so that their dependency chains overlap
       constexpr int kChunks = 4;
-      for (int i0 = wave * kWave * kChunks; i0 < n_free; i0 += THREADS * kChunks) {
+      for (int i0 = wave * kWave * kChunks; i0 < n_items; i0 += THREADS * kChunks) {
         uint32_t digit[kChunks];
         bool part[kChunks];
 #pragma unroll
         for (int u = 0; u < kChunks; ++u) {
           const int i = i0 + u * kWave + lane;
-          const uint32_t key = (i < n_free) ? key_at(i) : 0u;
-          part[u] = (i < n_free) && ((key & mask) == prefix);
+          const uint32_t key = (i < n_items) ? item_key(i) : 0u;
+          part[u] = (i < n_items) && ((key & mask) == prefix);
           digit[u] = (key >> shift) & 255u;
         }
         // two rounds of wavefront aggregation absorb the hot bins (ties, shared exponents)
@@ -123,26 +128,59 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
         if (lane == L) {
           uint32_t above = suf - (b0 + b1 + b2 + b3);  // candidates in bins above this lane's
           int dsel;
+          uint32_t in_bin;
           if (above + b3 >= remaining) {
             dsel = 3;
+            in_bin = b3;
           } else if (above + b3 + b2 >= remaining) {
             dsel = 2;
             above += b3;
+            in_bin = b2;
           } else if (above + b3 + b2 + b1 >= remaining) {
             dsel = 1;
             above += b3 + b2;
+            in_bin = b1;
           } else {
             dsel = 0;
             above += b3 + b2 + b1;
+            in_bin = b0;
           }
           s_prefix = prefix | (static_cast<uint32_t>(4 * L + dsel) << shift);
           s_remaining = remaining - above;
+          s_cand = in_bin;  // items that carry the chosen digit
         }
       }
       __syncthreads();
       prefix = s_prefix;
       remaining = s_remaining;
       mask |= 255u << shift;
+    };
+    radix_pass(24, n_free, key_at);
+    const int n_cand = static_cast<int>(s_cand);
+    if (STAGED && n_cand <= kCandCap) {
+      // positions of the tokens that share the chosen top byte, in any order
+      uint16_t* cand = reinterpret_cast<uint16_t*>(keys_lds + max_n);
+      __syncthreads();  // everyone has read s_cand
+      if (tid == 0) s_cand = 0;
+      __syncthreads();
+      for (int i0 = wave * kWave; i0 < n_free; i0 += THREADS) {
+        const int i = i0 + lane;
+        const bool is_c = i < n_free && (keys_lds[i] & mask) == prefix;
+        const uint64_t cm = __ballot(is_c);
+        if (cm != 0) {
+          const int leader = __ffsll(static_cast<long long>(cm)) - 1;
+          uint32_t base = 0;
+          if (lane == leader) base = atomicAdd(&s_cand, static_cast<uint32_t>(__popcll(cm)));
+          base = __builtin_amdgcn_readlane(base, leader);
+          const uint32_t at = base + popc_below_lane(cm);
+          if (is_c && at < static_cast<uint32_t>(kCandCap)) cand[at] = static_cast<uint16_t>(i);  // at < n_cand always
+        }
+      }
+      __syncthreads();
+      auto cand_key = [&](int c) -> uint32_t { return keys_lds[cand[c]]; };
+      for (int pass = 1; pass < 4; ++pass) radix_pass(24 - 8 * pass, n_cand, cand_key);
+    } else {
+      for (int pass = 1; pass < 4; ++pass) radix_pass(24 - 8 * pass, n_free, key_at);
     }
     const uint32_t T = prefix;                        // key of the k_free-th best token
     const int need_eq = static_cast<int>(remaining);  // tokens equal to T still to take, lowest index first
@@ -189,7 +227,7 @@ template <int THREADS>
 int launch_select(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int32_t max_n,
                   uint32_t flags, int32_t* nugget_idx, hipStream_t stream) {
   if (max_n <= kStagedMaxKeys) {
-    const size_t lds = static_cast<size_t>(max_n) * sizeof(uint32_t);
+    const size_t lds = static_cast<size_t>(max_n) * sizeof(uint32_t) + kCandCap * sizeof(uint16_t);
     auto kern = select_topk_kernel<THREADS, true>;
     if (lds > 48 * 1024) {
       DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
