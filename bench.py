@@ -121,7 +121,7 @@ def main():
     O = torch.empty_like(g["Q"])
     Od = torch.empty_like(g["Qd"])
     ws_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max_k, max(dec_local), D.BF16 if E == 2 else D.F32)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
     names = ["score", "select", "gather", "attn_block", "attn_decode"]
 

@@ -110,7 +110,12 @@ int dodo_gather_nuggets(const void* K, const void* V, int dtype, const int32_t* 
                         const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t H_kv,
                         int32_t d_h, int64_t token_stride, void* Kn, void* Vn, int layout, void* stream);
 
-/* Bytes of device workspace dodo_nugget_attention needs for these bounds (may be 0). */
+/* Bytes of device workspace dodo_nugget_attention needs for these bounds (may be 0).  The workspace holds
+ * the partial results of the split-K kernel and one flag word per partial.  Its contents need not be
+ * initialised, with one exception: no flag word may hold the library's "ready" value 0x600DD0D0 on
+ * entry -- the call clears the flags it used, so memory that was never a workspace of this library and
+ * memory that was one in a completed call both qualify; fill it with zeros after a call that was aborted.
+ * A workspace must not be shared by calls that may overlap in time. */
 size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, int32_t max_k,
                                              int32_t max_local, int dtype);
 
@@ -128,7 +133,7 @@ size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, 
  * host-side upper bounds on q_b / k_b / m_b.  Arithmetic: bf16 inputs are
  * multiplied on the matrix cores with fp32 accumulation when max_q >= 16
  * (query-block kernel); smaller max_q and all fp32 inputs use the bandwidth-
- * bound split-K kernel with a fixed-order combine.  Both are deterministic.
+ * bound split-K kernel, whose last split combines the partials in split order.  Both are deterministic.
  * Supported: d_h in {64, 128} for the split-K kernel, d_h = 128 for the block kernel.
  */
 int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,

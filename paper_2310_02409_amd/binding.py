@@ -188,7 +188,8 @@ def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, K
     code = _dtype_code(Q)
     need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, code)
     if need and ws is None:
-        ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+        # zero-filled: the split-K flags must not hold the library's "ready" value on entry
+        ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
     _check(lib.dodo_nugget_attention(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(Kl), _ptr(Vl), _ptr(cu_q), _ptr(cu_nuggets),
                                      _ptr(cu_local), B, H, H_kv, d_h, max_q, max_k, max_local, Kt,
                                      float(softmax_scale), code, layout, _ptr(O), _ptr(lse), _ptr(ws),

@@ -6,8 +6,13 @@
 // G = 256 / lanes-per-row groups; group g walks rows g, g+G, ... of the split,
 // keeping an independent online-softmax state (running max, sum, d_h partial
 // outputs spread over its lanes) in base 2.  Groups are merged through LDS in
-// group order; splits are merged by a second kernel in split order.  No float
-// atomics anywhere, so results are run-to-run deterministic.
+// group order.  With several splits every workgroup but the last of a row
+// writes its partial (m, s, o) to the workspace and raises a flag; the
+// workgroup of the last split waits for those flags (workgroups start in index
+// order and the last split has the highest indices, so what it waits for is
+// running or done; the wait is bounded anyway), merges the partials in split
+// order, writes the row and clears the flags.  No float atomics anywhere, so
+// results are run-to-run deterministic.
 #include "dodo_attn.h"
 
 namespace dodo {
@@ -36,9 +41,12 @@ struct Vec16<DODO_DTYPE_F32> {
 
 __device__ __forceinline__ float exp2_guard(float x) { return __builtin_amdgcn_exp2f(x); }  // exp2(-inf) = 0
 
-// partial record of one split in the workspace: [m, s, o[0..DH)] floats
+// partial record of one split in the workspace: [m, s, o[0..DH)] floats; after all records, one
+// 32-bit flag per record
 template <int DH>
 __host__ __device__ constexpr int partial_floats() { return DH + 2; }
+constexpr uint32_t kPartialReady = 0x600DD0D0u;  // flag value of a record that has been written
+constexpr int kMaxPolls = 1 << 17;               // bound of the combiner's wait (~0.1 s, never reached in a healthy run)
 
 template <int DTYPE, int DH, int kThreads>
 __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
@@ -56,8 +64,11 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   __shared__ float part_m[kGroups], part_s[kGroups];
   __shared__ float part_o[kGroups][DH];
 
-  int t = blockIdx.x;
-  const int split = t % nsplit; t /= nsplit;
+  // Split-major order: workgroups are started in index order, so the workgroups of the last split,
+  // which wait for the others of their row and combine, start after everything they wait for.
+  const int rows_total = gridDim.x / nsplit;
+  int t = blockIdx.x % rows_total;
+  const int split = blockIdx.x / rows_total;
   const int h = t % H; t /= H;
   const int i = t % max_q;
   const int b = t / max_q;
@@ -148,6 +159,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) part_o[g][sub * kEPL + e] = o[e];
   __syncthreads();
+  float Mg = kNegInf, Sg = 0.f, og = 0.f;  // this workgroup's merged partial (threads < DH: channel threadIdx.x)
   if (threadIdx.x < DH) {
     const int c = threadIdx.x;
     float M = kNegInf;
@@ -160,6 +172,9 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
         oc = fmaf(part_o[gg][c], wgt, oc);
       }
     }
+    Mg = M;
+    Sg = S;
+    og = oc;
     if (nsplit == 1) {
       const float val = (S > 0.f) ? oc / S : 0.f;
       if (DTYPE == DODO_DTYPE_F32) {
@@ -168,50 +183,91 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
         static_cast<uint16_t*>(O)[row_id * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
       }
       if (lse != nullptr && c == 0) lse[row_id] = (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
-    } else {
-      const int64_t slot = ((static_cast<int64_t>(b) * max_q + i) * H + h) * nsplit + split;
-      float* rec = ws + slot * partial_floats<DH>();
-      if (c == 0) {
-        rec[0] = M;
-        rec[1] = S;
-      }
-      rec[2 + c] = oc;
     }
   }
-}
+  if (nsplit == 1) return;
 
-template <int DTYPE, int DH>
-__global__ __launch_bounds__(DH) void splitk_combine_kernel(const float* __restrict__ ws,
-                                                            const int32_t* __restrict__ cu_q, int H, int max_q,
-                                                            int nsplit, void* __restrict__ O,
-                                                            float* __restrict__ lse) {
-  int t = blockIdx.x;
-  const int h = t % H; t /= H;
-  const int i = t % max_q;
-  const int b = t / max_q;
-  const int q0 = cu_q[b];
-  if (i >= cu_q[b + 1] - q0) return;
-  const int c = threadIdx.x;
-  const float* rec = ws + (((static_cast<int64_t>(b) * max_q + i) * H + h) * nsplit) * partial_floats<DH>();
-  float M = kNegInf;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, rec[s * partial_floats<DH>()]);
-  float S = 0.f, oc = 0.f;
-  if (M != kNegInf) {
-    for (int s = 0; s < nsplit; ++s) {
-      const float* r = rec + s * partial_floats<DH>();
-      const float wgt = exp2_guard(r[0] - M);
-      S = fmaf(r[1], wgt, S);
-      oc = fmaf(r[2 + c], wgt, oc);
+  // ---- several splits: the last one combines, in split order ----
+  const int64_t slot0 = ((static_cast<int64_t>(b) * max_q + i) * H + h) * nsplit;
+  uint32_t* flags = reinterpret_cast<uint32_t*>(ws + static_cast<int64_t>(gridDim.x) * partial_floats<DH>());
+  __shared__ int all_there;
+  if (split + 1 < nsplit) {
+    // Records and flags are written and read with device-scope atomic accesses (plain stores and
+    // loads that go to the level where all XCDs agree), so no cache has to be written back or
+    // invalidated as a whole; the wait makes sure that the record has arrived there before the
+    // flag is sent after it.
+    if (threadIdx.x < DH) {
+      float* rec = ws + (slot0 + split) * partial_floats<DH>();
+      if (threadIdx.x == 0) {
+        __hip_atomic_store(rec + 0, Mg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(rec + 1, Sg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      __hip_atomic_store(rec + 2 + threadIdx.x, og, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this thread's stores are acknowledged
     }
+    __syncthreads();
+    if (threadIdx.x == 0)
+      __hip_atomic_store(flags + slot0 + split, kPartialReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
   }
-  const int64_t row_id = static_cast<int64_t>(q0 + i) * H + h;
-  const float val = (S > 0.f) ? oc / S : 0.f;
-  if (DTYPE == DODO_DTYPE_F32) {
-    static_cast<float*>(O)[row_id * DH + c] = val;
-  } else {
-    static_cast<uint16_t*>(O)[row_id * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
+  if (threadIdx.x == 0) {
+    int ok = 1;
+    for (int s2 = 0; ok && s2 + 1 < nsplit; ++s2) {
+      int polls = 0;
+      while (__hip_atomic_load(flags + slot0 + s2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != kPartialReady) {
+        if (++polls > kMaxPolls) {
+          ok = 0;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(16);
+      }
+    }
+    all_there = ok;
   }
-  if (lse != nullptr && c == 0) lse[row_id] = (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
+  __syncthreads();
+  if (threadIdx.x < DH) {
+    const int c = threadIdx.x;
+    const float* rec0 = ws + slot0 * partial_floats<DH>();
+    // splits in batches of 8 with all loads of a batch issued before the first use; the own
+    // partial (the last split) comes last, so the order of the merge is the split order
+    constexpr int kBatch = 8;
+    float M = kNegInf, S = 0.f, oc = 0.f;
+    auto merge = [&](float m1, float s1, float o1) {
+      const float mb = fmaxf(M, m1);
+      if (mb != kNegInf) {
+        const float keep = exp2_guard(M - mb), wgt = exp2_guard(m1 - mb);
+        S = fmaf(s1, wgt, S * keep);
+        oc = fmaf(o1, wgt, oc * keep);
+        M = mb;
+      }
+    };
+    for (int s0 = 0; s0 + 1 < nsplit; s0 += kBatch) {
+      float mm[kBatch], sv[kBatch], ov[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const float* r = rec0 + min(s0 + u, nsplit - 2) * partial_floats<DH>();
+        mm[u] = __hip_atomic_load(r + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sv[u] = __hip_atomic_load(r + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ov[u] = __hip_atomic_load(r + 2 + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        if (s0 + u + 1 < nsplit) merge(mm[u], sv[u], ov[u]);
+    }
+    merge(Mg, Sg, og);
+    const bool ok = all_there != 0;
+    const float nan = __builtin_nanf("");
+    const float val = !ok ? nan : (S > 0.f) ? oc / S : 0.f;  // a partial never arrived: fail loudly
+    if (DTYPE == DODO_DTYPE_F32) {
+      static_cast<float*>(O)[row_id * DH + c] = val;
+    } else {
+      static_cast<uint16_t*>(O)[row_id * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
+    }
+    if (lse != nullptr && c == 0)
+      lse[row_id] = !ok ? nan : (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
+    // the flags are left cleared for the next call on this workspace
+    if (c + 1 < nsplit) __hip_atomic_store(flags + slot0 + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 template <int DTYPE, int DH>
@@ -231,10 +287,6 @@ int launch_t(const AttnParams& p, int nsplit) {
                        p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws));
   }
-  int rc = launch_status();
-  if (rc != DODO_OK || nsplit == 1) return rc;
-  hipLaunchKernelGGL((splitk_combine_kernel<DTYPE, DH>), dim3(static_cast<unsigned>(rows)), dim3(DH), 0, p.stream,
-                     static_cast<const float*>(p.ws), p.cu_q, p.H, p.max_q, nsplit, p.O, p.lse);
   return launch_status();
 }
 
@@ -253,7 +305,7 @@ int splitk_count(int32_t B, int32_t H, int32_t max_q, int32_t max_k, int32_t max
 
 size_t splitk_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, int nsplit) {
   if (nsplit <= 1) return 0;
-  return static_cast<size_t>(B) * max_q * H * nsplit * (d_h + 2) * sizeof(float);
+  return static_cast<size_t>(B) * max_q * H * nsplit * (d_h + 3) * sizeof(float);  // records, then one flag each
 }
 
 int launch_splitk_attention(const AttnParams& p) {

@@ -45,10 +45,29 @@ def test_decode_ragged(D, dtype, H, H_kv, d_h):
 
 
 def test_decode_split_k_paths(D):
-    # few (sequence, head) pairs and many rows: the split count goes above 1 and the combine kernel runs
+    # few (sequence, head) pairs and many rows: the split count goes above 1 and the last split combines
     assert D.dodo_nugget_attention_workspace_bytes(2, 2, 128, 1, 3277, 1089, D.BF16) > 0
     _full_check(D, 401, [1, 1], [3277, 1500], [1089, 1025], 2, 2, 128, torch.bfloat16)
     _full_check(D, 402, [1], [2000], [300], 2, 1, 64, torch.float32)
+
+
+def test_split_k_workspace_is_reusable_and_needs_no_initialisation(D):
+    # the last split of a row waits for the flags of the others and clears them: the same workspace
+    # serves call after call, and bytes that are not the "ready" value are as good as zeros
+    q_lens, k_lens, m_lens, H, d_h = [1, 1], [3000, 1234], [700, 1025], 2, 128
+    need = D.dodo_nugget_attention_workspace_bytes(2, H, d_h, 1, max(k_lens), max(m_lens), D.BF16)
+    assert need > 0
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=dev())
+    scale = default_scale(d_h)
+    for seed in (410, 411, 412):
+        host, devt = make_attention_case(seed, q_lens, k_lens, m_lens, H, H, d_h, torch.bfloat16, dev())
+        O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
+                                          host["cu_nuggets"], host["cu_local"], scale)
+        O, lse = D.dodo_nugget_attention(devt["Q"], devt["Kn"], devt["Vn"], devt["Kl"], devt["Vl"], devt["cu_q"],
+                                         devt["cu_nuggets"], devt["cu_local"], 1, max(k_lens), max(m_lens), scale, 0,
+                                         want_lse=True, ws=ws)
+        check_attention(O, O_ref, torch.bfloat16)
+        check_lse(lse, lse_ref, torch.bfloat16)
 
 
 def test_tiny_fp32_config_block_through_split_k_kernel(D):
