@@ -637,9 +637,9 @@ __device__ __forceinline__ void attend_query_block(
 // Workgroups are handed to the 8 XCDs round-robin, each XCD has an L2 of its own: the query blocks
 // of one (sequence, head) go to one XCD back to back (heaviest first), so that they start together
 // and share the K/V tiles in that L2.  With pair != 0 a workgroup takes two query blocks, one
-// after the other: block i from the end and block i from the start, so that under the causal mask
-// all workgroups carry the same load (new workgroups are handed out in order, and a compute unit
-// that finishes early is not refilled before the ones ahead of it in that order).
+// after the other: a block i from the end and a block i from the start, so that under the causal
+// mask all workgroups carry the same load (new workgroups are handed out in order, and a compute
+// unit that finishes early is not refilled before the ones ahead of it in that order).
 template <int NW>
 __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) void block_attention_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
@@ -649,18 +649,32 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     uint16_t* __restrict__ O, float* __restrict__ lse) {
   const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int bh = (slot / n_groups) * 8 + xcd;
-  int first = n_qblocks - 1 - slot % n_groups;
+  const int j = slot / n_groups;
+  const int bh = j * 8 + xcd;
+  const int heavy = n_qblocks - 1 - slot % n_groups, light = n_qblocks - 1 - heavy;
   if (bh >= B * H) return;
-  // every other workgroup starts with its light block, so that the bursts of first loads (Q and
-  // the first tiles, which nothing hides) do not come from all compute units at the same time
-  if (pair && ((slot / n_groups) & 1)) first = n_qblocks - 1 - first;
-  attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh, first, nug_tok_stride,
+  // Two neighbouring workgroups of an XCD (j even and odd) share two (sequence, head) pairs
+  // crosswise: one takes the heavy block of the first pair and then the light block of the second,
+  // the other the light block of the first and then the heavy block of the second.  Both carry the
+  // same load, the two blocks that read the same K/V run at the same time and share it in L2, and
+  // the bursts of first loads come from half of the compute units at a time.
+  const int bh_other = (j ^ 1) * 8 + xcd;
+  const bool cross = pair && light != heavy && bh_other < B * H;
+  int bh1 = bh, q1 = heavy, bh2 = bh, q2 = (pair && light != heavy) ? light : -1;
+  if (cross) {
+    if (j & 1) {
+      bh1 = bh_other;
+      q1 = light;
+      q2 = heavy;
+    } else {
+      bh2 = bh_other;
+    }
+  }
+  attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh1, q1, nug_tok_stride,
                          nug_head_stride, scale_log2e, O, lse);
-  const int second = n_qblocks - 1 - first;
-  if (pair && second != first) {
+  if (q2 >= 0) {
     __syncthreads();  // the first block's use of LDS is over
-    attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh, second, nug_tok_stride,
+    attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, bh2, q2, nug_tok_stride,
                            nug_head_stride, scale_log2e, O, lse);
   }
 }
