@@ -45,6 +45,9 @@ def _load():
         lib.oracle_nugget_count.restype = ctypes.c_int64
         lib.oracle_nugget_count.argtypes = [ctypes.c_int64] * 3
         lib.oracle_select_topk.restype = ctypes.c_int
+        lib.oracle_threshold_from_sample.restype = ctypes.c_float
+        lib.oracle_stream_append.restype = ctypes.c_int32
+        lib.oracle_select_threshold_indices.restype = None
         for name in ("oracle_score", "oracle_select_threshold", "oracle_gather", "oracle_attention",
                      "oracle_attention_rows"):
             getattr(lib, name).restype = None
@@ -114,6 +117,40 @@ def select_threshold(scores: np.ndarray, cu_seqlens: np.ndarray, lam: float):
     _load().oracle_select_threshold(_p(scores), _p(cu_seqlens), ctypes.c_int32(B), ctypes.c_float(lam), _p(alpha),
                                     _p(counts))
     return alpha, counts
+
+
+def threshold_from_sample(sample: np.ndarray, num: int, den: int) -> float:
+    """Threshold calibration (Sec. 2.4): the (k+1)-th highest of the sampled scores, k = nugget_count(n)."""
+    sample = _c(sample, np.float32)
+    return float(_load().oracle_threshold_from_sample(_p(sample), ctypes.c_int64(len(sample)), ctypes.c_int64(num),
+                                                      ctypes.c_int64(den)))
+
+
+def select_threshold_indices(scores: np.ndarray, cu_seqlens: np.ndarray, lam: float):
+    """Threshold selection (Eq. 8) as packed index lists: (counts [B], cu_nuggets [B+1], nugget_idx [sum counts])."""
+    scores, cu_seqlens = _c(scores, np.float32), _c(cu_seqlens, np.int32)
+    B = len(cu_seqlens) - 1
+    counts = np.zeros(B, dtype=np.int32)
+    cu_nuggets = np.zeros(B + 1, dtype=np.int32)
+    idx = np.zeros(len(scores), dtype=np.int32)
+    _load().oracle_select_threshold_indices(_p(scores), _p(cu_seqlens), ctypes.c_int32(B), ctypes.c_float(lam),
+                                            _p(counts), _p(cu_nuggets), _p(idx))
+    return counts, cu_nuggets, idx[: int(cu_nuggets[-1])].copy()
+
+
+def stream_append(scores: np.ndarray, lam: float, K_rows: np.ndarray, V_rows: np.ndarray, counts: np.ndarray,
+                  Kn: np.ndarray, Vn: np.ndarray) -> int:
+    """One step of the autoregressive mode: append the rows [B, H_kv, d_h] whose score exceeds lam to the caches
+    [B, cap, H_kv, d_h] in place, update counts in place; returns how many tokens a full cache dropped."""
+    scores = _c(scores, np.float32)
+    K_rows, V_rows = _c(K_rows), _c(V_rows)
+    assert Kn.flags.c_contiguous and Vn.flags.c_contiguous and counts.dtype == np.int32 and counts.flags.c_contiguous
+    B, H_kv, d_h = K_rows.shape
+    cap = Kn.shape[1]
+    return int(_load().oracle_stream_append(_p(scores), ctypes.c_float(lam), _p(K_rows), _p(V_rows), _dtype_code(K_rows),
+                                            ctypes.c_int32(B), ctypes.c_int32(H_kv), ctypes.c_int32(d_h),
+                                            ctypes.c_int64(H_kv * d_h), ctypes.c_int32(cap), _p(counts), _p(Kn),
+                                            _p(Vn)))
 
 
 def gather(K: np.ndarray, V: np.ndarray, nugget_idx: np.ndarray, cu_seqlens: np.ndarray, cu_nuggets: np.ndarray,

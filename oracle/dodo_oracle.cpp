@@ -182,6 +182,61 @@ void oracle_select_threshold(const float* scores, const int32_t* cu_seqlens, int
   }
 }
 
+// Threshold calibration (Sec. 2.4: the threshold is estimated by running the scorer on sampled
+// tokens so that about t/r of t tokens are kept): with k = nugget count of the n sampled scores,
+// Lambda is the (k+1)-th highest score of the sample, so that exactly k of them exceed it when there
+// are no ties.  Score order is that of the selection rule (NaN lowest).  If k >= n, or the
+// (k+1)-th highest is NaN, everything that can be kept is kept: Lambda = -inf.
+float oracle_threshold_from_sample(const float* sample, int64_t n, int64_t num, int64_t den) {
+  const int64_t k = oracle_nugget_count(n, num, den);
+  if (k >= n) return -std::numeric_limits<float>::infinity();
+  std::vector<float> v(sample, sample + n);
+  std::stable_sort(v.begin(), v.end(), [](float a, float b) { return higher(a, b); });
+  const float lam = v[k];
+  if (std::isnan(lam)) return -std::numeric_limits<float>::infinity();
+  return lam == 0.0f ? 0.0f : lam;  // canonical zero
+}
+
+// Threshold selection as index lists: the kept tokens of every sequence in ascending position
+// order, packed (sequence b at cu_nuggets_out[b] ...), with the counts and their running sum.
+void oracle_select_threshold_indices(const float* scores, const int32_t* cu_seqlens, int32_t B, float lambda,
+                                     int32_t* counts, int32_t* cu_nuggets_out, int32_t* nugget_idx) {
+  cu_nuggets_out[0] = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    int32_t c = 0;
+    for (int64_t t = cu_seqlens[b]; t < cu_seqlens[b + 1]; ++t)
+      if (scores[t] > lambda) nugget_idx[cu_nuggets_out[b] + c++] = static_cast<int32_t>(t - cu_seqlens[b]);
+    counts[b] = c;
+    cu_nuggets_out[b + 1] = cu_nuggets_out[b] + c;
+  }
+}
+
+// One step of the autoregressive mode (Sec. 2.4 with the mixed resolution of Eq. 9): in every
+// sequence one token leaves the window of uncompressed tokens; if its score exceeds Lambda its K and
+// V rows are appended to that sequence's nugget cache (capacity `cap` rows per sequence, caches
+// token-major [B, cap, H_kv, d_h]); a full cache drops the token and reports it through the return
+// value (number of dropped tokens).  counts[b] is updated.
+int32_t oracle_stream_append(const float* scores, float lambda, const void* K_rows, const void* V_rows, int dtype,
+                             int32_t B, int32_t H_kv, int32_t d_h, int64_t row_stride, int32_t cap, int32_t* counts,
+                             void* Kn, void* Vn) {
+  const size_t es = elem_size(dtype);
+  const size_t row_bytes = static_cast<size_t>(H_kv) * d_h * es;
+  int32_t dropped = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    if (!(scores[b] > lambda)) continue;
+    if (counts[b] >= cap) {
+      ++dropped;
+      continue;
+    }
+    const size_t dst = (static_cast<size_t>(b) * cap + counts[b]) * row_bytes;
+    const size_t src = static_cast<size_t>(b) * row_stride * es;
+    std::memcpy(static_cast<char*>(Kn) + dst, static_cast<const char*>(K_rows) + src, row_bytes);
+    std::memcpy(static_cast<char*>(Vn) + dst, static_cast<const char*>(V_rows) + src, row_bytes);
+    ++counts[b];
+  }
+  return dropped;
+}
+
 // Sub-selection (Eq. 5): nuggets are the chosen tokens' own K and V rows,
 // copied bit for bit into the compact cache.
 void oracle_gather(const void* K, const void* V, int dtype, const int32_t* nugget_idx, const int32_t* cu_seqlens,
