@@ -183,6 +183,49 @@ def main():
         kernels["note"] = "instrumented pre-pass with events between all calls"
         dom = max(names, key=lambda n: kernels[n]["avg_us"])
 
+        # The autoregressive mode's selection (threshold rule), outside the step and its timing: Lambda from
+        # the step's own scores as the sample, threshold selection of the whole batch, and one decode step
+        # (append the leaving token of every sequence, then attend over the caches with room to grow).
+        cap = max_k + 64
+        lam = D.dodo_threshold_from_sample(scores, wl.keep_num, wl.keep_den)
+        Kc = torch.zeros((B, cap, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
+        Vc = torch.zeros_like(Kc)
+        counts = torch.zeros(B, dtype=torch.int32, device=dev)
+        Kc[:, :max_k] = Kn.view(B, -1, wl.H_kv, wl.d_h)[:, :max_k] if len(set(ks)) == 1 else 0
+        Vc[:, :max_k] = Vn.view(B, -1, wl.H_kv, wl.d_h)[:, :max_k] if len(set(ks)) == 1 else 0
+        counts.fill_(max_k if len(set(ks)) == 1 else 0)
+        starts = (torch.arange(B, dtype=torch.int32, device=dev) * cap).contiguous()
+        leave_s = scores[: B].clone()
+        leave_K, leave_V = g["K"][: B].contiguous(), g["V"][: B].contiguous()
+        ar_calls = {
+            "threshold_from_sample": lambda: D.dodo_threshold_from_sample(scores, wl.keep_num, wl.keep_den, out=lam),
+            "select_threshold": lambda: D.dodo_select_threshold(scores, g["cu_seqlens"], lam),
+            "stream_append": lambda: (counts.fill_(max_k if len(set(ks)) == 1 else 0),
+                                      D.dodo_stream_append(leave_s, lam, leave_K, leave_V, counts, Kc, Vc)),
+            "attn_decode_cached": lambda: D.dodo_nugget_attention_cached(
+                g["Qd"], Kc.view(B * cap, wl.H_kv, wl.d_h), Vc.view(B * cap, wl.H_kv, wl.d_h), g["Kld"], g["Vld"], cu_qd,
+                starts, counts, cu_ld, 1, cap, max(dec_local), scale, D.TOKEN_MAJOR, Od, ws=ws_c),
+        }
+        ws_c_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, cap, max(dec_local),
+                                                             D.BF16 if E == 2 else D.F32)
+        ws_c = torch.zeros(max(ws_c_bytes, 16), dtype=torch.uint8, device=dev)
+        ar = {}
+        for name, fn in ar_calls.items():
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+            for a, b in evs:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            ar[name] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2)}
+        ar["note"] = ("threshold rule of the autoregressive mode, timed apart from the step: sample = the step's "
+                      f"{wl.N} scores; stream_append includes a fill of the {B} counters; caches of {cap} rows per sequence")
+        kernels["autoregressive_mode"] = ar
+
     # Timed region: exactly `steps` steps; the only events inside it bracket the dominant kernel.
     dom_idx = names.index(dom) if dom is not None else -1
 

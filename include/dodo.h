@@ -103,7 +103,8 @@ int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32
  * nugget cache, bit for bit.  K, V are [N, H_kv, d_h] with `token_stride`
  * elements between tokens (>= H_kv*d_h); nugget_idx holds sequence-local
  * indices as written by dodo_select_topk; Kt = cu_nuggets[B] is the total
- * nugget count (host value).  Output Kn, Vn: [Kt, H_kv, d_h] (token-major) or
+ * nugget count (host value), or an upper bound of it (rows from cu_nuggets[B] on are
+ * left untouched).  Output Kn, Vn: [Kt, H_kv, d_h] (token-major) or
  * [H_kv, Kt, d_h] (head-major), contiguous.  Kt == 0 is a no-op.
  */
 int dodo_gather_nuggets(const void* K, const void* V, int dtype, const int32_t* nugget_idx,
@@ -141,6 +142,57 @@ int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const v
                           int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local,
                           int64_t Kt, float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws,
                           size_t ws_bytes, void* stream);
+
+/*
+ * As dodo_nugget_attention, for nugget caches with room to grow (the autoregressive mode of
+ * Sec. 2.4, where the number of nuggets depends on the data): the nuggets of sequence b are the
+ * rows nugget_start[b] .. nugget_start[b] + nugget_len[b] of the cache (device int32 [B] each;
+ * for the caches of dodo_stream_append: nugget_start[b] = b * cap, nugget_len = counts).
+ * Kt is the number of rows of the whole cache (it only matters for the head-major layout) and
+ * max_k a host-side upper bound on nugget_len (for instance cap).
+ */
+int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                                 const int32_t* cu_q, const int32_t* nugget_start, const int32_t* nugget_len,
+                                 const int32_t* cu_local, int32_t B, int32_t H, int32_t H_kv, int32_t d_h,
+                                 int32_t max_q, int32_t max_k, int32_t max_local, int64_t Kt, float softmax_scale,
+                                 int dtype, int layout, void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Threshold of the autoregressive mode from sampled scores (Sec. 2.4: Lambda is set so that about
+ * t/r of t tokens are kept, and is estimated by running the scorer on sampled tokens).  With
+ * k = dodo_nugget_count(n, num, den), writes to *lambda_out (device, fp32) the (k+1)-th highest
+ * of the n sampled scores (device, fp32), so that exactly k of them exceed it when there are no
+ * ties; NaN ranks lowest, -0 counts as +0.  If k >= n, or that score is NaN, the threshold is
+ * -inf (keep everything).  Integer comparisons on the score bits only: bit-exact.  n >= 1.
+ */
+int dodo_threshold_from_sample(const float* sample, int64_t n, int64_t num, int64_t den, float* lambda_out,
+                               void* stream);
+
+/*
+ * Threshold selection (Eq. 8): token i of a sequence is kept iff scores[i] > *lambda (device fp32;
+ * strict, false for NaN), which does not depend on later tokens.  Writes, without any host
+ * read-back: counts[b] (int32 [B]), their running sum cu_nuggets (int32 [B+1]) and the kept tokens'
+ * sequence-local indices in ascending order, packed, to nugget_idx[cu_nuggets[b] ..] (room for
+ * cu_seqlens[B] entries) -- the format dodo_gather_nuggets and dodo_nugget_attention take.  The
+ * total cu_nuggets[B] is only known on the device: pass dodo_gather_nuggets an upper bound as Kt
+ * (token-major layout; rows past cu_nuggets[B] are skipped).  B == 0 is a no-op.
+ */
+int dodo_select_threshold(const float* scores, const int32_t* cu_seqlens, int32_t B, const float* lambda,
+                          int32_t* counts, int32_t* cu_nuggets, int32_t* nugget_idx, void* stream);
+
+/*
+ * One decode step of the autoregressive mode (Sec. 2.4 with the mixed resolution of Eq. 9): in each
+ * of B sequences one token leaves the window of uncompressed tokens.  scores[b] is its score
+ * (device fp32 [B]), K_rows / V_rows its key and value rows ([B, H_kv, d_h] of `dtype`, row_stride
+ * elements between sequences).  If scores[b] > *lambda the rows are appended to sequence b's nugget
+ * cache at row b * cap + counts[b] of Kn / Vn ([B * cap, H_kv, d_h], token-major) and counts[b]
+ * (device int32, in/out) grows by one; a full cache drops the token and adds one to *dropped
+ * (device int32, may be NULL).  H_kv * d_h * element size and the row stride must be multiples
+ * of 16 bytes.
+ */
+int dodo_stream_append(const float* scores, const float* lambda, const void* K_rows, const void* V_rows, int dtype,
+                       int32_t B, int32_t H_kv, int32_t d_h, int64_t row_stride, int32_t cap, int32_t* counts,
+                       int32_t* dropped, void* Kn, void* Vn, void* stream);
 
 #ifdef __cplusplus
 }

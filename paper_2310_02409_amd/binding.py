@@ -50,6 +50,15 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_attention.restype = ctypes.c_int
     L.dodo_nugget_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
                                         ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    L.dodo_nugget_attention_cached.restype = ctypes.c_int
+    L.dodo_nugget_attention_cached.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                               i64, f32, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    L.dodo_threshold_from_sample.restype = ctypes.c_int
+    L.dodo_threshold_from_sample.argtypes = [vp, i64, i64, i64, vp, vp]
+    L.dodo_select_threshold.restype = ctypes.c_int
+    L.dodo_select_threshold.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
+    L.dodo_stream_append.restype = ctypes.c_int
+    L.dodo_stream_append.argtypes = [vp, vp, vp, vp, ctypes.c_int, i32, i32, i32, i64, i32, vp, vp, vp, vp, vp]
     return L
 
 
@@ -195,3 +204,75 @@ def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, K
                                      float(softmax_scale), code, layout, _ptr(O), _ptr(lse), _ptr(ws),
                                      0 if ws is None else ws.numel(), _stream()), "dodo_nugget_attention")
     return O, lse
+
+
+def dodo_nugget_attention_cached(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, Kl: torch.Tensor,
+                                 Vl: torch.Tensor, cu_q: torch.Tensor, nugget_start: torch.Tensor,
+                                 nugget_len: torch.Tensor, cu_local: torch.Tensor, max_q: int, max_k: int,
+                                 max_local: int, softmax_scale: Optional[float] = None, layout: int = TOKEN_MAJOR,
+                                 O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                                 want_lse: bool = False, ws: Optional[torch.Tensor] = None):
+    """dodo_nugget_attention over caches with room to grow: nuggets of sequence b are the rows
+    nugget_start[b] .. + nugget_len[b] of Kn / Vn [rows, H_kv, d_h]; returns (O, lse or None)."""
+    _dev(Q, Kn, Vn, Kl, Vl, cu_q, nugget_start, nugget_len, cu_local, O, lse, ws)
+    Sq, H, d_h = Q.shape
+    H_kv = Kl.shape[1]
+    Kt = Kn.shape[0] if layout == TOKEN_MAJOR else Kn.shape[1]
+    B = cu_q.numel() - 1
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d_h)
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None and want_lse:
+        lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
+    code = _dtype_code(Q)
+    need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, code)
+    if need and ws is None:
+        ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
+    _check(lib.dodo_nugget_attention_cached(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(Kl), _ptr(Vl), _ptr(cu_q),
+                                            _ptr(nugget_start), _ptr(nugget_len), _ptr(cu_local), B, H, H_kv, d_h,
+                                            max_q, max_k, max_local, Kt, float(softmax_scale), code, layout, _ptr(O),
+                                            _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "dodo_nugget_attention_cached")
+    return O, lse
+
+
+def dodo_threshold_from_sample(sample: torch.Tensor, num: int, den: int,
+                               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Threshold Lambda (device tensor with one fp32) from sampled scores: the (k+1)-th highest, k = nugget count."""
+    _dev(sample, out)
+    assert sample.dtype == torch.float32 and sample.is_contiguous()
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=sample.device)
+    _check(lib.dodo_threshold_from_sample(_ptr(sample), sample.numel(), num, den, _ptr(out), _stream()),
+           "dodo_threshold_from_sample")
+    return out
+
+
+def dodo_select_threshold(scores: torch.Tensor, cu_seqlens: torch.Tensor, lam: torch.Tensor):
+    """Threshold selection (Eq. 8): returns (counts [B], cu_nuggets [B+1], nugget_idx with room for all tokens),
+    all on the device; the first cu_nuggets[B] entries of nugget_idx are the packed index lists."""
+    _dev(scores, cu_seqlens, lam)
+    assert scores.dtype == torch.float32 and lam.dtype == torch.float32
+    B = cu_seqlens.numel() - 1
+    counts = torch.empty(B, dtype=torch.int32, device=scores.device)
+    cu_nuggets = torch.empty(B + 1, dtype=torch.int32, device=scores.device)
+    idx = torch.empty(max(1, scores.numel()), dtype=torch.int32, device=scores.device)
+    _check(lib.dodo_select_threshold(_ptr(scores), _ptr(cu_seqlens), B, _ptr(lam), _ptr(counts), _ptr(cu_nuggets),
+                                     _ptr(idx), _stream()), "dodo_select_threshold")
+    return counts, cu_nuggets, idx
+
+
+def dodo_stream_append(scores: torch.Tensor, lam: torch.Tensor, K_rows: torch.Tensor, V_rows: torch.Tensor,
+                       counts: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor,
+                       dropped: Optional[torch.Tensor] = None) -> None:
+    """One decode step: rows [B, H_kv, d_h] whose score exceeds Lambda are appended to the caches
+    [B, cap, H_kv, d_h] (in place), counts [B] int32 is updated in place."""
+    _dev(scores, lam, K_rows, V_rows, counts, Kn, Vn, dropped)
+    B, H_kv, d_h = K_rows.shape
+    cap = Kn.shape[1]
+    assert Kn.shape == (B, cap, H_kv, d_h) and Kn.is_contiguous() and Vn.is_contiguous()
+    assert K_rows.stride(2) == 1 and K_rows.stride(1) == d_h and V_rows.stride() == K_rows.stride()
+    _check(lib.dodo_stream_append(_ptr(scores), _ptr(lam), _ptr(K_rows), _ptr(V_rows), _dtype_code(K_rows), B, H_kv,
+                                  d_h, K_rows.stride(0), cap, _ptr(counts), _ptr(dropped), _ptr(Kn), _ptr(Vn),
+                                  _stream()), "dodo_stream_append")

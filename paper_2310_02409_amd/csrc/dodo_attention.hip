@@ -22,12 +22,14 @@ extern "C" size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, in
   return splitk_workspace_bytes(B, H, d_h, max_q, splitk_count(B, H, max_q, max_k, max_local));
 }
 
-extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
-                                     const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local,
-                                     int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
-                                     int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout,
-                                     void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
-  using namespace dodo;
+namespace dodo {
+namespace {
+
+int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl, const int32_t* cu_q,
+                    const int32_t* cu_nuggets, const int32_t* nug_len, const int32_t* cu_local, int32_t B, int32_t H,
+                    int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local, int64_t Kt,
+                    float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws, size_t ws_bytes,
+                    void* stream) {
   if (B < 0 || H <= 0 || H_kv <= 0 || d_h <= 0 || max_q < 0 || max_k < 0 || max_local < 0 || Kt < 0)
     return DODO_ERR_INVALID_ARG;
   if (H % H_kv != 0) return DODO_ERR_INVALID_ARG;
@@ -46,7 +48,7 @@ extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* 
 
   AttnParams p;
   p.Q = Q; p.Kn = Kn; p.Vn = Vn; p.Kl = Kl; p.Vl = Vl;
-  p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.cu_local = cu_local;
+  p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.nug_len = nug_len; p.cu_local = cu_local;
   p.B = B; p.H = H; p.H_kv = H_kv; p.d_h = d_h; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
   if (layout == DODO_LAYOUT_TOKEN_MAJOR) {
     p.nug_tok_stride = static_cast<int64_t>(H_kv) * d_h;
@@ -61,4 +63,27 @@ extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* 
   p.stream = static_cast<hipStream_t>(stream);
   if (use_block_kernel(dtype, d_h, max_q)) return launch_block_attention(p);
   return launch_splitk_attention(p);
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                                     const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local,
+                                     int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
+                                     int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout,
+                                     void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nullptr, cu_local, B, H, H_kv, d_h, max_q, max_k,
+                               max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
+}
+
+extern "C" int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, const void* Kl,
+                                            const void* Vl, const int32_t* cu_q, const int32_t* nugget_start,
+                                            const int32_t* nugget_len, const int32_t* cu_local, int32_t B, int32_t H,
+                                            int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local,
+                                            int64_t Kt, float softmax_scale, int dtype, int layout, void* O, float* lse,
+                                            void* ws, size_t ws_bytes, void* stream) {
+  if (B > 0 && max_q > 0 && !nugget_len) return DODO_ERR_INVALID_ARG;
+  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, nugget_start, nugget_len, cu_local, B, H, H_kv, d_h, max_q,
+                               max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
 }

@@ -7,6 +7,7 @@ namespace dodo {
 struct AttnParams {
   const void *Q, *Kn, *Vn, *Kl, *Vl;
   const int32_t *cu_q, *cu_nuggets, *cu_local;
+  const int32_t* nug_len;  // null: nuggets of sequence b are rows cu_nuggets[b] .. cu_nuggets[b+1]; else cu_nuggets[b] .. + nug_len[b]
   int32_t B, H, H_kv, d_h, max_q, max_k, max_local;
   int64_t nug_tok_stride, nug_head_stride;  // elements between tokens / KV heads of the nugget cache
   float scale_log2e;                        // softmax_scale * log2(e): logits are kept in base 2

@@ -20,6 +20,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt,
     int vec_per_head, int vec_per_row, int64_t token_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
   const int64_t dst_tok = blockIdx.x;
+  if (dst_tok >= cu_nuggets[B]) return;  // Kt may be an upper bound of the nugget count
   // sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1]
   int lo = 0, hi = B;
   while (hi - lo > 1) {

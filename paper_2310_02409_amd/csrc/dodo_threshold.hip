@@ -1,0 +1,216 @@
+// Selection of the autoregressive mode (Sec. 2.4 of the Dodo paper): a token is
+// kept as a nugget if its score exceeds a threshold Lambda (Eq. 8), which does
+// not look at later tokens.
+//   dodo_threshold_from_sample  Lambda from a sample of scores: the (k+1)-th
+//                               highest, k = nugget count of the sample size
+//   dodo_select_threshold       kept tokens of whole sequences as packed index
+//                               lists (same format as the TopK selection)
+//   dodo_stream_append          one decode step: the token that leaves the
+//                               window of uncompressed tokens is appended to
+//                               its sequence's nugget cache if it is kept
+// Integer and copy work only: results are unique and bit-exact.
+#include "dodo_common.h"
+
+namespace dodo {
+namespace {
+
+constexpr int kSampleThreads = 1024;
+constexpr int kThreshThreads = 256;
+constexpr int kAppendThreads = 256;
+
+// Order-preserving image of an fp32 score (NaN lowest, -0 == +0) and its inverse on non-NaN keys.
+__device__ __forceinline__ uint32_t order_key(float s) {
+  uint32_t u = __float_as_uint(s);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_score(uint32_t key) {
+  if (key == 0u) return -__builtin_inff();  // NaN ranks lowest: everything that can be kept is kept
+  return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
+
+// Key of the `rank`-th highest of n scores (1 <= rank <= n) by a 4-pass, 8-bit MSB radix select;
+// one workgroup, the scores are re-read from global memory in every pass (they sit in L2).
+__global__ __launch_bounds__(kSampleThreads) void kth_highest_kernel(const float* __restrict__ sample, int64_t n,
+                                                                     int64_t rank, float* __restrict__ lambda_out) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t s_prefix;
+  __shared__ unsigned long long s_remaining;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  uint32_t prefix = 0, mask = 0;
+  unsigned long long remaining = static_cast<unsigned long long>(rank);
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    for (int i = tid; i < 256; i += kSampleThreads) hist[i] = 0;
+    __syncthreads();
+    for (int64_t i0 = static_cast<int64_t>(wave) * kWave; i0 < n; i0 += kSampleThreads) {
+      const int64_t i = i0 + lane;
+      const uint32_t key = (i < n) ? order_key(sample[i]) : 0u;
+      bool part = (i < n) && ((key & mask) == prefix);
+      const uint32_t digit = (key >> shift) & 255u;
+      // two rounds of wavefront aggregation absorb the hot bins, the rest goes lane by lane
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {
+        const uint64_t act = __ballot(part);
+        if (act != 0) {
+          const int leader = __ffsll(static_cast<long long>(act)) - 1;
+          const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
+          const bool same = part && digit == d0;
+          const uint64_t mm = __ballot(same);
+          if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
+          part = part && !same;
+        }
+      }
+      if (part) atomicAdd(&hist[digit], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {  // 256 bins, once per pass: a plain scan from the top
+      unsigned long long above = 0;
+      int d = 255;
+      for (; d > 0; --d) {
+        if (above + hist[d] >= remaining) break;
+        above += hist[d];
+      }
+      s_prefix = prefix | (static_cast<uint32_t>(d) << shift);
+      s_remaining = remaining - above;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    remaining = s_remaining;
+    mask |= 255u << shift;
+  }
+  if (tid == 0) *lambda_out = key_to_score(prefix);
+}
+
+__global__ void fill_float_kernel(float* p, float v) { *p = v; }
+
+// Stable compaction of { i : scores[i] > lambda } of one sequence per workgroup.
+// COUNT_ONLY: counts[b] only.  Otherwise the workgroup finds its place in the packed list by
+// summing the counts of the sequences before it, writes its indices there and cu_nuggets[b + 1].
+template <bool COUNT_ONLY>
+__global__ __launch_bounds__(kThreshThreads) void select_threshold_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ cu_seqlens, const float* __restrict__ lambda, int B,
+    int32_t* __restrict__ counts, int32_t* __restrict__ cu_nuggets, int32_t* __restrict__ nugget_idx) {
+  constexpr int kWaves = kThreshThreads / kWave;
+  __shared__ int wave_cnt[kWaves];
+  __shared__ int s_base;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  const int seq0 = cu_seqlens[b];
+  const int n = cu_seqlens[b + 1] - seq0;
+  const float lam = *lambda;
+  const float* s = scores + seq0;
+  // contiguous per-wavefront ranges keep the output in position order
+  const int per_wave = ((n + kWaves * kWave - 1) / (kWaves * kWave)) * kWave;
+  const int start = wave * per_wave;
+  const int end = min(start + per_wave, n);
+  int cnt = 0;
+  for (int i0 = start; i0 < end; i0 += kWave) {
+    const int i = i0 + lane;
+    cnt += __popcll(__ballot(i < end && s[i] > lam));  // false for NaN
+  }
+  if (lane == 0) wave_cnt[wave] = cnt;
+  if (!COUNT_ONLY && tid == 0) {
+    int base = 0;
+    for (int bb = 0; bb < b; ++bb) base += counts[bb];
+    s_base = base;
+  }
+  __syncthreads();
+  int total = 0, before = 0;
+  for (int w = 0; w < kWaves; ++w) {
+    if (w < wave) before += wave_cnt[w];
+    total += wave_cnt[w];
+  }
+  if (COUNT_ONLY) {
+    if (tid == 0) counts[b] = total;
+    return;
+  }
+  int out_at = s_base + before;
+  for (int i0 = start; i0 < end; i0 += kWave) {
+    const int i = i0 + lane;
+    const bool keep = i < end && s[i] > lam;
+    const uint64_t km = __ballot(keep);
+    if (keep) nugget_idx[out_at + popc_below_lane(km)] = i;
+    out_at += __popcll(km);
+  }
+  if (tid == 0) {
+    cu_nuggets[b + 1] = s_base + total;
+    if (b == 0) cu_nuggets[0] = 0;
+  }
+}
+
+// One workgroup per sequence: append the leaving token's K and V rows if its score exceeds lambda.
+__global__ __launch_bounds__(kAppendThreads) void stream_append_kernel(
+    const float* __restrict__ scores, const float* __restrict__ lambda, const uint4* __restrict__ K_rows,
+    const uint4* __restrict__ V_rows, int64_t row_stride_vec, int vec_per_row, int cap, int32_t* __restrict__ counts,
+    int32_t* __restrict__ dropped, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
+  const int b = blockIdx.x;
+  if (!(scores[b] > *lambda)) return;  // uniform over the workgroup
+  const int at = counts[b];
+  if (at >= cap) {
+    if (threadIdx.x == 0 && dropped != nullptr) atomicAdd(dropped, 1);
+    return;
+  }
+  const uint4* ks = K_rows + b * row_stride_vec;
+  const uint4* vs = V_rows + b * row_stride_vec;
+  const int64_t dst = (static_cast<int64_t>(b) * cap + at) * vec_per_row;
+  for (int c = threadIdx.x; c < vec_per_row; c += kAppendThreads) {
+    Kn[dst + c] = ks[c];
+    Vn[dst + c] = vs[c];
+  }
+  __syncthreads();  // every thread has read counts[b]
+  if (threadIdx.x == 0) counts[b] = at + 1;
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" int dodo_threshold_from_sample(const float* sample, int64_t n, int64_t num, int64_t den, float* lambda_out,
+                                          void* stream) {
+  using namespace dodo;
+  if (n <= 0 || num <= 0 || den <= 0) return DODO_ERR_INVALID_ARG;
+  if (!sample || !lambda_out) return DODO_ERR_INVALID_ARG;
+  const int64_t k = dodo_nugget_count(n, num, den);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (k >= n) {
+    hipLaunchKernelGGL(fill_float_kernel, dim3(1), dim3(1), 0, s, lambda_out, -__builtin_inff());
+  } else {
+    hipLaunchKernelGGL(kth_highest_kernel, dim3(1), dim3(kSampleThreads), 0, s, sample, n, k + 1, lambda_out);
+  }
+  return launch_status();
+}
+
+extern "C" int dodo_select_threshold(const float* scores, const int32_t* cu_seqlens, int32_t B, const float* lambda,
+                                     int32_t* counts, int32_t* cu_nuggets, int32_t* nugget_idx, void* stream) {
+  using namespace dodo;
+  if (B < 0) return DODO_ERR_INVALID_ARG;
+  if (B == 0) return DODO_OK;
+  if (!scores || !cu_seqlens || !lambda || !counts || !cu_nuggets || !nugget_idx) return DODO_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(select_threshold_kernel<true>, dim3(B), dim3(kThreshThreads), 0, s, scores, cu_seqlens, lambda, B,
+                     counts, cu_nuggets, nugget_idx);
+  int rc = launch_status();
+  if (rc != DODO_OK) return rc;
+  hipLaunchKernelGGL(select_threshold_kernel<false>, dim3(B), dim3(kThreshThreads), 0, s, scores, cu_seqlens, lambda, B,
+                     counts, cu_nuggets, nugget_idx);
+  return launch_status();
+}
+
+extern "C" int dodo_stream_append(const float* scores, const float* lambda, const void* K_rows, const void* V_rows,
+                                  int dtype, int32_t B, int32_t H_kv, int32_t d_h, int64_t row_stride, int32_t cap,
+                                  int32_t* counts, int32_t* dropped, void* Kn, void* Vn, void* stream) {
+  using namespace dodo;
+  if (B < 0 || H_kv <= 0 || d_h <= 0 || cap < 0) return DODO_ERR_INVALID_ARG;
+  if (row_stride < static_cast<int64_t>(H_kv) * d_h) return DODO_ERR_INVALID_ARG;
+  if (B == 0) return DODO_OK;
+  if (!scores || !lambda || !K_rows || !V_rows || !counts || !Kn || !Vn) return DODO_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
+  const int es = elem_bytes(dtype);
+  if ((static_cast<int64_t>(H_kv) * d_h * es) % 16 != 0 || (row_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
+  if (!aligned16(K_rows) || !aligned16(V_rows) || !aligned16(Kn) || !aligned16(Vn)) return DODO_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(stream_append_kernel, dim3(B), dim3(kAppendThreads), 0, static_cast<hipStream_t>(stream), scores,
+                     lambda, static_cast<const uint4*>(K_rows), static_cast<const uint4*>(V_rows), row_stride * es / 16,
+                     H_kv * d_h * es / 16, cap, counts, dropped, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
+  return launch_status();
+}

@@ -26,7 +26,8 @@ def test_header_symbols_are_exported(lib):
     names = _declared_functions()
     assert {"dodo_score", "dodo_select_topk", "dodo_gather_nuggets", "dodo_nugget_attention", "dodo_nugget_count",
             "dodo_version", "dodo_status_string", "dodo_select_topk_workspace_bytes",
-            "dodo_nugget_attention_workspace_bytes"} <= set(names)
+            "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
+            "dodo_select_threshold", "dodo_stream_append"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
@@ -115,3 +116,23 @@ def test_attention_argument_validation(lib):
     assert call(B=2, H=2, H_kv=2, max_q=1, max_k=3277, max_local=1089, ws=0, ws_bytes=0) == -3
     assert call(B=2, H=2, H_kv=2, max_q=1, max_k=3277, max_local=1089, ws=P, ws_bytes=need - 1) == -3
     assert lib.dodo_nugget_attention_workspace_bytes(8, 32, 128, 512, 410, 640, 1) == 0
+
+
+def test_threshold_path_argument_validation(lib):
+    P = ctypes.c_void_p(16)  # never dereferenced: validation fails first
+    i64 = ctypes.c_int64
+    assert lib.dodo_threshold_from_sample(P, i64(0), i64(1), i64(10), P, None) == -1
+    assert lib.dodo_threshold_from_sample(P, i64(10), i64(0), i64(10), P, None) == -1
+    assert lib.dodo_threshold_from_sample(None, i64(10), i64(1), i64(10), P, None) == -1
+    assert lib.dodo_select_threshold(P, P, -1, P, P, P, P, None) == -1
+    assert lib.dodo_select_threshold(P, P, 0, P, P, P, P, None) == 0
+    assert lib.dodo_select_threshold(P, P, 2, None, P, P, P, None) == -1
+    # stream append: shapes, stride, dtype, 16-byte rows
+    ok = dict(B=2, H_kv=2, d_h=64, stride=128, cap=8, dtype=1)
+    def call(**kw):
+        a = {**ok, **kw}
+        return lib.dodo_stream_append(P, P, P, P, a["dtype"], a["B"], a["H_kv"], a["d_h"], i64(a["stride"]), a["cap"], P,
+                                      None, P, P, None)
+    assert call(B=-1) == -1 and call(stride=100) == -1 and call(cap=-1) == -1
+    assert call(dtype=7) == -2 and call(d_h=3, H_kv=1, stride=3) == -2
+    assert call(B=0) == 0
