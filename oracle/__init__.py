@@ -48,7 +48,7 @@ def _load():
         lib.oracle_threshold_from_sample.restype = ctypes.c_float
         lib.oracle_stream_append.restype = ctypes.c_int32
         lib.oracle_select_threshold_indices.restype = None
-        for name in ("oracle_score", "oracle_select_threshold", "oracle_gather", "oracle_attention",
+        for name in ("oracle_score", "oracle_select_threshold", "oracle_gather", "oracle_meanpool", "oracle_attention",
                      "oracle_attention_rows"):
             getattr(lib, name).restype = None
         _lib = lib
@@ -117,6 +117,22 @@ def select_threshold(scores: np.ndarray, cu_seqlens: np.ndarray, lam: float):
     _load().oracle_select_threshold(_p(scores), _p(cu_seqlens), ctypes.c_int32(B), ctypes.c_float(lam), _p(alpha),
                                     _p(counts))
     return alpha, counts
+
+
+def meanpool(K: np.ndarray, V: np.ndarray, cu_seqlens: np.ndarray, cu_nuggets: np.ndarray, layout: int = TOKEN_MAJOR):
+    """Pooling baseline's compaction (Sec. 5.1): k_b even chunks per sequence, each mean-pooled into one row."""
+    K, V = _c(K), _c(V)
+    assert K.ndim == 3 and K.shape == V.shape and K.dtype == V.dtype
+    cu_seqlens, cu_nuggets = _c(cu_seqlens, np.int32), _c(cu_nuggets, np.int32)
+    _, H_kv, d_h = K.shape
+    B = len(cu_seqlens) - 1
+    Kt = int(cu_nuggets[-1])
+    shape = (Kt, H_kv, d_h) if layout == TOKEN_MAJOR else (H_kv, Kt, d_h)
+    Kn, Vn = np.zeros(shape, dtype=K.dtype), np.zeros(shape, dtype=K.dtype)
+    _load().oracle_meanpool(_p(K), _p(V), _dtype_code(K), _p(cu_seqlens), _p(cu_nuggets), ctypes.c_int32(B),
+                            ctypes.c_int64(Kt), ctypes.c_int32(H_kv), ctypes.c_int32(d_h),
+                            ctypes.c_int64(H_kv * d_h), _p(Kn), _p(Vn), ctypes.c_int(layout))
+    return Kn, Vn
 
 
 def threshold_from_sample(sample: np.ndarray, num: int, den: int) -> float:

@@ -40,6 +40,45 @@ inline double load(const void* base, int dtype, int64_t i) {
   return static_cast<double>(f);
 }
 
+// Rounds a double to the storage type (round to nearest even, once) and stores it.
+inline void store(void* base, int dtype, int64_t i, double v) {
+  const float f = static_cast<float>(v);
+  if (dtype == kF32) {
+    static_cast<float*>(base)[i] = f;
+    return;
+  }
+  // double -> bf16 in one rounding: round the double's value at bf16 precision directly
+  uint32_t bits;
+  std::memcpy(&bits, &f, 4);
+  if (std::isnan(v)) {
+    static_cast<uint16_t*>(base)[i] = 0x7fc0;
+    return;
+  }
+  // candidates: f truncated to bf16 and its neighbour away from zero; pick the nearer to v (ties to even)
+  uint32_t lo = bits & 0xffff0000u;
+  float flo;
+  std::memcpy(&flo, &lo, 4);
+  if (static_cast<double>(flo) == v) {
+    static_cast<uint16_t*>(base)[i] = static_cast<uint16_t>(lo >> 16);
+    return;
+  }
+  // f may itself have been rounded from v; compare against v, not f, using both bf16 neighbours of v
+  const double av = std::fabs(v);
+  uint32_t mag = lo & 0x7fff0000u;
+  float fm;
+  std::memcpy(&fm, &mag, 4);
+  if (static_cast<double>(fm) > av) {  // rounding to float went up past a bf16 value: step down
+    mag -= 0x10000u;
+    std::memcpy(&fm, &mag, 4);
+  }
+  uint32_t up = mag + 0x10000u;
+  float fu;
+  std::memcpy(&fu, &up, 4);
+  const double dl = av - static_cast<double>(fm), du = static_cast<double>(fu) - av;
+  uint32_t pick = (dl < du) ? mag : (du < dl) ? up : ((mag >> 16) & 1u) ? up : mag;
+  static_cast<uint16_t*>(base)[i] = static_cast<uint16_t>((pick | (lo & 0x80000000u)) >> 16);
+}
+
 // "a has a strictly higher score than b" with NaN placed below everything.
 inline bool higher(float a, float b) {
   if (std::isnan(a)) return false;
@@ -235,6 +274,37 @@ int32_t oracle_stream_append(const float* scores, float lambda, const void* K_ro
     ++counts[b];
   }
   return dropped;
+}
+
+// Compaction of the pooling baseline the paper compares with (Sec. 5.1: the text is chunked evenly
+// into segments and each segment's states are mean-pooled into one vector, at the same compression
+// ratio): sequence b of n_b tokens becomes k_b = cu_nuggets[b+1] - cu_nuggets[b] rows, row j being the
+// mean of tokens floor(j n_b / k_b) .. floor((j+1) n_b / k_b) - 1, summed in double and rounded once.
+void oracle_meanpool(const void* K, const void* V, int dtype, const int32_t* cu_seqlens, const int32_t* cu_nuggets,
+                     int32_t B, int64_t Kt, int32_t H_kv, int32_t d_h, int64_t token_stride, void* Kn, void* Vn,
+                     int layout) {
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t n = cu_seqlens[b + 1] - cu_seqlens[b];
+    const int64_t k = cu_nuggets[b + 1] - cu_nuggets[b];
+    for (int64_t j = 0; j < k; ++j) {
+      const int64_t t0 = j * n / k, t1 = (j + 1) * n / k;
+      const int64_t dst_tok = cu_nuggets[b] + j;
+      for (int32_t h = 0; h < H_kv; ++h)
+        for (int32_t c = 0; c < d_h; ++c) {
+          double sk = 0.0, sv = 0.0;
+          for (int64_t t = t0; t < t1; ++t) {
+            const int64_t src = (cu_seqlens[b] + t) * token_stride + static_cast<int64_t>(h) * d_h + c;
+            sk += load(K, dtype, src);
+            sv += load(V, dtype, src);
+          }
+          const double inv = t1 > t0 ? 1.0 / static_cast<double>(t1 - t0) : 0.0;
+          const int64_t dst = (layout == kTokenMajor) ? (dst_tok * H_kv + h) * d_h + c
+                                                      : (static_cast<int64_t>(h) * Kt + dst_tok) * d_h + c;
+          store(Kn, dtype, dst, sk * inv);
+          store(Vn, dtype, dst, sv * inv);
+        }
+    }
+  }
 }
 
 // Sub-selection (Eq. 5): nuggets are the chosen tokens' own K and V rows,
