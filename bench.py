@@ -358,6 +358,21 @@ def main():
             torch.cuda.synchronize()
             us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
             ar[name] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2)}
+        # the pooling baseline's compaction (same output shape as the gather)
+        for _ in range(3):
+            D.dodo_meanpool_nuggets(g["K"], g["V"], g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for a, b in evs:
+            a.record()
+            D.dodo_meanpool_nuggets(g["K"], g["V"], g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
+            b.record()
+        torch.cuda.synchronize()
+        us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        mp_bytes = 2 * (wl.N + Kt) * wl.H_kv * wl.d_h * E
+        kernels["meanpool_baseline"] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2),
+                                        "GBps": round(mp_bytes / (sum(us) / len(us)) * 1e-3, 1)}
+        D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)  # restore the cache
         ar["note"] = ("threshold rule of the autoregressive mode, timed apart from the step: sample = the step's "
                       f"{wl.N} scores; stream_append includes a fill of the {B} counters; caches of {cap} rows per sequence")
         kernels["autoregressive_mode"] = ar

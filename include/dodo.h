@@ -144,6 +144,18 @@ int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const v
                           size_t ws_bytes, void* stream);
 
 /*
+ * Compaction of the pooling baseline the paper compares with (Sec. 5.1: the text is chunked evenly
+ * into segments whose states are mean-pooled, at the same compression ratio): sequence b becomes
+ * k_b = cu_nuggets[b+1] - cu_nuggets[b] rows, row j the mean of the K (V) rows of tokens
+ * floor(j n_b / k_b) .. floor((j+1) n_b / k_b) - 1.  Same shapes, layouts and restrictions as
+ * dodo_gather_nuggets (without an index list), so the result feeds the same attention calls.
+ * Sums and the division are done in double in token order and rounded once: bit-exact.
+ */
+int dodo_meanpool_nuggets(const void* K, const void* V, int dtype, const int32_t* cu_seqlens,
+                          const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t H_kv, int32_t d_h,
+                          int64_t token_stride, void* Kn, void* Vn, int layout, void* stream);
+
+/*
  * As dodo_nugget_attention, for nugget caches with room to grow (the autoregressive mode of
  * Sec. 2.4, where the number of nuggets depends on the data): the nuggets of sequence b are the
  * rows nugget_start[b] .. nugget_start[b] + nugget_len[b] of the cache (device int32 [B] each;

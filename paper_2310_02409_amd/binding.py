@@ -50,6 +50,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_attention.restype = ctypes.c_int
     L.dodo_nugget_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
                                         ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    L.dodo_meanpool_nuggets.restype = ctypes.c_int
+    L.dodo_meanpool_nuggets.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i64, i32, i32, i64, vp, vp, ctypes.c_int, vp]
     L.dodo_nugget_attention_cached.restype = ctypes.c_int
     L.dodo_nugget_attention_cached.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                                i64, f32, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
@@ -276,3 +278,20 @@ def dodo_stream_append(scores: torch.Tensor, lam: torch.Tensor, K_rows: torch.Te
     _check(lib.dodo_stream_append(_ptr(scores), _ptr(lam), _ptr(K_rows), _ptr(V_rows), _dtype_code(K_rows), B, H_kv,
                                   d_h, K_rows.stride(0), cap, _ptr(counts), _ptr(dropped), _ptr(Kn), _ptr(Vn),
                                   _stream()), "dodo_stream_append")
+
+
+def dodo_meanpool_nuggets(K: torch.Tensor, V: torch.Tensor, cu_seqlens: torch.Tensor, cu_nuggets: torch.Tensor,
+                          Kt: int, layout: int = TOKEN_MAJOR, Kn: Optional[torch.Tensor] = None,
+                          Vn: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Pooling baseline's compaction: K, V [N, H_kv, d_h] -> mean-pooled caches of Kt rows."""
+    _dev(K, V, cu_seqlens, cu_nuggets, Kn, Vn)
+    N, H_kv, d_h = K.shape
+    shape = (Kt, H_kv, d_h) if layout == TOKEN_MAJOR else (H_kv, Kt, d_h)
+    if Kn is None:
+        Kn = torch.empty(shape, dtype=K.dtype, device=K.device)
+    if Vn is None:
+        Vn = torch.empty(shape, dtype=K.dtype, device=K.device)
+    B = cu_seqlens.numel() - 1
+    _check(lib.dodo_meanpool_nuggets(_ptr(K), _ptr(V), _dtype_code(K), _ptr(cu_seqlens), _ptr(cu_nuggets), B, Kt, H_kv,
+                                     d_h, H_kv * d_h, _ptr(Kn), _ptr(Vn), layout, _stream()), "dodo_meanpool_nuggets")
+    return Kn, Vn

@@ -27,7 +27,7 @@ def test_header_symbols_are_exported(lib):
     assert {"dodo_score", "dodo_select_topk", "dodo_gather_nuggets", "dodo_nugget_attention", "dodo_nugget_count",
             "dodo_version", "dodo_status_string", "dodo_select_topk_workspace_bytes",
             "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
-            "dodo_select_threshold", "dodo_stream_append"} <= set(names)
+            "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
