@@ -48,7 +48,7 @@ def _load():
         lib.oracle_threshold_from_sample.restype = ctypes.c_float
         lib.oracle_stream_append.restype = ctypes.c_int32
         lib.oracle_select_threshold_indices.restype = None
-        for name in ("oracle_score", "oracle_select_threshold", "oracle_gather", "oracle_meanpool", "oracle_attention",
+        for name in ("oracle_score", "oracle_score_mlp", "oracle_select_threshold", "oracle_gather", "oracle_meanpool", "oracle_attention",
                      "oracle_attention_rows"):
             getattr(lib, name).restype = None
         _lib = lib
@@ -92,6 +92,24 @@ def score(hidden: np.ndarray, w: np.ndarray, bias: float = 0.0) -> np.ndarray:
     out = np.empty(N, dtype=np.float32)
     _load().oracle_score(_p(hidden), _p(w), ctypes.c_float(bias), _dtype_code(hidden), ctypes.c_int64(N),
                          ctypes.c_int64(d), ctypes.c_int64(d), _p(out))
+    return out
+
+
+RELU, GELU, TANH = 0, 1, 2
+
+
+def score_mlp(hidden: np.ndarray, W1: np.ndarray, b1: np.ndarray, w2: np.ndarray, b2: float = 0.0,
+              act: int = RELU) -> np.ndarray:
+    """2-layer scorer (App. B): s = w2 . act(W1 x + b1) + b2, W1 [d_hid, d]; fp32 [N]."""
+    hidden, W1, w2 = _c(hidden), _c(W1), _c(w2)
+    b1 = _c(b1, np.float32)
+    assert hidden.ndim == 2 and W1.ndim == 2 and W1.shape[1] == hidden.shape[1] and W1.shape[0] == len(w2) == len(b1)
+    assert hidden.dtype == W1.dtype == w2.dtype
+    N, d = hidden.shape
+    out = np.empty(N, dtype=np.float32)
+    _load().oracle_score_mlp(_p(hidden), _p(W1), _p(b1), _p(w2), ctypes.c_float(b2), ctypes.c_int(act),
+                             _dtype_code(hidden), ctypes.c_int64(N), ctypes.c_int64(d), ctypes.c_int64(W1.shape[0]),
+                             ctypes.c_int64(d), _p(out))
     return out
 
 

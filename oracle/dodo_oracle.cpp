@@ -178,6 +178,35 @@ void oracle_score(const void* hidden, const void* w, float bias, int dtype, int6
   }
 }
 
+// Scorer as the 2-layer feedforward network of the paper's appendix (Sec. 2.1, App. B: d -> d_hid -> 1,
+// 16.8 M parameters for d = d_hid = 4096): s[t] = sum_j w2[j] * act(sum_c W1[j,c] x[t,c] + b1[j]) + b2,
+// W1 row-major [d_hid, d].  The paper does not name the activation; act is 0 = ReLU, 1 = GELU
+// (x Phi(x), erf form), 2 = tanh.  Sums left to right in double, one rounding to fp32, -0 emitted as +0.
+void oracle_score_mlp(const void* hidden, const void* W1, const float* b1, const void* w2, float b2, int act,
+                      int dtype, int64_t N, int64_t d, int64_t d_hid, int64_t row_stride, float* scores) {
+  for (int64_t t = 0; t < N; ++t) {
+    double acc = 0.0;
+    for (int64_t j = 0; j < d_hid; ++j) {
+      double h = 0.0;
+      for (int64_t c = 0; c < d; ++c) h += load(W1, dtype, j * d + c) * load(hidden, dtype, t * row_stride + c);
+      h += static_cast<double>(b1[j]);
+      double a;
+      if (act == 0) {
+        a = h > 0.0 ? h : 0.0;
+      } else if (act == 1) {
+        a = 0.5 * h * (1.0 + std::erf(h * 0.70710678118654752440));
+      } else {
+        a = std::tanh(h);
+      }
+      acc += load(w2, dtype, j) * a;
+    }
+    acc += static_cast<double>(b2);
+    float s = static_cast<float>(acc);
+    if (s == 0.0f) s = 0.0f;
+    scores[t] = s;
+  }
+}
+
 // TopK selection (Eq. 14): per sequence, the k_b tokens with the highest score,
 // ties won by the lower index, emitted in ascending position order.  With the
 // force-last flag (footnote to Eq. 14) the final token of the sequence is
