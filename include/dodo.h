@@ -79,6 +79,29 @@ int64_t dodo_nugget_count(int64_t n, int64_t num, int64_t den);
 int dodo_score(const void* hidden, const void* w, float bias, int dtype, int64_t N, int32_t d, int64_t row_stride,
                float* scores, void* stream);
 
+/* activations of dodo_score_mlp */
+#define DODO_ACT_RELU 0
+#define DODO_ACT_GELU 1 /* x * Phi(x), erf form */
+#define DODO_ACT_TANH 2
+
+/* Bytes of device workspace dodo_score_mlp needs (may be 0). */
+size_t dodo_score_mlp_workspace_bytes(int dtype, int64_t N, int32_t d, int32_t d_hid);
+
+/*
+ * Scorer as the 2-layer feedforward network of the paper's appendix (Sec. 2.1, App. B:
+ * d -> d_hid -> 1; 16.8 M parameters for d = d_hid = 4096):
+ *   scores[t] = sum_j w2[j] * act( sum_c W1[j,c] * hidden[t,c] + b1[j] ) + b2
+ * hidden [N, d] (row_stride elements between rows), W1 [d_hid, d] row-major and w2 [d_hid] of
+ * `dtype`; b1 [d_hid] fp32; scores fp32 [N], -0 written as +0.  The paper does not name the
+ * activation: `act` is one of DODO_ACT_*.  bf16 inputs with d % 32 == 0 and d_hid % 256 == 0 run on
+ * the matrix cores (products bf16 x bf16, sums fp32, the N x d_hid intermediate stays in registers);
+ * everything else takes a plain kernel that is correct for any shape with d <= 32768 but slow for
+ * large ones.  Run-to-run deterministic.  N == 0 is a no-op.
+ */
+int dodo_score_mlp(const void* hidden, const void* W1, const float* b1, const void* w2, float b2, int act,
+                   int dtype, int64_t N, int32_t d, int32_t d_hid, int64_t row_stride, float* scores, void* ws,
+                   size_t ws_bytes, void* stream);
+
 /* Bytes of device workspace dodo_select_topk needs for B sequences of at most max_n tokens (may be 0). */
 size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n);
 

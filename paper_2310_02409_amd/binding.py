@@ -12,6 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdodo.so")
 
 F32, BF16 = 0, 1
+RELU, GELU, TANH = 0, 1, 2
 FORCE_LAST = 1
 TOKEN_MAJOR, HEAD_MAJOR = 0, 1
 
@@ -50,6 +51,10 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_attention.restype = ctypes.c_int
     L.dodo_nugget_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
                                         ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    L.dodo_score_mlp_workspace_bytes.restype = sz
+    L.dodo_score_mlp_workspace_bytes.argtypes = [ctypes.c_int, i64, i32, i32]
+    L.dodo_score_mlp.restype = ctypes.c_int
+    L.dodo_score_mlp.argtypes = [vp, vp, vp, vp, f32, ctypes.c_int, ctypes.c_int, i64, i32, i32, i64, vp, vp, sz, vp]
     L.dodo_meanpool_nuggets.restype = ctypes.c_int
     L.dodo_meanpool_nuggets.argtypes = [vp, vp, ctypes.c_int, vp, vp, i32, i64, i32, i32, i64, vp, vp, ctypes.c_int, vp]
     L.dodo_nugget_attention_cached.restype = ctypes.c_int
@@ -295,3 +300,26 @@ def dodo_meanpool_nuggets(K: torch.Tensor, V: torch.Tensor, cu_seqlens: torch.Te
     _check(lib.dodo_meanpool_nuggets(_ptr(K), _ptr(V), _dtype_code(K), _ptr(cu_seqlens), _ptr(cu_nuggets), B, Kt, H_kv,
                                      d_h, H_kv * d_h, _ptr(Kn), _ptr(Vn), layout, _stream()), "dodo_meanpool_nuggets")
     return Kn, Vn
+
+
+def dodo_score_mlp(hidden: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, w2: torch.Tensor, b2: float = 0.0,
+                   act: int = RELU, out: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """2-layer scorer (App. B): s = w2 . act(W1 x + b1) + b2 with W1 [d_hid, d]; returns fp32 scores [N]."""
+    _dev(W1, b1, w2, out, ws)
+    if not hidden.is_cuda or hidden.stride(1) != 1:
+        raise ValueError("hidden must be a device tensor with unit stride along d")
+    N, d = hidden.shape
+    d_hid = W1.shape[0]
+    assert W1.shape == (d_hid, d) and b1.shape == (d_hid,) and w2.shape == (d_hid,) and b1.dtype == torch.float32
+    assert W1.dtype == hidden.dtype == w2.dtype
+    if out is None:
+        out = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    code = _dtype_code(hidden)
+    need = int(lib.dodo_score_mlp_workspace_bytes(code, N, d, d_hid))
+    if need and ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=hidden.device)
+    _check(lib.dodo_score_mlp(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(w2), float(b2), act, code, N, d, d_hid,
+                              hidden.stride(0), _ptr(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "dodo_score_mlp")
+    return out

@@ -27,7 +27,8 @@ def test_header_symbols_are_exported(lib):
     assert {"dodo_score", "dodo_select_topk", "dodo_gather_nuggets", "dodo_nugget_attention", "dodo_nugget_count",
             "dodo_version", "dodo_status_string", "dodo_select_topk_workspace_bytes",
             "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
-            "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets"} <= set(names)
+            "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets", "dodo_score_mlp",
+            "dodo_score_mlp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
