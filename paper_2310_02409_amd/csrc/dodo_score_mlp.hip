@@ -69,8 +69,14 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
   const int j32 = lane & 31, g = lane >> 5;
   const int tg = wave >> 1, hg = wave & 1;  // token group (64 tokens) and hidden group (128 units) of this wavefront
 
-  const int64_t tok0 = static_cast<int64_t>(blockIdx.x / hsplit) * kTokTile;
-  const int split = blockIdx.x % hsplit;
+  // Workgroup -> (token tile, split).  Block i runs on XCD i % 8, and the workgroups resident on one XCD at a time
+  // are consecutive slots i / 8: these cover a few token tiles times all the splits, so that their X panels and
+  // W1 panels are shared through that XCD's L2 instead of every workgroup streaming panels of its own.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int split = slot % hsplit;
+  const int64_t tok_tile = static_cast<int64_t>(slot / hsplit) * 8 + xcd;
+  const int64_t tok0 = tok_tile * kTokTile;
+  if (tok0 >= N) return;  // the grid is rounded up to whole groups of 8 token tiles
   const int tiles_total = d_hid / kHidTile;
   const int tiles_per_split = (tiles_total + hsplit - 1) / hsplit;
   const int tile0 = split * tiles_per_split;
@@ -261,8 +267,10 @@ bool mfma_path(int dtype, int64_t N, int32_t d, int32_t d_hid, int64_t row_strid
 int hidden_splits(int64_t N, int32_t d_hid) {
   const int64_t blocks = (N + kTokTile - 1) / kTokTile;
   const int tiles = d_hid / kHidTile;
+  // at least 4 splits (when there are that many tiles) so that an XCD's resident workgroups form a 2-D patch of
+  // the (token tile, hidden tile) plane; more while the grid does not fill the chip
   int hs = 1;
-  while (blocks * hs < compute_units() && hs * 2 <= tiles) hs *= 2;
+  while (hs * 2 <= tiles && (hs < 4 || blocks * hs < compute_units())) hs *= 2;
   return hs;
 }
 
@@ -291,7 +299,7 @@ extern "C" int dodo_score_mlp(const void* hidden, const void* W1, const float* b
     const int hs = hidden_splits(N, d_hid);
     const size_t need = hs > 1 ? static_cast<size_t>(hs) * N * sizeof(float) : 0;
     if (need > 0 && (!ws || ws_bytes < need)) return DODO_ERR_WORKSPACE_TOO_SMALL;
-    const int64_t blocks = (N + kTokTile - 1) / kTokTile * hs;
+    const int64_t blocks = ((N + kTokTile - 1) / kTokTile + 7) / 8 * 8 * hs;
     if (blocks > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
     constexpr int kLds = kStagesG * kStageBytesG;
     DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_mfma_kernel),
