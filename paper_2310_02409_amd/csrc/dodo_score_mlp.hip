@@ -12,12 +12,17 @@
 // of the accumulators and the reduction over hidden units stays inside a lane),
 // then applies bias, activation and w2 to the accumulators and adds them to the
 // tokens' partial scores.  The N x d_hid intermediate never leaves the registers.
-// X and W1 tiles stream global -> LDS with 16-byte direct loads, four 32 KiB
-// stages, three steps ahead; rows are 64 bytes with an XOR swizzle of the 16-byte
-// pieces that makes the fragment reads conflict-free.  All sums have a fixed
-// order (no atomics): run-to-run deterministic.  When there are fewer token
-// blocks than compute units, the hidden tiles are split over several workgroups
-// whose partial scores a second kernel adds in split order.
+// X and W1 tiles stream global -> LDS with 16-byte direct loads into four 32 KiB
+// stages; rows are 64 bytes with an XOR swizzle of the 16-byte pieces that makes
+// the fragment reads conflict-free (measured: no bank-conflict cycles).  The one
+// barrier per step sits in the middle of the step: by then a wavefront holds the
+// step's second-half fragments in registers, so the stage can be refilled (for
+// three and a half steps ahead) right after the barrier, and the next step's
+// first fragments are fetched under the second half's matrix instructions.
+// The hidden tiles are split over (at least four) workgroups, and the workgroups
+// resident on one XCD form a patch of token tiles x splits that share their
+// panels through that XCD's L2; a second kernel adds the partial scores in split
+// order.  All sums have a fixed order (no atomics): run-to-run deterministic.
 //
 // Everything else (fp32 inputs, other shapes) takes a plain kernel that keeps a
 // few token rows in LDS and gives one wavefront a hidden unit at a time: correct
@@ -86,9 +91,9 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
 
   // ---- loader: per step, wavefront w brings rows 32w .. 32w+31 of the X tile and of the W1 tile,
   // 16 rows (1 KiB) per instruction; lane i sits at (row i/4, position i%4) and fetches the piece that
-  // the swizzle stores there: piece = pos ^ ((row >> 1) & 3)
+  // the swizzle stores there: piece = pos ^ ((row >> 2) & 3)
   const int l_row = lane >> 2, l_pos = lane & 3;
-  const uint32_t l_piece_bytes = static_cast<uint32_t>((l_pos ^ ((l_row >> 1) & 3)) * 16);
+  const uint32_t l_piece_bytes = static_cast<uint32_t>((l_pos ^ ((l_row >> 2) & 3)) * 16);
   uint32_t x_off[2], w_off[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
@@ -111,8 +116,8 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
     }
   };
 
-  // ---- fragment addresses: row r of a tile at r*64, piece p at (p ^ ((r >> 1) & 3)) * 16
-  const int f_sw = (j32 >> 1) & 3;
+  // ---- fragment addresses: row r of a tile at r*64, piece p at (p ^ ((r >> 2) & 3)) * 16
+  const int f_sw = (j32 >> 2) & 3;
   const int x_row_off = (64 * tg + j32) * 64;                     // token blocks tb = 0, 1: + 32*64*tb
   const int w_row_off = kOperandBytes + (128 * hg + j32) * 64;    // hidden blocks hb = 0..3: + 32*64*hb
 
@@ -128,28 +133,56 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
   };
   zero_acc();
 
+  auto issue_part = [&](int step, int q) {  // quarter q of a step's loads: (u = q / 2, operand = q % 2)
+    const int st = min(step, n_steps - 1);  // past the end: re-read the last step into a stage nobody reads any more
+    const int ht = tile0 + st / ksteps, ks = st % ksteps;
+    const uint32_t stage = lds_base + (step % kStagesG) * kStageBytesG;
+    const int u = q >> 1;
+    if ((q & 1) == 0) {
+      dma16(x_base + ks * kBK, x_off[u], __builtin_amdgcn_readfirstlane(stage + (32 * wave + 16 * u) * 64));
+    } else {
+      dma16(W1 + static_cast<int64_t>(ht) * kHidTile * d + ks * kBK, w_off[u],
+            __builtin_amdgcn_readfirstlane(stage + kOperandBytes + (32 * wave + 16 * u) * 64));
+    }
+  };
+  bf16x8 xf[2][2], wf[2][4];  // fragment sets of the two half steps
+  auto read_frags = [&](int step, int ks, bf16x8* xo, bf16x8* wo) {
+    const char* stg = lds + (step % kStagesG) * kStageBytesG;
+    const int piece = ((2 * ks + g) ^ f_sw) << 4;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) xo[tb] = *reinterpret_cast<const bf16x8*>(stg + x_row_off + tb * 2048 + piece);
+#pragma unroll
+    for (int hb = 0; hb < 4; ++hb) wo[hb] = *reinterpret_cast<const bf16x8*>(stg + w_row_off + hb * 2048 + piece);
+  };
   if (n_steps > 0) {
 #pragma unroll
-    for (int s = 0; s < kStagesG - 1; ++s) issue_step(s);
+    for (int s = 0; s < kStagesG; ++s) issue_step(s);
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kLoadsPerStep));  // step 0 has landed
+    __syncthreads();
+    read_frags(0, 0, xf[0], wf[0]);
   }
   for (int step = 0; step < n_steps; ++step) {
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * kLoadsPerStep));  // this step has landed; two younger ones may be in flight
-    __syncthreads();                                             // everyone's part has landed; the stage of step-1 is free
-    issue_step(step + kStagesG - 1);
-    const char* stg = lds + (step % kStagesG) * kStageBytesG;
+    // first half: the second half's fragments are requested, then the matrix cores work on the first half's
+    read_frags(step, 1, xf[1], wf[1]);
 #pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      const int piece = ((2 * ks + g) ^ f_sw) << 4;
-      bf16x8 xf[2], wf[4];
+    for (int hb = 0; hb < 4; ++hb)
 #pragma unroll
-      for (int tb = 0; tb < 2; ++tb) xf[tb] = *reinterpret_cast<const bf16x8*>(stg + x_row_off + tb * 2048 + piece);
+      for (int tb = 0; tb < 2; ++tb)
+        acc[hb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][hb], xf[0][tb], acc[hb][tb], 0, 0, 0);
+    // middle: this wavefront has read everything it needs of this step's stage, and its part of the next step
+    // has landed (two younger steps may be in flight); after the barrier that holds for every wavefront
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * kLoadsPerStep));
+    __syncthreads();
+    read_frags(step + 1, 0, xf[0], wf[0]);  // (after the last step: a stage that holds old data; not used)
 #pragma unroll
-      for (int hb = 0; hb < 4; ++hb) wf[hb] = *reinterpret_cast<const bf16x8*>(stg + w_row_off + hb * 2048 + piece);
+    for (int hb = 0; hb < 4; ++hb) {
 #pragma unroll
-      for (int hb = 0; hb < 4; ++hb)
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-          acc[hb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[hb], xf[tb], acc[hb][tb], 0, 0, 0);
+      for (int tb = 0; tb < 2; ++tb)
+        acc[hb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][hb], xf[1][tb], acc[hb][tb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      issue_part(step + kStagesG, hb);  // refill this step's stage
+      __builtin_amdgcn_sched_barrier(0);
     }
     if ((step + 1) % ksteps == 0) {
       // a hidden tile is complete: accumulator v of block hb is hidden unit 32 hb + 8 (v/4) + 4 g + v%4
