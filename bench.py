@@ -373,6 +373,32 @@ def main():
         kernels["meanpool_baseline"] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2),
                                         "GBps": round(mp_bytes / (sum(us) / len(us)) * 1e-3, 1)}
         D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)  # restore the cache
+        # the scorer as a 2-layer feedforward network (d -> d -> 1) over the step's hidden states
+        if E == 2:
+            d_model = g["hidden"].shape[1]
+            gen = torch.Generator(device="cpu").manual_seed(wl.seed + 77)
+            W1 = (torch.randn(d_model, d_model, generator=gen) * d_model ** -0.5).to(torch.bfloat16).to(dev)
+            b1 = (torch.randn(d_model, generator=gen) * 0.5).to(dev)
+            w2 = (torch.randn(d_model, generator=gen) * d_model ** -0.5).to(torch.bfloat16).to(dev)
+            mlp_ws = torch.empty(max(D.dodo_score_mlp_workspace_bytes(D.BF16, wl.N, d_model, d_model), 16),
+                                 dtype=torch.uint8, device=dev)
+            mlp_out = torch.empty(wl.N, dtype=torch.float32, device=dev)
+            for _ in range(2):
+                D.dodo_score_mlp(g["hidden"], W1, b1, w2, 0.0, D.RELU, mlp_out, mlp_ws)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+            for a, b in evs:
+                a.record()
+                D.dodo_score_mlp(g["hidden"], W1, b1, w2, 0.0, D.RELU, mlp_out, mlp_ws)
+                b.record()
+            torch.cuda.synchronize()
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            mlp_flop = 2.0 * wl.N * d_model * d_model
+            kernels["scorer_2layer"] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2),
+                                        "TFLOPs": round(mlp_flop / (sum(us) / len(us)) * 1e-6, 1),
+                                        "frac_of_bf16_peak": round(mlp_flop / (sum(us) / len(us)) * 1e-6 / 2500.0, 3),
+                                        "note": "ReLU, d_hid = d; replaces the linear head when used (not part of the step)"}
+            del W1, mlp_ws
         ar["note"] = ("threshold rule of the autoregressive mode, timed apart from the step: sample = the step's "
                       f"{wl.N} scores; stream_append includes a fill of the {B} counters; caches of {cap} rows per sequence")
         kernels["autoregressive_mode"] = ar

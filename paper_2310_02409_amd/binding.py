@@ -302,6 +302,10 @@ def dodo_meanpool_nuggets(K: torch.Tensor, V: torch.Tensor, cu_seqlens: torch.Te
     return Kn, Vn
 
 
+def dodo_score_mlp_workspace_bytes(dtype: int, N: int, d: int, d_hid: int) -> int:
+    return int(lib.dodo_score_mlp_workspace_bytes(dtype, N, d, d_hid))
+
+
 def dodo_score_mlp(hidden: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, w2: torch.Tensor, b2: float = 0.0,
                    act: int = RELU, out: Optional[torch.Tensor] = None,
                    ws: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -316,7 +320,7 @@ def dodo_score_mlp(hidden: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, w2:
     if out is None:
         out = torch.empty(N, dtype=torch.float32, device=hidden.device)
     code = _dtype_code(hidden)
-    need = int(lib.dodo_score_mlp_workspace_bytes(code, N, d, d_hid))
+    need = dodo_score_mlp_workspace_bytes(code, N, d, d_hid)
     if need and ws is None:
         ws = torch.empty(need, dtype=torch.uint8, device=hidden.device)
     _check(lib.dodo_score_mlp(_ptr(hidden), _ptr(W1), _ptr(b1), _ptr(w2), float(b2), act, code, N, d, d_hid,
