@@ -148,6 +148,13 @@ def suite(args):
     Kt = sum(ks)
     cu_s = W.cumulative(wl.seq_lens, dev)
     lay = [W.make_inputs(wl, dev, layer=l, which=["hidden", "w", "K", "V"]) for l in range(L)]
+    # the layers' K and V in one allocation each ([L, N, H_kv, d_h]) so that one launch can pack all of them
+    K_all = torch.empty((L,) + tuple(lay[0]["K"].shape), dtype=wl.dtype, device=dev)
+    V_all = torch.empty_like(K_all)
+    for l in range(L):
+        K_all[l].copy_(lay[l]["K"])
+        V_all[l].copy_(lay[l]["V"])
+        lay[l]["K"], lay[l]["V"] = K_all[l], V_all[l]
     scores = torch.empty((L, wl.N), dtype=torch.float32, device=dev)
     idx = torch.empty((L, Kt), dtype=torch.int32, device=dev)
     Kn = torch.empty((L, Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
@@ -169,7 +176,22 @@ def suite(args):
                            idx.view(-1))
         for l in range(L):
             D.dodo_gather_nuggets(lay[l]["K"], lay[l]["V"], idx[l], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn[l], Vn[l])
+
+    def shared_indices():
+        # the Scorer reads one fixed layer and its indices serve every layer (Sec. 2.1): 3 launches in all
+        D.dodo_score(lay[0]["hidden"], lay[0]["w"], 0.0, scores[0])
+        D.dodo_select_topk(scores[0], cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx[0])
+        D.dodo_gather_nuggets_layers(K_all, V_all, idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
+
+    def shared_indices_gather_per_layer():
+        D.dodo_score(lay[0]["hidden"], lay[0]["w"], 0.0, scores[0])
+        D.dodo_select_topk(scores[0], cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx[0])
+        for l in range(L):
+            D.dodo_gather_nuggets(lay[l]["K"], lay[l]["V"], idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn[l], Vn[l])
     E = 2
+    by3 = (wl.N * wl.d_model * E + wl.d_model * E + 4 * wl.N + 4 * wl.N + 4 * Kt) + L * 4 * Kt * wl.H_kv * wl.d_h * E
+    a3, m3 = timed(shared_indices, 5)
+    a4, m4 = timed(shared_indices_gather_per_layer, 5)
     by = L * (wl.N * wl.d_model * E + wl.d_model * E + 4 * wl.N + 4 * wl.N + 4 * Kt + 4 * Kt * wl.H_kv * wl.d_h * E)
     a1, m1 = timed(per_layer, 5)
     a2, m2 = timed(batched_select, 5)
@@ -178,9 +200,15 @@ def suite(args):
                              "GBps": round(by / a1 * 1e-3, 1)},
         "one_select_launch_for_all_layers": {"launches": 2 * L + 1, "avg_us": round(a2, 1), "min_us": round(m2, 1),
                                              "GBps": round(by / a2 * 1e-3, 1)},
-        "bytes": by, "note": "16 x 2048 tokens, d = 5120, 20x compression, per-layer scores and selections; the "
-                             "second form selects the 640 (layer, sequence) segments in one launch"}
-    del lay, Kn, Vn
+        "shared_indices_one_gather_launch": {"launches": 3, "avg_us": round(a3, 1), "min_us": round(m3, 1),
+                                             "GBps": round(by3 / a3 * 1e-3, 1), "bytes": by3},
+        "shared_indices_gather_per_layer": {"launches": L + 2, "avg_us": round(a4, 1), "min_us": round(m4, 1),
+                                            "GBps": round(by3 / a4 * 1e-3, 1), "bytes": by3},
+        "bytes": by, "note": "16 x 2048 tokens, d = 5120, 20x compression. First two forms: per-layer scores and "
+                             "selections (the second selects the 640 (layer, sequence) segments in one launch). Last "
+                             "two: one scored layer whose indices pack all 40 layers, as in the paper (Sec. 2.1), "
+                             "with one gather launch for all layers or one per layer"}
+    del lay, Kn, Vn, K_all, V_all
     torch.cuda.empty_cache()
 
     # ---- workload 5: 64 decode steps after the 1024-token prefill (the local buffer grows by one row per step)

@@ -134,6 +134,20 @@ int dodo_gather_nuggets(const void* K, const void* V, int dtype, const int32_t* 
                         const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t H_kv,
                         int32_t d_h, int64_t token_stride, void* Kn, void* Vn, int layout, void* stream);
 
+/*
+ * Sub-selection (Eq. 5) for L layers in one launch.  The Scorer reads one fixed layer and the indices it
+ * yields select the nuggets of every layer (Sec. 2.1), so the K/V of all layers are packed with the
+ * same nugget_idx / cu_nuggets: layer l reads K + l * src_layer_stride, V + l * src_layer_stride
+ * ([N, H_kv, d_h] with token_stride each) and writes Kn + l * dst_layer_stride, Vn + l * dst_layer_stride
+ * (each as dodo_gather_nuggets writes it, in `layout` with Kt rows).  Strides in elements, multiples of
+ * 16 bytes; dst_layer_stride >= Kt * H_kv * d_h; src_layer_stride may be 0 (every layer reads the same
+ * rows).  L == 0 is a no-op; L <= 65535.  Bit for bit what L calls of dodo_gather_nuggets produce.
+ */
+int dodo_gather_nuggets_layers(const void* K, const void* V, int dtype, const int32_t* nugget_idx,
+                               const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t L,
+                               int32_t H_kv, int32_t d_h, int64_t token_stride, int64_t src_layer_stride,
+                               int64_t dst_layer_stride, void* Kn, void* Vn, int layout, void* stream);
+
 /* Bytes of device workspace dodo_nugget_attention needs for these bounds (may be 0).  The workspace holds
  * the partial results of the split-K kernel and one flag word per partial.  Its contents need not be
  * initialised, with one exception: no flag word may hold the library's "ready" value 0x600DD0D0 on

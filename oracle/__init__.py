@@ -204,6 +204,14 @@ def gather(K: np.ndarray, V: np.ndarray, nugget_idx: np.ndarray, cu_seqlens: np.
     return Kn, Vn
 
 
+def gather_layers(K: np.ndarray, V: np.ndarray, nugget_idx: np.ndarray, cu_seqlens: np.ndarray, cu_nuggets: np.ndarray,
+                  layout: int = TOKEN_MAJOR):
+    """Sub-selection (Eq. 5) of K/V [L, N, H_kv, d_h]: every layer is packed with the one index list (Sec. 2.1)."""
+    assert K.ndim == 4 and K.shape == V.shape
+    per_layer = [gather(K[l], V[l], nugget_idx, cu_seqlens, cu_nuggets, layout) for l in range(K.shape[0])]
+    return np.stack([kv[0] for kv in per_layer]), np.stack([kv[1] for kv in per_layer])
+
+
 def _attn_common(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, layout):
     Q, Kn, Vn, Kl, Vl = _c(Q), _c(Kn), _c(Vn), _c(Kl), _c(Vl)
     assert Q.ndim == 3 and Kn.ndim == 3 and Kl.ndim == 3

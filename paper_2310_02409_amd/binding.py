@@ -43,6 +43,9 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_select_topk_workspace_bytes.argtypes = [i32, i32]
     L.dodo_select_topk.restype = ctypes.c_int
     L.dodo_select_topk.argtypes = [vp, vp, vp, i32, i32, i32, u32, vp, vp, sz, vp]
+    L.dodo_gather_nuggets_layers.restype = ctypes.c_int
+    L.dodo_gather_nuggets_layers.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i64, i32, i32, i32, i64, i64, i64, vp,
+                                             vp, ctypes.c_int, vp]
     L.dodo_gather_nuggets.restype = ctypes.c_int
     L.dodo_gather_nuggets.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i64, i32, i32, i64, vp, vp, ctypes.c_int,
                                       vp]
@@ -175,6 +178,31 @@ def dodo_gather_nuggets(K: torch.Tensor, V: torch.Tensor, nugget_idx: torch.Tens
     _check(lib.dodo_gather_nuggets(_ptr(K), _ptr(V), _dtype_code(K), _ptr(nugget_idx), _ptr(cu_seqlens),
                                    _ptr(cu_nuggets), B, total_nuggets, H_kv, d_h, K.stride(0), _ptr(Kn), _ptr(Vn),
                                    layout, _stream()), "dodo_gather_nuggets")
+    return Kn, Vn
+
+
+def dodo_gather_nuggets_layers(K: torch.Tensor, V: torch.Tensor, nugget_idx: torch.Tensor, cu_seqlens: torch.Tensor,
+                               cu_nuggets: torch.Tensor, total_nuggets: int, layout: int = TOKEN_MAJOR,
+                               Kn: Optional[torch.Tensor] = None, Vn: Optional[torch.Tensor] = None):
+    """Packs the chosen rows of K, V [L, N, H_kv, d_h] of all L layers (one shared index list) in one launch."""
+    _dev(nugget_idx, cu_seqlens, cu_nuggets)
+    if not (K.is_cuda and V.is_cuda):
+        raise ValueError("dodo tensors must be device tensors")
+    L, _, H_kv, d_h = K.shape
+    assert V.shape == K.shape and V.dtype == K.dtype and K.stride() == V.stride()
+    assert K.stride(3) == 1 and K.stride(2) == d_h
+    B = cu_seqlens.numel() - 1
+    shape = (L, total_nuggets, H_kv, d_h) if layout == TOKEN_MAJOR else (L, H_kv, total_nuggets, d_h)
+    if Kn is None:
+        Kn = torch.empty(shape, dtype=K.dtype, device=K.device)
+    if Vn is None:
+        Vn = torch.empty(shape, dtype=K.dtype, device=K.device)
+    assert tuple(Kn.shape) == shape and tuple(Vn.shape) == shape and Kn.stride() == Vn.stride()
+    assert Kn[0].is_contiguous() and Vn[0].is_contiguous()
+    _check(lib.dodo_gather_nuggets_layers(_ptr(K), _ptr(V), _dtype_code(K), _ptr(nugget_idx), _ptr(cu_seqlens),
+                                          _ptr(cu_nuggets), B, total_nuggets, L, H_kv, d_h, K.stride(1), K.stride(0),
+                                          Kn.stride(0), _ptr(Kn), _ptr(Vn), layout, _stream()),
+           "dodo_gather_nuggets_layers")
     return Kn, Vn
 
 

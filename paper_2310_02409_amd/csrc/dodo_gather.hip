@@ -6,6 +6,9 @@
 // (H_kv*d_h elements each, 8 KiB for LLaMA-7B in bf16) with 16-byte loads that
 // are all issued before the first store.  The destination row's sequence is
 // found by a binary search over cu_nuggets, so nothing is read back to the host.
+// dodo_gather_nuggets_layers does the same for the K/V of several layers with the
+// one index list they share (Sec. 2.1), in one launch: the grid's second
+// dimension is the layer.
 #include "dodo_common.h"
 
 namespace dodo {
@@ -18,7 +21,8 @@ template <bool HEAD_MAJOR>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const int32_t* __restrict__ nugget_idx,
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt,
-    int vec_per_head, int vec_per_row, int64_t token_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
+    int vec_per_head, int vec_per_row, int64_t token_stride_vec, int64_t src_layer_stride_vec,
+    int64_t dst_layer_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
   const int64_t dst_tok = blockIdx.x;
   if (dst_tok >= cu_nuggets[B]) return;  // Kt may be an upper bound of the nugget count
   // sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1]
@@ -29,8 +33,11 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
   const int b = lo;
   const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
-  const uint4* ksrc = K + src_tok * token_stride_vec;
-  const uint4* vsrc = V + src_tok * token_stride_vec;
+  const int64_t layer = blockIdx.y;
+  const uint4* ksrc = K + layer * src_layer_stride_vec + src_tok * token_stride_vec;
+  const uint4* vsrc = V + layer * src_layer_stride_vec + src_tok * token_stride_vec;
+  Kn += layer * dst_layer_stride_vec;
+  Vn += layer * dst_layer_stride_vec;
 
   for (int c0 = threadIdx.x; c0 < vec_per_row; c0 += kGatherThreads * kMaxVec) {
     uint4 kk[kMaxVec], vv[kMaxVec];
@@ -60,6 +67,41 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
 }
 
+int gather_entry(const void* K, const void* V, int dtype, const int32_t* nugget_idx, const int32_t* cu_seqlens,
+                 const int32_t* cu_nuggets, int32_t B, int64_t Kt, int32_t L, int32_t H_kv, int32_t d_h,
+                 int64_t token_stride, int64_t src_layer_stride, int64_t dst_layer_stride, void* Kn, void* Vn, int layout,
+                 void* stream) {
+  if (B < 0 || Kt < 0 || L < 0 || H_kv <= 0 || d_h <= 0) return DODO_ERR_INVALID_ARG;
+  if (token_stride < static_cast<int64_t>(H_kv) * d_h) return DODO_ERR_INVALID_ARG;
+  if (layout != DODO_LAYOUT_TOKEN_MAJOR && layout != DODO_LAYOUT_HEAD_MAJOR) return DODO_ERR_INVALID_ARG;
+  if (L > 1 && (src_layer_stride < 0 || dst_layer_stride < Kt * H_kv * d_h)) return DODO_ERR_INVALID_ARG;
+  if (Kt == 0 || B == 0 || L == 0) return DODO_OK;
+  if (!K || !V || !nugget_idx || !cu_seqlens || !cu_nuggets || !Kn || !Vn) return DODO_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
+  if (Kt > 0x7fffffffLL || L > 65535) return DODO_ERR_UNSUPPORTED;
+  const int es = elem_bytes(dtype);
+  if ((static_cast<int64_t>(d_h) * es) % 16 != 0 || (token_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
+  if ((src_layer_stride * es) % 16 != 0 || (dst_layer_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(Kn) || !aligned16(Vn)) return DODO_ERR_UNSUPPORTED;
+
+  const int vec_per_head = d_h * es / 16;
+  const int vec_per_row = vec_per_head * H_kv;
+  const int64_t stride_vec = token_stride * es / 16;
+  const int64_t src_l = src_layer_stride * es / 16, dst_l = dst_layer_stride * es / 16;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid(static_cast<unsigned>(Kt), static_cast<unsigned>(L)), block(kGatherThreads);
+  if (layout == DODO_LAYOUT_HEAD_MAJOR) {
+    hipLaunchKernelGGL(gather_kernel<true>, grid, block, 0, s, static_cast<const uint4*>(K),
+                       static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
+                       vec_per_row, stride_vec, src_l, dst_l, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
+  } else {
+    hipLaunchKernelGGL(gather_kernel<false>, grid, block, 0, s, static_cast<const uint4*>(K),
+                       static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
+                       vec_per_row, stride_vec, src_l, dst_l, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
+  }
+  return launch_status();
+}
+
 }  // namespace
 }  // namespace dodo
 
@@ -67,31 +109,15 @@ extern "C" int dodo_gather_nuggets(const void* K, const void* V, int dtype, cons
                                    const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt,
                                    int32_t H_kv, int32_t d_h, int64_t token_stride, void* Kn, void* Vn, int layout,
                                    void* stream) {
-  using namespace dodo;
-  if (B < 0 || Kt < 0 || H_kv <= 0 || d_h <= 0) return DODO_ERR_INVALID_ARG;
-  if (token_stride < static_cast<int64_t>(H_kv) * d_h) return DODO_ERR_INVALID_ARG;
-  if (layout != DODO_LAYOUT_TOKEN_MAJOR && layout != DODO_LAYOUT_HEAD_MAJOR) return DODO_ERR_INVALID_ARG;
-  if (Kt == 0 || B == 0) return DODO_OK;
-  if (!K || !V || !nugget_idx || !cu_seqlens || !cu_nuggets || !Kn || !Vn) return DODO_ERR_INVALID_ARG;
-  if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
-  if (Kt > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
-  const int es = elem_bytes(dtype);
-  if ((static_cast<int64_t>(d_h) * es) % 16 != 0 || (token_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
-  if (!aligned16(K) || !aligned16(V) || !aligned16(Kn) || !aligned16(Vn)) return DODO_ERR_UNSUPPORTED;
+  return dodo::gather_entry(K, V, dtype, nugget_idx, cu_seqlens, cu_nuggets, B, Kt, 1, H_kv, d_h, token_stride, 0, 0, Kn,
+                            Vn, layout, stream);
+}
 
-  const int vec_per_head = d_h * es / 16;
-  const int vec_per_row = vec_per_head * H_kv;
-  const int64_t stride_vec = token_stride * es / 16;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const dim3 grid(static_cast<unsigned>(Kt)), block(kGatherThreads);
-  if (layout == DODO_LAYOUT_HEAD_MAJOR) {
-    hipLaunchKernelGGL(gather_kernel<true>, grid, block, 0, s, static_cast<const uint4*>(K),
-                       static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
-                       vec_per_row, stride_vec, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
-  } else {
-    hipLaunchKernelGGL(gather_kernel<false>, grid, block, 0, s, static_cast<const uint4*>(K),
-                       static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
-                       vec_per_row, stride_vec, static_cast<uint4*>(Kn), static_cast<uint4*>(Vn));
-  }
-  return launch_status();
+extern "C" int dodo_gather_nuggets_layers(const void* K, const void* V, int dtype, const int32_t* nugget_idx,
+                                          const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B, int64_t Kt,
+                                          int32_t L, int32_t H_kv, int32_t d_h, int64_t token_stride,
+                                          int64_t src_layer_stride, int64_t dst_layer_stride, void* Kn, void* Vn,
+                                          int layout, void* stream) {
+  return dodo::gather_entry(K, V, dtype, nugget_idx, cu_seqlens, cu_nuggets, B, Kt, L, H_kv, d_h, token_stride,
+                            src_layer_stride, dst_layer_stride, Kn, Vn, layout, stream);
 }

@@ -28,7 +28,7 @@ def test_header_symbols_are_exported(lib):
             "dodo_version", "dodo_status_string", "dodo_select_topk_workspace_bytes",
             "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
             "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets", "dodo_score_mlp",
-            "dodo_score_mlp_workspace_bytes"} <= set(names)
+            "dodo_score_mlp_workspace_bytes", "dodo_gather_nuggets_layers"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
@@ -93,6 +93,12 @@ def test_gather_argument_validation(lib):
     assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 10, 4, 64, 100, P, P, 0, 0) == -1   # stride < H_kv*d_h
     assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 10, 4, 64, 256, P, P, 2, 0) == -1   # layout
     assert lib.dodo_gather_nuggets(P, P, 5, P, P, P, 2, 10, 4, 64, 256, P, P, 0, 0) == -2   # dtype
+    G = lib.dodo_gather_nuggets_layers
+    assert G(P, P, 1, P, P, P, 2, 10, 0, 4, 64, 256, 0, 0, P, P, 0, 0) == 0            # no layers: no-op
+    assert G(P, P, 1, P, P, P, 2, 10, -1, 4, 64, 256, 0, 0, P, P, 0, 0) == -1
+    assert G(P, P, 1, P, P, P, 2, 10, 3, 4, 64, 256, 4096, 100, P, P, 0, 0) == -1      # layers of the output overlap
+    assert G(P, P, 1, P, P, P, 2, 10, 3, 4, 64, 256, 4100, 2560, P, P, 0, 0) == -2     # layer stride not 16-byte
+    assert G(P, P, 1, P, P, P, 2, 10, 70000, 4, 64, 256, 4096, 2560, P, P, 0, 0) == -2  # too many layers
     assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 10, 4, 60, 240, P, P, 0, 0) == -2   # row not 16-byte multiple
     assert lib.dodo_gather_nuggets(P, P, 1, P, P, P, 2, 0, 4, 64, 256, P, P, 0, 0) == 0     # no nuggets: no-op
 

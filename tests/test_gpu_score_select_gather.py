@@ -157,3 +157,33 @@ def test_gather_ratio_one_is_identity(D):
     idx = torch.cat([torch.arange(n, dtype=torch.int32) for n in n_lens]).to(dev())
     Kn, Vn = D.dodo_gather_nuggets(K, V, idx, cu, cu, sum(n_lens))
     assert torch.equal(Kn, K) and torch.equal(Vn, V)
+
+
+@pytest.mark.parametrize("dtype,L,H_kv,d_h", [(torch.bfloat16, 5, 32, 128), (torch.float32, 2, 4, 64), (torch.bfloat16, 1, 3, 64)])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_gather_layers_bit_exact(D, dtype, L, H_kv, d_h, layout):
+    n_lens = [300, 1, 0, 211]
+    N = sum(n_lens)
+    K = W.normal(310, 0, (L, N, H_kv, d_h), 1.0, dtype)
+    V = W.normal(310, 1, (L, N, H_kv, d_h), 1.0, dtype)
+    k_lens, cu_k = oracle_counts(n_lens, 1, 5)
+    cu_s = oracle.cu_from_lengths(n_lens)
+    s = W.normal(310, 2, (N,), 1.0, torch.float32).numpy()
+    idx = oracle.select_topk(s, cu_s, cu_k)
+    Kn_ref, Vn_ref = oracle.gather_layers(W.to_numpy(K), W.to_numpy(V), idx, cu_s, cu_k, layout)
+    args = (torch.from_numpy(idx).to(dev()), torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()),
+            int(cu_k[-1]), layout)
+    Kn, Vn = D.dodo_gather_nuggets_layers(K.to(dev()), V.to(dev()), *args)
+    assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)
+    # strided views: a padded token stride in the source and room between the layers of the destination
+    Kp = torch.zeros((L, N, H_kv + 1, d_h), dtype=dtype, device=dev())
+    Vp = torch.zeros_like(Kp)
+    Kp[:, :, :H_kv] = K.to(dev())
+    Vp[:, :, :H_kv] = V.to(dev())
+    Kt = int(cu_k[-1])
+    shape = (Kt, H_kv, d_h) if layout == 0 else (H_kv, Kt, d_h)
+    Kbig = torch.full((L, 2) + shape, 7.0, dtype=dtype, device=dev())
+    Vbig = torch.full((L, 2) + shape, 7.0, dtype=dtype, device=dev())
+    D.dodo_gather_nuggets_layers(Kp[:, :, :H_kv], Vp[:, :, :H_kv], *args, Kn=Kbig[:, 0], Vn=Vbig[:, 0])
+    assert np.array_equal(W.to_numpy(Kbig[:, 0]), Kn_ref) and np.array_equal(W.to_numpy(Vbig[:, 0]), Vn_ref)
+    assert bool((Kbig[:, 1] == 7.0).all()) and bool((Vbig[:, 1] == 7.0).all())

@@ -51,3 +51,17 @@ def test_indices_are_sequence_local():
     Kn, _ = oracle.gather(K, K, np.array([1, 0, 2], np.int32), oracle.cu_from_lengths([4, 3]),
                           oracle.cu_from_lengths([1, 2]))
     assert list(Kn[:, 0, 0]) == [1.0, 4.0, 6.0]
+
+
+def test_layers_share_the_index_list_and_match_library_indexing():
+    # [L, N, H_kv, d_h]: every layer is indexed with the same rows (Sec. 2.1); layer l's values are offset by 1000 l
+    n_lens = [21, 40]
+    K0, V0, idx, cu_s, cu_k = _case(torch.float32, n_lens)
+    L = 3
+    K = torch.stack([K0 + 1000.0 * l for l in range(L)])
+    V = torch.stack([V0 - 1000.0 * l for l in range(L)])
+    glob = torch.from_numpy(np.concatenate([idx[cu_k[b]:cu_k[b + 1]] + cu_s[b] for b in range(2)])).long()
+    Kn, Vn = oracle.gather_layers(K.numpy(), V.numpy(), idx, cu_s, cu_k)
+    assert np.array_equal(Kn, K[:, glob].numpy()) and np.array_equal(Vn, V[:, glob].numpy())
+    Kh, Vh = oracle.gather_layers(K.numpy(), V.numpy(), idx, cu_s, cu_k, oracle.HEAD_MAJOR)
+    assert np.array_equal(Kh, Kn.transpose(0, 2, 1, 3)) and np.array_equal(Vh, Vn.transpose(0, 2, 1, 3))
