@@ -401,6 +401,31 @@ def main():
         kernels["meanpool_baseline"] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2),
                                         "GBps": round(mp_bytes / (sum(us) / len(us)) * 1e-3, 1)}
         D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)  # restore the cache
+        # gather-free attention: the nuggets are read in place through the index list (no packed cache)
+        def _timed_us(fn, reps=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for a, b in evs:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            return round(sum(us) / len(us), 2), round(us[0], 2)
+        gf = {}
+        a, m = _timed_us(lambda: D.dodo_nugget_attention_indexed(
+            g["Q"], g["K"], g["V"], idx, g["cu_seqlens"], g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k,
+            max_m, max_n, scale, O=O))
+        gf["attn_block_indexed"] = {"avg_us": a, "min_us": m}
+        a, m = _timed_us(lambda: D.dodo_nugget_attention_indexed(
+            g["Qd"], g["K"], g["V"], idx, g["cu_seqlens"], g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1, max_k,
+            max(dec_local), max_n, scale, O=Od, ws=ws))
+        gf["attn_decode_indexed"] = {"avg_us": a, "min_us": m}
+        gf["note"] = ("same results, bit for bit, as gather + attention; compare with gather + attn_block and "
+                      "gather + attn_decode above")
+        kernels["gather_free"] = gf
         # the scorer as a 2-layer feedforward network (d -> d -> 1) over the step's hidden states
         if E == 2:
             d_model = g["hidden"].shape[1]

@@ -207,6 +207,26 @@ int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, 
                                  int dtype, int layout, void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Nugget attention without a packed cache (Eq. 5 and Eq. 13 / Eq. 9 in one call): the nuggets of
+ * sequence b are read where they are, as tokens cu_seqlens[b] + nugget_idx[cu_nuggets[b] + j] of the
+ * context's K, V ([N, H_kv, d_h], token_stride elements between tokens, a multiple of 16 bytes).
+ * The result is what dodo_gather_nuggets (token-major) followed by dodo_nugget_attention gives,
+ * bit for bit; the other arguments are those of dodo_nugget_attention, and
+ * dodo_nugget_attention_workspace_bytes gives the workspace for the same bounds.  max_n is a host-
+ * side upper bound on the context length of a sequence.  Limits of the query-block kernel (bf16,
+ * d_h = 128, max_q >= 16): max_k <= 7680 (4096 when max_q <= 128), max_n * token_stride *
+ * sizeof(element) < 2^31; beyond them DODO_ERR_UNSUPPORTED (pack the cache instead).
+ * Meant for caches that are read once: a packed cache is cheaper to read again and lets the
+ * context's K/V be freed, which is the point of the method.
+ */
+int dodo_nugget_attention_indexed(const void* Q, const void* K, const void* V, const int32_t* nugget_idx,
+                                  const int32_t* cu_seqlens, const void* Kl, const void* Vl, const int32_t* cu_q,
+                                  const int32_t* cu_nuggets, const int32_t* cu_local, int32_t B, int32_t H,
+                                  int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local,
+                                  int32_t max_n, int64_t token_stride, float softmax_scale, int dtype, void* O,
+                                  float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Threshold of the autoregressive mode from sampled scores (Sec. 2.4: Lambda is set so that about
  * t/r of t tokens are kept, and is estimated by running the scorer on sampled tokens).  With
  * k = dodo_nugget_count(n, num, den), writes to *lambda_out (device, fp32) the (k+1)-th highest

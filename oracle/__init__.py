@@ -241,6 +241,13 @@ def attention(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float, layou
     return O, lse
 
 
+def attention_indexed(Q, K, V, nugget_idx, cu_seqlens, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float):
+    """Nugget attention with the nuggets named by an index list into the context's K, V [N, H_kv, d_h]: the
+    sub-selection of Eq. 5 followed by the attention of Eq. 13 / Eq. 9, as two steps."""
+    Kn, Vn = gather(K, V, nugget_idx, cu_seqlens, cu_nuggets, TOKEN_MAJOR)
+    return attention(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale, TOKEN_MAJOR)
+
+
 def attention_rows(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float, rows, layout: int = TOKEN_MAJOR):
     """Nugget attention for sampled (b, h, i) triples -> (O float64 [R,d_h], lse float64 [R])."""
     Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, Kt = _attn_common(

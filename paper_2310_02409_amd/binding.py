@@ -43,6 +43,9 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_select_topk_workspace_bytes.argtypes = [i32, i32]
     L.dodo_select_topk.restype = ctypes.c_int
     L.dodo_select_topk.argtypes = [vp, vp, vp, i32, i32, i32, u32, vp, vp, sz, vp]
+    L.dodo_nugget_attention_indexed.restype = ctypes.c_int
+    L.dodo_nugget_attention_indexed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                                i32, i64, f32, ctypes.c_int, vp, vp, vp, sz, vp]
     L.dodo_gather_nuggets_layers.restype = ctypes.c_int
     L.dodo_gather_nuggets_layers.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i64, i32, i32, i32, i64, i64, i64, vp,
                                              vp, ctypes.c_int, vp]
@@ -238,6 +241,38 @@ def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, K
                                      _ptr(cu_local), B, H, H_kv, d_h, max_q, max_k, max_local, Kt,
                                      float(softmax_scale), code, layout, _ptr(O), _ptr(lse), _ptr(ws),
                                      0 if ws is None else ws.numel(), _stream()), "dodo_nugget_attention")
+    return O, lse
+
+
+def dodo_nugget_attention_indexed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, nugget_idx: torch.Tensor,
+                                  cu_seqlens: torch.Tensor, Kl: torch.Tensor, Vl: torch.Tensor, cu_q: torch.Tensor,
+                                  cu_nuggets: torch.Tensor, cu_local: torch.Tensor, max_q: int, max_k: int,
+                                  max_local: int, max_n: int, softmax_scale: Optional[float] = None,
+                                  O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                                  want_lse: bool = False, ws: Optional[torch.Tensor] = None):
+    """dodo_nugget_attention with the nuggets read in place from the context's K, V [N, H_kv, d_h] through
+    the index list (no packed cache); returns (O, lse or None)."""
+    _dev(Q, nugget_idx, cu_seqlens, Kl, Vl, cu_q, cu_nuggets, cu_local, O, lse, ws)
+    if not (K.is_cuda and V.is_cuda) or K.stride() != V.stride() or K.stride(2) != 1 or K.stride(1) != K.shape[2]:
+        raise ValueError("K, V must be device tensors [N, H_kv, d_h] with contiguous rows and equal strides")
+    Sq, H, d_h = Q.shape
+    H_kv = K.shape[1]
+    B = cu_q.numel() - 1
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d_h)
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None and want_lse:
+        lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
+    code = _dtype_code(Q)
+    need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, code)
+    if need and ws is None:
+        ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
+    _check(lib.dodo_nugget_attention_indexed(_ptr(Q), _ptr(K), _ptr(V), _ptr(nugget_idx), _ptr(cu_seqlens), _ptr(Kl),
+                                             _ptr(Vl), _ptr(cu_q), _ptr(cu_nuggets), _ptr(cu_local), B, H, H_kv, d_h,
+                                             max_q, max_k, max_local, max_n, K.stride(0), float(softmax_scale), code,
+                                             _ptr(O), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "dodo_nugget_attention_indexed")
     return O, lse
 
 

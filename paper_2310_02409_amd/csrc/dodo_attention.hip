@@ -25,8 +25,10 @@ extern "C" size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, in
 namespace dodo {
 namespace {
 
+// nug_idx != null: the gather-free form (Kn / Vn are the context's K / V with ctx_stride elements between tokens)
 int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl, const int32_t* cu_q,
-                    const int32_t* cu_nuggets, const int32_t* nug_len, const int32_t* cu_local, int32_t B, int32_t H,
+                    const int32_t* cu_nuggets, const int32_t* nug_len, const int32_t* cu_local, const int32_t* nug_idx,
+                    const int32_t* cu_ctx, int64_t ctx_stride, int32_t max_n, int32_t B, int32_t H,
                     int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local, int64_t Kt,
                     float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws, size_t ws_bytes,
                     void* stream) {
@@ -49,8 +51,12 @@ int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* K
   AttnParams p;
   p.Q = Q; p.Kn = Kn; p.Vn = Vn; p.Kl = Kl; p.Vl = Vl;
   p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.nug_len = nug_len; p.cu_local = cu_local;
+  p.nug_idx = nug_idx; p.cu_ctx = cu_ctx; p.max_n = max_n;
   p.B = B; p.H = H; p.H_kv = H_kv; p.d_h = d_h; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
-  if (layout == DODO_LAYOUT_TOKEN_MAJOR) {
+  if (nug_idx != nullptr) {
+    p.nug_tok_stride = ctx_stride;
+    p.nug_head_stride = d_h;
+  } else if (layout == DODO_LAYOUT_TOKEN_MAJOR) {
     p.nug_tok_stride = static_cast<int64_t>(H_kv) * d_h;
     p.nug_head_stride = d_h;
   } else {
@@ -73,8 +79,9 @@ extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* 
                                      int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
                                      int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout,
                                      void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
-  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nullptr, cu_local, B, H, H_kv, d_h, max_q, max_k,
-                               max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
+  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nullptr, cu_local, nullptr, nullptr, 0, 0, B, H, H_kv,
+                               d_h, max_q, max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes,
+                               stream);
 }
 
 extern "C" int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, const void* Kl,
@@ -84,6 +91,25 @@ extern "C" int dodo_nugget_attention_cached(const void* Q, const void* Kn, const
                                             int64_t Kt, float softmax_scale, int dtype, int layout, void* O, float* lse,
                                             void* ws, size_t ws_bytes, void* stream) {
   if (B > 0 && max_q > 0 && !nugget_len) return DODO_ERR_INVALID_ARG;
-  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, nugget_start, nugget_len, cu_local, B, H, H_kv, d_h, max_q,
-                               max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
+  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, nugget_start, nugget_len, cu_local, nullptr, nullptr, 0, 0, B, H,
+                               H_kv, d_h, max_q, max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes,
+                               stream);
+}
+
+extern "C" int dodo_nugget_attention_indexed(const void* Q, const void* K, const void* V, const int32_t* nugget_idx,
+                                             const int32_t* cu_seqlens, const void* Kl, const void* Vl,
+                                             const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local,
+                                             int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q,
+                                             int32_t max_k, int32_t max_local, int32_t max_n, int64_t token_stride,
+                                             float softmax_scale, int dtype, void* O, float* lse, void* ws,
+                                             size_t ws_bytes, void* stream) {
+  if (max_n < 0 || max_k > max_n) return DODO_ERR_INVALID_ARG;
+  if (H_kv > 0 && d_h > 0 && token_stride < static_cast<int64_t>(H_kv) * d_h) return DODO_ERR_INVALID_ARG;
+  if (B > 0 && max_q > 0 && max_k > 0 && (!nugget_idx || !cu_seqlens)) return DODO_ERR_INVALID_ARG;
+  if (dodo::dtype_ok(dtype) && (token_stride * dodo::elem_bytes(dtype)) % 16 != 0) return DODO_ERR_UNSUPPORTED;
+  // without nuggets the call is the plain one (nothing is read through the index list)
+  const bool indexed = max_k > 0;
+  return dodo::attention_entry(Q, K, V, Kl, Vl, cu_q, cu_nuggets, nullptr, cu_local, indexed ? nugget_idx : nullptr,
+                               indexed ? cu_seqlens : nullptr, token_stride, max_n, B, H, H_kv, d_h, max_q, max_k,
+                               max_local, 0, softmax_scale, dtype, DODO_LAYOUT_TOKEN_MAJOR, O, lse, ws, ws_bytes, stream);
 }

@@ -8,6 +8,10 @@ struct AttnParams {
   const void *Q, *Kn, *Vn, *Kl, *Vl;
   const int32_t *cu_q, *cu_nuggets, *cu_local;
   const int32_t* nug_len;  // null: nuggets of sequence b are rows cu_nuggets[b] .. cu_nuggets[b+1]; else cu_nuggets[b] .. + nug_len[b]
+  // gather-free form (both null otherwise): Kn / Vn are the context's K / V, nugget j of sequence b is its token
+  // cu_ctx[b] + nug_idx[cu_nuggets[b] + j]
+  const int32_t *nug_idx, *cu_ctx;
+  int32_t max_n;  // gather-free form: host-side upper bound on the context length of a sequence
   int32_t B, H, H_kv, d_h, max_q, max_k, max_local;
   int64_t nug_tok_stride, nug_head_stride;  // elements between tokens / KV heads of the nugget cache
   float scale_log2e;                        // softmax_scale * log2(e): logits are kept in base 2

@@ -112,6 +112,36 @@ struct TileLoader {
       dma16(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
+  // The same three with the rows taken through an index list: row r of the tile is token idx[r] of `base`
+  // (idx points into LDS at the tile's first entry).
+  __device__ __forceinline__ void issue_idx(const uint16_t* kbase, const uint16_t* vbase, uint32_t stride_bytes, int cnt,
+                                            uint32_t lds_k, uint32_t lds_v, const int32_t* idx) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const int row = row0 + 4 * u;
+      const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
+      const uint32_t k_piece_bytes = (pos ^ (row & 15)) * 16u;
+      dma16(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
+      dma16(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
+    }
+  }
+  __device__ __forceinline__ void issue_rows_v_idx(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst,
+                                                   const int32_t* idx) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const uint32_t roff = static_cast<uint32_t>(idx[min(row0 + 4 * u, cnt - 1)]) * stride_bytes;
+      dma16(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+    }
+  }
+  __device__ __forceinline__ void issue_rows_idx(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst,
+                                                 const int32_t* idx) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const int row = row0 + 4 * u;
+      const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
+      dma16(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+    }
+  }
 };
 
 // Online-softmax update of one 32-row block for one 64-key tile.  acc holds the raw
@@ -211,15 +241,20 @@ struct BlockCfg {
   static constexpr int kStages = NW == 4 ? 2 : 4;  // K/V tiles resident in LDS
   static constexpr int kLdsBytes = kStages * 2 * kTileBytes;
   static constexpr int kMinBlocks = NW == 4 ? 2 : 1;
+  // gather-free form: the sequence's index list sits in LDS after the stages (160 KiB per compute unit in all)
+  static constexpr int kIdxCap = NW == 4 ? 4096 : 7680;  // (the 8-wavefront kernel has 1 KiB of static LDS besides)
+  static constexpr int kIdxBytes = kIdxCap * 4;
 };
 
 // One query block (kBM rows) of one (sequence, head); called by the whole workgroup.
-template <int NW>
+// IDX: Kn / Vn are the context's K / V and nugget j of sequence b is its token cu_ctx[b] + nug_idx[cu_nuggets[b] + j].
+template <int NW, bool IDX>
 __device__ __forceinline__ void attend_query_block(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, int H, int H_kv, int bh, int qblk,
+    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ nug_idx, const int32_t* __restrict__ cu_ctx,
+    int H, int H_kv, int bh, int qblk,
     int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse) {
   using Cfg = BlockCfg<NW>;
@@ -254,8 +289,16 @@ __device__ __forceinline__ void attend_query_block(
   const int n_loc_tiles = (wg_vis + kBN - 1) / kBN;
   const int n_tiles = n_nug_tiles + n_loc_tiles;
 
-  const uint16_t* nugK = Kn + static_cast<int64_t>(k0) * nug_tok_stride + static_cast<int64_t>(kvh) * nug_head_stride;
-  const uint16_t* nugV = Vn + static_cast<int64_t>(k0) * nug_tok_stride + static_cast<int64_t>(kvh) * nug_head_stride;
+  const int64_t nug_row0 = IDX ? cu_ctx[b] : k0;  // IDX: the index list holds tokens of the sequence that starts here
+  const uint16_t* nugK = Kn + nug_row0 * nug_tok_stride + static_cast<int64_t>(kvh) * nug_head_stride;
+  const uint16_t* nugV = Vn + nug_row0 * nug_tok_stride + static_cast<int64_t>(kvh) * nug_head_stride;
+  const int32_t* idx_l = reinterpret_cast<const int32_t*>(lds + Cfg::kLdsBytes);
+  if (IDX) {
+    // (a previous query block of this workgroup is past its last tile request: the caller's barrier)
+    int32_t* dst = reinterpret_cast<int32_t*>(lds + Cfg::kLdsBytes);
+    for (int t = threadIdx.x; t < min(k_b, Cfg::kIdxCap); t += Cfg::kThreads) dst[t] = nug_idx[k0 + t];
+    __syncthreads();
+  }
   const int64_t loc_stride = static_cast<int64_t>(H_kv) * kDH;
   const uint16_t* locK = Kl + (static_cast<int64_t>(l0) * H_kv + kvh) * kDH;
   const uint16_t* locV = Vl + (static_cast<int64_t>(l0) * H_kv + kvh) * kDH;
@@ -271,9 +314,14 @@ __device__ __forceinline__ void attend_query_block(
     const int base = nug ? tl * kBN : (tl - n_nug_tiles) * kBN;
     const int cnt = min(kBN, (nug ? k_b : wg_vis) - base);
     const int64_t stride = nug ? nug_tok_stride : loc_stride;
-    loader.issue((nug ? nugK : locK) + base * stride, (nug ? nugV : locV) + base * stride,
-                 static_cast<uint32_t>(stride) * 2u, cnt, lds_base + (2 * stage) * kTileBytes,
-                 lds_base + (2 * stage + 1) * kTileBytes);
+    if (IDX && nug) {
+      loader.issue_idx(nugK, nugV, static_cast<uint32_t>(stride) * 2u, cnt, lds_base + (2 * stage) * kTileBytes,
+                       lds_base + (2 * stage + 1) * kTileBytes, idx_l + base);
+    } else {
+      loader.issue((nug ? nugK : locK) + base * stride, (nug ? nugV : locV) + base * stride,
+                   static_cast<uint32_t>(stride) * 2u, cnt, lds_base + (2 * stage) * kTileBytes,
+                   lds_base + (2 * stage + 1) * kTileBytes);
+    }
   };
   // per-tile bookkeeping shared by the phases
   struct TileInfo {
@@ -501,7 +549,15 @@ __device__ __forceinline__ void attend_query_block(
       const int base = nug ? tl * kBN : (tl - n_nug_tiles) * kBN;
       const int cnt = min(kBN, (nug ? k_b : wg_vis) - base);
       const int64_t stride = nug ? nug_tok_stride : loc_stride;
-      if (IS_V) {
+      if (IDX && nug) {
+        if (IS_V) {
+          half_loader.issue_rows_v_idx(nugV, static_cast<uint32_t>(stride) * 2u, cnt,
+                                       lds_base + (2 * stage + 1) * kTileBytes, idx_l + base);
+        } else {
+          half_loader.issue_rows_idx(nugK, static_cast<uint32_t>(stride) * 2u, cnt, lds_base + (2 * stage) * kTileBytes,
+                                     idx_l + base);
+        }
+      } else if (IS_V) {
         half_loader.issue_rows_v((nug ? nugV : locV) + base * stride, static_cast<uint32_t>(stride) * 2u, cnt,
                                  lds_base + (2 * stage + 1) * kTileBytes);
       } else {
@@ -641,12 +697,13 @@ __device__ __forceinline__ void attend_query_block(
 // after the other: a block i from the end and a block i from the start, so that under the causal
 // mask all workgroups carry the same load (new workgroups are handed out in order, and a compute
 // unit that finishes early is not refilled before the ones ahead of it in that order).
-template <int NW>
+template <int NW, bool IDX>
 __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) void block_attention_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, int B, int H, int H_kv, int n_qblocks, int pair, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
+    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ nug_idx, const int32_t* __restrict__ cu_ctx,
+    int B, int H, int H_kv, int n_qblocks, int pair, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
     uint16_t* __restrict__ O, float* __restrict__ lse) {
   const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -671,12 +728,12 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       bh2 = bh_other;
     }
   }
-  attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, H, H_kv, bh1, q1, nug_tok_stride,
-                         nug_head_stride, scale_log2e, O, lse);
+  attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, nug_idx, cu_ctx, H, H_kv, bh1, q1,
+                              nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
   if (q2 >= 0) {
     __syncthreads();  // the first block's use of LDS is over
-    attend_query_block<NW>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, H, H_kv, bh2, q2, nug_tok_stride,
-                           nug_head_stride, scale_log2e, O, lse);
+    attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, nug_idx, cu_ctx, H, H_kv, bh2,
+                                q2, nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
   }
 }
 
@@ -687,24 +744,27 @@ int compute_units() {
   return cus;
 }
 
-template <int NW>
+template <int NW, bool IDX>
 int launch_nw(const AttnParams& p) {
   using Cfg = BlockCfg<NW>;
+  if (IDX && p.max_k > Cfg::kIdxCap) return DODO_ERR_UNSUPPORTED;
+  constexpr int kLds = Cfg::kLdsBytes + (IDX ? Cfg::kIdxBytes : 0);
   const int n_qblocks = (p.max_q + Cfg::kBM - 1) / Cfg::kBM;
   // pairs of query blocks per workgroup, if that still leaves a workgroup for every compute unit
   const int64_t bh8 = (static_cast<int64_t>(p.B) * p.H + 7) / 8 * 8;
   const int pair = (n_qblocks >= 2 && bh8 * ((n_qblocks + 1) / 2) >= compute_units()) ? 1 : 0;
   const int64_t grid = bh8 * (pair ? (n_qblocks + 1) / 2 : n_qblocks);
   if (grid > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
-  auto kern = block_attention_kernel<NW>;
-  if (Cfg::kLdsBytes > 64 * 1024) {
+  auto kern = block_attention_kernel<NW, IDX>;
+  if (kLds > 64 * 1024) {
     DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     Cfg::kLdsBytes));
+                                     kLds));
   }
-  hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(Cfg::kThreads), Cfg::kLdsBytes, p.stream,
+  hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(Cfg::kThreads), kLds, p.stream,
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
-                     static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.B, p.H, p.H_kv, n_qblocks, pair,
+                     static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.nug_idx, p.cu_ctx, p.B, p.H, p.H_kv,
+                     n_qblocks, pair,
                      p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, static_cast<uint16_t*>(p.O), p.lse);
   return launch_status();
 }
@@ -717,8 +777,13 @@ int launch_block_attention(const AttnParams& p) {
   if (p.nug_tok_stride * 2 * kBN > 0x7fffffffLL || static_cast<int64_t>(p.H_kv) * kDH * 2 * kBN > 0x7fffffffLL ||
       static_cast<int64_t>(p.H) * kDH * 2 * kBN > 0x7fffffffLL)
     return DODO_ERR_UNSUPPORTED;
-  if (p.max_q > 128) return launch_nw<8>(p);
-  return launch_nw<4>(p);
+  if (p.nug_idx != nullptr) {
+    // a token's byte offset from its sequence's first row is kept in 32 bits as well
+    if (static_cast<int64_t>(p.max_n) * p.nug_tok_stride * 2 > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
+    return p.max_q > 128 ? launch_nw<8, true>(p) : launch_nw<4, true>(p);
+  }
+  if (p.max_q > 128) return launch_nw<8, false>(p);
+  return launch_nw<4, false>(p);
 }
 
 }  // namespace dodo

@@ -48,13 +48,16 @@ __host__ __device__ constexpr int partial_floats() { return DH + 2; }
 constexpr uint32_t kPartialReady = 0x600DD0D0u;  // flag value of a record that has been written
 constexpr int kMaxPolls = 1 << 17;               // bound of the combiner's wait (~0.1 s, never reached in a healthy run)
 
-template <int DTYPE, int DH, int kThreads>
+// INDEXED: Kn / Vn are the context's K / V ([N, H_kv, DH], nug_tok_stride between tokens) and nugget j of
+// sequence b is token cu_ctx[b] + nug_idx[cu_nuggets[b] + j] of it (no packed cache has been made).
+template <int DTYPE, int DH, int kThreads, bool INDEXED>
 __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const void* __restrict__ Q, const void* __restrict__ Kn, const void* __restrict__ Vn,
     const void* __restrict__ Kl, const void* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, int H, int H_kv, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, void* __restrict__ O,
-    float* __restrict__ lse, float* __restrict__ ws) {
+    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ nug_idx, const int32_t* __restrict__ cu_ctx,
+    int H, int H_kv, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
+    void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws) {
   using VT = Vec16<DTYPE>;
   constexpr int kEPL = VT::kElems;          // elements per lane
   constexpr int kLPR = DH / kEPL;           // lanes per K/V row
@@ -103,9 +106,19 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) o[e] = 0.f;
 
+  const int64_t ctx0 = INDEXED ? cu_ctx[b] : 0;
   for (int j0 = r0; j0 < r1; j0 += kGroups * kRowsInFlight) {
     uint4 kv[kRowsInFlight], vv[kRowsInFlight];
     bool valid[kRowsInFlight];
+    int tok[kRowsInFlight];  // INDEXED: sequence-local token of a nugget row (all index loads go out before the rows')
+    if (INDEXED) {
+#pragma unroll
+      for (int u = 0; u < kRowsInFlight; ++u) {
+        const int jr = j0 + u * kGroups + g;
+        const int j = jr < r1 ? jr : r1 - 1;
+        tok[u] = j < k_b ? nug_idx[k0 + j] : 0;
+      }
+    }
 #pragma unroll
     for (int u = 0; u < kRowsInFlight; ++u) {
       // loads are unconditional (rows past the end re-read the last row of the range and are
@@ -114,7 +127,8 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
       valid[u] = jr < r1;
       const int j = valid[u] ? jr : r1 - 1;
       const bool nug = j < k_b;
-      const int64_t off = nug ? (static_cast<int64_t>(k0 + j) * nug_tok_stride + nug_base) * kEs
+      const int64_t nug_row = INDEXED ? ctx0 + tok[u] : static_cast<int64_t>(k0 + j);
+      const int64_t off = nug ? (nug_row * nug_tok_stride + nug_base) * kEs
                               : (static_cast<int64_t>(l0 + j - k_b) * H_kv * DH + loc_base) * kEs;
       kv[u] = load16_stream(static_cast<const char*>(nug ? Kn : Kl) + off);
       vv[u] = load16_stream(static_cast<const char*>(nug ? Vn : Vl) + off);
@@ -270,21 +284,21 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   }
 }
 
-template <int DTYPE, int DH>
+template <int DTYPE, int DH, bool INDEXED>
 int launch_t(const AttnParams& p, int nsplit) {
   const int64_t rows = static_cast<int64_t>(p.B) * p.max_q * p.H;
   // few workgroups (about one per CU) with many rows each: 16 wavefronts per workgroup keep enough
   // loads in flight; otherwise 4 wavefronts and several workgroups per CU
   const bool wide = rows * nsplit <= 512 && static_cast<int64_t>(p.max_k) + p.max_local >= 512;
   if (wide) {
-    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024>), dim3(static_cast<unsigned>(rows * nsplit)),
-                       dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.H,
-                       p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
+    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
+                       dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local,
+                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws));
   } else {
-    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256>), dim3(static_cast<unsigned>(rows * nsplit)),
-                       dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.H,
-                       p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
+    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
+                       dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local,
+                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws));
   }
   return launch_status();
@@ -311,12 +325,13 @@ size_t splitk_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, 
 int launch_splitk_attention(const AttnParams& p) {
   const int nsplit = splitk_count(p.B, p.H, p.max_q, p.max_k, p.max_local);
   if (static_cast<int64_t>(p.B) * p.max_q * p.H * nsplit > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
+  const bool indexed = p.nug_idx != nullptr;
   if (p.dtype == DODO_DTYPE_BF16) {
-    if (p.d_h == 128) return launch_t<DODO_DTYPE_BF16, 128>(p, nsplit);
-    if (p.d_h == 64) return launch_t<DODO_DTYPE_BF16, 64>(p, nsplit);
+    if (p.d_h == 128) return indexed ? launch_t<DODO_DTYPE_BF16, 128, true>(p, nsplit) : launch_t<DODO_DTYPE_BF16, 128, false>(p, nsplit);
+    if (p.d_h == 64) return indexed ? launch_t<DODO_DTYPE_BF16, 64, true>(p, nsplit) : launch_t<DODO_DTYPE_BF16, 64, false>(p, nsplit);
   } else {
-    if (p.d_h == 128) return launch_t<DODO_DTYPE_F32, 128>(p, nsplit);
-    if (p.d_h == 64) return launch_t<DODO_DTYPE_F32, 64>(p, nsplit);
+    if (p.d_h == 128) return indexed ? launch_t<DODO_DTYPE_F32, 128, true>(p, nsplit) : launch_t<DODO_DTYPE_F32, 128, false>(p, nsplit);
+    if (p.d_h == 64) return indexed ? launch_t<DODO_DTYPE_F32, 64, true>(p, nsplit) : launch_t<DODO_DTYPE_F32, 64, false>(p, nsplit);
   }
   return DODO_ERR_UNSUPPORTED;
 }

@@ -28,7 +28,8 @@ def test_header_symbols_are_exported(lib):
             "dodo_version", "dodo_status_string", "dodo_select_topk_workspace_bytes",
             "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
             "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets", "dodo_score_mlp",
-            "dodo_score_mlp_workspace_bytes", "dodo_gather_nuggets_layers"} <= set(names)
+            "dodo_score_mlp_workspace_bytes", "dodo_gather_nuggets_layers",
+            "dodo_nugget_attention_indexed"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
@@ -143,3 +144,17 @@ def test_threshold_path_argument_validation(lib):
     assert call(B=-1) == -1 and call(stride=100) == -1 and call(cap=-1) == -1
     assert call(dtype=7) == -2 and call(d_h=3, H_kv=1, stride=3) == -2
     assert call(B=0) == 0
+
+
+def test_indexed_attention_argument_validation(lib):
+    A = lib.dodo_nugget_attention_indexed
+    #  Q  K  V idx cu_s Kl Vl cu_q cu_k cu_l  B  H H_kv d_h  mq  mk  ml  max_n stride scale dtype O lse ws ws_bytes stream
+    assert A(P, P, P, 0, P, P, P, P, P, P, 2, 4, 4, 128, 1, 10, 5, 100, 512, 0.1, 1, P, 0, 0, 0, 0) == -1  # no index list
+    assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 1, 10, 5, 9, 512, 0.1, 1, P, 0, 0, 0, 0) == -1   # max_k > max_n
+    assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 1, 10, 5, 100, 500, 0.1, 1, P, 0, 0, 0, 0) == -1  # stride < H_kv d_h
+    assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 1, 10, 5, 100, 516, 0.1, 1, P, 0, 0, 0, 0) == -2  # stride not 16-byte
+    assert A(0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 4, 4, 128, 1, 10, 5, 100, 512, 0.1, 1, 0, 0, 0, 0, 0) == 0   # B == 0
+    # query-block kernel: index list longer than its LDS buffer, and byte offsets beyond 31 bits
+    assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 256, 7681, 5, 9000, 512, 0.1, 1, P, 0, 0, 0, 0) == -2
+    assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 64, 4097, 5, 9000, 512, 0.1, 1, P, 0, 0, 0, 0) == -2
+    assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 256, 10, 5, 3000000, 512, 0.1, 1, P, 0, 0, 0, 0) == -2

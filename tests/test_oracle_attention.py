@@ -177,3 +177,39 @@ def test_whole_path_at_ratio_one_is_causal_attention_on_uncompressed_kv():
     want = dense_masked_softmax(t["Q"], t["K"], t["V"], t["Kl"], t["Vl"],
                                 (n["cu_q"], n["cu_seqlens"], n["cu_local"]), 0.25)
     assert np.allclose(O, want, rtol=1e-12, atol=1e-13)
+
+
+def test_indexed_form_is_masked_attention_over_the_uncompressed_context():
+    # Attention over [all context tokens ; local rows] in float64 with every context token that is not a nugget
+    # masked out never forms a packed cache, yet must give the same rows (softmax ignores the order of keys).
+    n_lens, q_lens, H, H_kv, d_h = [50, 23], [6, 3], 4, 2, 8
+    m_lens = [9, 3]
+    N = sum(n_lens)
+    K = W.normal(77, 0, (N, H_kv, d_h), 1.0, torch.float32)
+    V = W.normal(77, 1, (N, H_kv, d_h), 1.0, torch.float32)
+    Q = W.normal(77, 2, (sum(q_lens), H, d_h), 1.0, torch.float32)
+    Kl = W.normal(77, 3, (sum(m_lens), H_kv, d_h), 1.0, torch.float32)
+    Vl = W.normal(77, 4, (sum(m_lens), H_kv, d_h), 1.0, torch.float32)
+    s = W.normal(77, 5, (N,), 1.0, torch.float32).numpy()
+    k_lens = [oracle.nugget_count(n, 1, 5) for n in n_lens]
+    cu_s, cu_k = oracle.cu_from_lengths(n_lens), oracle.cu_from_lengths(k_lens)
+    cu_q, cu_l = oracle.cu_from_lengths(q_lens), oracle.cu_from_lengths(m_lens)
+    idx = oracle.select_topk(s, cu_s, cu_k)
+    scale = 0.3
+    O, lse = oracle.attention_indexed(Q.numpy(), K.numpy(), V.numpy(), idx, cu_s, Kl.numpy(), Vl.numpy(), cu_q, cu_k,
+                                      cu_l, scale)
+    for b in range(2):
+        chosen = torch.zeros(n_lens[b], dtype=torch.bool)
+        chosen[torch.from_numpy(idx[cu_k[b]:cu_k[b + 1]]).long()] = True
+        for h in range(H):
+            kvh = h // (H // H_kv)
+            keys = torch.cat([K[cu_s[b]:cu_s[b + 1], kvh], Kl[cu_l[b]:cu_l[b + 1], kvh]]).double()
+            vals = torch.cat([V[cu_s[b]:cu_s[b + 1], kvh], Vl[cu_l[b]:cu_l[b + 1], kvh]]).double()
+            for i in range(q_lens[b]):
+                vis_local = torch.arange(m_lens[b]) <= m_lens[b] - q_lens[b] + i
+                mask = torch.cat([chosen, vis_local])
+                logits = (keys @ Q[cu_q[b] + i, h].double()) * scale
+                logits[~mask] = -float("inf")
+                p = torch.softmax(logits, 0)
+                assert np.allclose(O[cu_q[b] + i, h], (p @ vals).numpy(), rtol=1e-12, atol=1e-13)
+                assert np.isclose(lse[cu_q[b] + i, h], torch.logsumexp(logits, 0).item(), rtol=1e-12)
