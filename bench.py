@@ -245,6 +245,42 @@ def suite(args):
         "frac_of_8TBps": round(by / avg * 1e-3 / HBM_PEAK_GBS, 4),
         "note": "2 sequences, 3277 nuggets each, local buffer 1024 + t + 1 rows at step t; the same 107 MB nugget "
                 "cache is re-read every step and stays in the 256 MB last-level cache, so this is not an HBM figure"}
+    del Kn, Vn, Kl, Vl, wins
+    torch.cuda.empty_cache()
+
+    # ---- segment form of the autoregressive objective: workload 2's 8 x 4096 tokens as 64 segments of 512 tokens
+    # that see the nuggets before (segment start - 128) and the uncompressed tokens from there on
+    wl = W.config(2)
+    B, seg_len, tau = wl.B, 512, 128
+    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
+    Kt = sum(ks)
+    cu_s = W.cumulative(wl.seq_lens, dev)
+    mk = lambda tid, n, h: W.normal(wl.seed, tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
+    Q, K, V = mk(300, wl.N, wl.H), mk(301, wl.N, wl.H_kv), mk(302, wl.N, wl.H_kv)
+    Kn, Vn = mk(303, Kt, wl.H_kv), mk(304, Kt, wl.H_kv)
+    sc = W.normal(wl.seed, 305, (wl.N,), 1.0, torch.float32, dev)
+    idx = torch.empty(Kt, dtype=torch.int32, device=dev)
+    D.dodo_select_topk(sc, cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx)
+    E = sum(-(-n // seg_len) for n in wl.seq_lens)
+    plan = D.dodo_segment_plan(idx, cu_s, cu_k, seg_len, tau, E)
+    O = torch.empty_like(Q)
+    a_plan, m_plan = timed(lambda: D.dodo_segment_plan(idx, cu_s, cu_k, seg_len, tau, E), 10)
+    a_att, m_att = timed(lambda: D.dodo_nugget_attention_segments(Q, Kn, Vn, K, V, plan[0], plan[1], plan[2], plan[3],
+                                                                  plan[4], seg_len, max(ks), seg_len + tau, scale,
+                                                                  D.TOKEN_MAJOR, O), 10)
+    cu_q_h, nl_h, ll_h = plan[0].cpu().tolist(), plan[2].cpu().tolist(), plan[4].cpu().tolist()
+    pairs = 0
+    for e in range(E):
+        q = cu_q_h[e + 1] - cu_q_h[e]
+        pairs += q * nl_h[e] + sum(min(ll_h[e], ll_h[e] - q + i + 1) for i in range(q))
+    flop = 4.0 * pairs * wl.d_h * wl.H
+    out["segment_form_8x4096_seg512_tau128"] = {
+        "entries": E, "plan_avg_us": round(a_plan, 1), "attention_avg_us": round(a_att, 1),
+        "attention_min_us": round(m_att, 1), "visible_pairs_per_head": pairs,
+        "TFLOPs": round(flop / a_att * 1e-6, 1), "frac_of_bf16_peak": round(flop / a_att * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "query_tokens_per_s": round(wl.N / a_att * 1e6),
+        "note": "forward attention of the training-time segment mask (Sec. 2.4): 32 heads x 128, 10x compression; "
+                "every token of the 8 texts is a query row"}
     print(json.dumps(out))
 
 

@@ -227,6 +227,43 @@ int dodo_nugget_attention_indexed(const void* Q, const void* K, const void* V, c
                                   float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Segment form of the autoregressive objective (Sec. 2.4, "Learning"): a text is chunked into
+ * segments of seg_len tokens, and the tokens of segment c share the splitting index
+ * t_c = max(0, c * seg_len - tau): they see the nuggets among the text's first t_c tokens and,
+ * causally, its uncompressed tokens from t_c on.  dodo_segment_plan writes one entry per segment,
+ * texts in order, segments in order (text b owns ceil(n_b / seg_len) entries):
+ *   seg_cu_q[e]      first query row (= first token of the segment in the packed token arrays);
+ *                    seg_cu_q[capacity] = N closes the cumulative array
+ *   seg_nug_start[e] = cu_nuggets[b];  seg_nug_len[e] = number of the text's nuggets with index < t_c
+ *   seg_loc_start[e] = cu_seqlens[b] + t_c;  seg_loc_len[e] = (end of the segment) - t_c
+ * nugget_idx / cu_nuggets are the text's nuggets as dodo_select_topk or dodo_select_threshold write
+ * them (ascending).  capacity >= the number of segments (a host value: the sum of ceil(n_b / seg_len));
+ * entries beyond the last segment come out empty (no query rows); n_segments_out (device, optional)
+ * receives the actual number, so that a capacity that was too small can be detected.  All arrays are
+ * device int32: [capacity + 1] for seg_cu_q, [capacity] for the others.
+ */
+int dodo_segment_plan(const int32_t* nugget_idx, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
+                      int32_t seg_len, int32_t tau, int32_t capacity, int32_t* seg_cu_q, int32_t* seg_nug_start,
+                      int32_t* seg_nug_len, int32_t* seg_loc_start, int32_t* seg_loc_len, int32_t* n_segments_out,
+                      void* stream);
+
+/*
+ * Nugget attention over the entries of dodo_segment_plan (or any other ranges of that form): entry e
+ * has query rows seg_cu_q[e] .. seg_cu_q[e+1] of Q, the nuggets seg_nug_start[e] .. + seg_nug_len[e]
+ * of the cache Kn / Vn (`layout`, Kt rows), and the local rows seg_loc_start[e] .. + seg_loc_len[e] of
+ * K / V ([N, H_kv, d_h] contiguous: the text's own uncompressed keys and values), under the same
+ * bottom-right aligned causal rule as dodo_nugget_attention.  Ranges of different entries may overlap.
+ * max_q / max_k / max_local bound the three lengths (for a plan: seg_len, the largest nugget count of
+ * a text, seg_len + tau).  Everything else as in dodo_nugget_attention.
+ */
+int dodo_nugget_attention_segments(const void* Q, const void* Kn, const void* Vn, const void* K, const void* V,
+                                   const int32_t* seg_cu_q, const int32_t* seg_nug_start, const int32_t* seg_nug_len,
+                                   const int32_t* seg_loc_start, const int32_t* seg_loc_len, int32_t n_segments,
+                                   int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
+                                   int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout, void* O,
+                                   float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Threshold of the autoregressive mode from sampled scores (Sec. 2.4: Lambda is set so that about
  * t/r of t tokens are kept, and is estimated by running the scorer on sampled tokens).  With
  * k = dodo_nugget_count(n, num, den), writes to *lambda_out (device, fp32) the (k+1)-th highest

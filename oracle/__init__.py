@@ -72,6 +72,15 @@ def _c(a, dtype=None):
     return a
 
 
+def _to_f64(a: np.ndarray) -> np.ndarray:
+    """float32 values, or bf16 values given as their uint16 bits, as float64 (exact)."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert a.dtype == np.float32
+    return a.astype(np.float64)
+
+
 def nugget_count(n: int, num: int, den: int) -> int:
     """k = clamp(ceil(n * num / den), 1, n); 0 for an empty context (Sec. 2.3, Eq. 7)."""
     return int(_load().oracle_nugget_count(int(n), int(num), int(den)))
@@ -246,6 +255,56 @@ def attention_indexed(Q, K, V, nugget_idx, cu_seqlens, Kl, Vl, cu_q, cu_nuggets,
     sub-selection of Eq. 5 followed by the attention of Eq. 13 / Eq. 9, as two steps."""
     Kn, Vn = gather(K, V, nugget_idx, cu_seqlens, cu_nuggets, TOKEN_MAJOR)
     return attention(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale, TOKEN_MAJOR)
+
+
+def segment_plan(nugget_idx, cu_seqlens, cu_nuggets, seg_len: int, tau: int):
+    """Entries of the segment form of the autoregressive objective (Sec. 2.4, "Learning"): the tokens of segment c
+    of a text share the splitting index t = max(0, c seg_len - tau).  Returns int32 arrays
+    (seg_cu_q [E+1], nug_start, nug_len, loc_start, loc_len [E]), texts in order, segments in order."""
+    cu_q, ns, nl, ls, ll = [], [], [], [], []
+    B = len(cu_seqlens) - 1
+    for b in range(B):
+        s0, n = int(cu_seqlens[b]), int(cu_seqlens[b + 1] - cu_seqlens[b])
+        idx = [int(i) for i in nugget_idx[cu_nuggets[b]:cu_nuggets[b + 1]]]
+        c = 0
+        while c * seg_len < n:
+            t = max(0, c * seg_len - tau)
+            cu_q.append(s0 + c * seg_len)
+            ns.append(int(cu_nuggets[b]))
+            nl.append(sum(1 for i in idx if i < t))
+            ls.append(s0 + t)
+            ll.append(min((c + 1) * seg_len, n) - t)
+            c += 1
+    cu_q.append(int(cu_seqlens[B]))
+    return tuple(np.asarray(a, dtype=np.int32) for a in (cu_q, ns, nl, ls, ll))
+
+
+def attention_segment_mask(Q, Kn, Vn, K, V, nugget_idx, cu_seqlens, cu_nuggets, seg_len: int, tau: int, scale: float):
+    """Attention under the segment form of the autoregressive objective (Sec. 2.4, Eq. 9 with a splitting index
+    shared by the tokens of a segment), one query token at a time: token i of a text, in segment c = i // seg_len
+    with t = max(0, c seg_len - tau), attends over the text's nuggets whose index is below t (rows of the packed,
+    token-major Kn / Vn) and the text's own tokens t .. i (rows of K / V).  Returns (O, lse) in float64."""
+    Q, Kn, Vn, K, V = (_to_f64(a) for a in (Q, Kn, Vn, K, V))
+    N, H, d_h = Q.shape
+    H_kv = K.shape[1]
+    O = np.zeros((N, H, d_h))
+    lse = np.zeros((N, H))
+    for b in range(len(cu_seqlens) - 1):
+        s0, n = int(cu_seqlens[b]), int(cu_seqlens[b + 1] - cu_seqlens[b])
+        k0, k1 = int(cu_nuggets[b]), int(cu_nuggets[b + 1])
+        for i in range(n):
+            t = max(0, (i // seg_len) * seg_len - tau)
+            nug_rows = [k0 + j for j in range(k1 - k0) if nugget_idx[k0 + j] < t]
+            for h in range(H):
+                kvh = h // (H // H_kv)
+                keys = np.concatenate([Kn[nug_rows, kvh], K[s0 + t:s0 + i + 1, kvh]])
+                vals = np.concatenate([Vn[nug_rows, kvh], V[s0 + t:s0 + i + 1, kvh]])
+                logits = scale * (keys @ Q[s0 + i, h])
+                m = logits.max()
+                p = np.exp(logits - m)
+                O[s0 + i, h] = (p @ vals) / p.sum()
+                lse[s0 + i, h] = m + np.log(p.sum())
+    return O, lse
 
 
 def attention_rows(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float, rows, layout: int = TOKEN_MAJOR):

@@ -43,6 +43,11 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_select_topk_workspace_bytes.argtypes = [i32, i32]
     L.dodo_select_topk.restype = ctypes.c_int
     L.dodo_select_topk.argtypes = [vp, vp, vp, i32, i32, i32, u32, vp, vp, sz, vp]
+    L.dodo_segment_plan.restype = ctypes.c_int
+    L.dodo_segment_plan.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.dodo_nugget_attention_segments.restype = ctypes.c_int
+    L.dodo_nugget_attention_segments.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                                 i64, f32, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
     L.dodo_nugget_attention_indexed.restype = ctypes.c_int
     L.dodo_nugget_attention_indexed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                                 i32, i64, f32, ctypes.c_int, vp, vp, vp, sz, vp]
@@ -273,6 +278,53 @@ def dodo_nugget_attention_indexed(Q: torch.Tensor, K: torch.Tensor, V: torch.Ten
                                              max_q, max_k, max_local, max_n, K.stride(0), float(softmax_scale), code,
                                              _ptr(O), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
            "dodo_nugget_attention_indexed")
+    return O, lse
+
+
+def dodo_segment_plan(nugget_idx: torch.Tensor, cu_seqlens: torch.Tensor, cu_nuggets: torch.Tensor, seg_len: int,
+                      tau: int, capacity: int):
+    """Entries of the segment form of the autoregressive objective (Sec. 2.4): returns the device int32 arrays
+    (seg_cu_q [capacity+1], seg_nug_start, seg_nug_len, seg_loc_start, seg_loc_len [capacity], n_segments [1])."""
+    _dev(nugget_idx, cu_seqlens, cu_nuggets)
+    B = cu_seqlens.numel() - 1
+    mk = lambda n: torch.empty(n, dtype=torch.int32, device=cu_seqlens.device)
+    seg_cu_q, ns, nl, ls, ll, cnt = mk(capacity + 1), mk(capacity), mk(capacity), mk(capacity), mk(capacity), mk(1)
+    _check(lib.dodo_segment_plan(_ptr(nugget_idx), _ptr(cu_seqlens), _ptr(cu_nuggets), B, seg_len, tau, capacity,
+                                 _ptr(seg_cu_q), _ptr(ns), _ptr(nl), _ptr(ls), _ptr(ll), _ptr(cnt), _stream()),
+           "dodo_segment_plan")
+    return seg_cu_q, ns, nl, ls, ll, cnt
+
+
+def dodo_nugget_attention_segments(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, K: torch.Tensor,
+                                   V: torch.Tensor, seg_cu_q: torch.Tensor, seg_nug_start: torch.Tensor,
+                                   seg_nug_len: torch.Tensor, seg_loc_start: torch.Tensor, seg_loc_len: torch.Tensor,
+                                   max_q: int, max_k: int, max_local: int, softmax_scale: Optional[float] = None,
+                                   layout: int = TOKEN_MAJOR, O: Optional[torch.Tensor] = None,
+                                   lse: Optional[torch.Tensor] = None, want_lse: bool = False,
+                                   ws: Optional[torch.Tensor] = None):
+    """dodo_nugget_attention over (start, length) ranges of the nugget cache and of the texts' own K, V
+    [N, H_kv, d_h], one entry per segment; returns (O, lse or None)."""
+    _dev(Q, Kn, Vn, K, V, seg_cu_q, seg_nug_start, seg_nug_len, seg_loc_start, seg_loc_len, O, lse, ws)
+    Sq, H, d_h = Q.shape
+    H_kv = K.shape[1]
+    Kt = Kn.shape[0] if layout == TOKEN_MAJOR else Kn.shape[1]
+    n_seg = seg_cu_q.numel() - 1
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d_h)
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None and want_lse:
+        lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
+    code = _dtype_code(Q)
+    need = dodo_nugget_attention_workspace_bytes(n_seg, H, d_h, max_q, max_k, max_local, code)
+    if need and ws is None:
+        ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
+    _check(lib.dodo_nugget_attention_segments(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(K), _ptr(V), _ptr(seg_cu_q),
+                                              _ptr(seg_nug_start), _ptr(seg_nug_len), _ptr(seg_loc_start),
+                                              _ptr(seg_loc_len), n_seg, H, H_kv, d_h, max_q, max_k, max_local, Kt,
+                                              float(softmax_scale), code, layout, _ptr(O), _ptr(lse), _ptr(ws),
+                                              0 if ws is None else ws.numel(), _stream()),
+           "dodo_nugget_attention_segments")
     return O, lse
 
 

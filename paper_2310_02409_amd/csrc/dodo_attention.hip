@@ -25,10 +25,18 @@ extern "C" size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, in
 namespace dodo {
 namespace {
 
-// nug_idx != null: the gather-free form (Kn / Vn are the context's K / V with ctx_stride elements between tokens)
+// What the variants of the call add to the plain one (all null / 0 there).
+struct Variant {
+  const int32_t* nug_len = nullptr;  // nuggets of b: rows cu_nuggets[b] .. + nug_len[b]
+  const int32_t* loc_len = nullptr;  // local rows of b: rows cu_local[b] .. + loc_len[b]
+  const int32_t* nug_idx = nullptr;  // gather-free form: Kn / Vn are the context's K / V with ctx_stride
+  const int32_t* cu_ctx = nullptr;   //   elements between tokens, sequences of at most max_n tokens
+  int64_t ctx_stride = 0;
+  int32_t max_n = 0;
+};
+
 int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl, const int32_t* cu_q,
-                    const int32_t* cu_nuggets, const int32_t* nug_len, const int32_t* cu_local, const int32_t* nug_idx,
-                    const int32_t* cu_ctx, int64_t ctx_stride, int32_t max_n, int32_t B, int32_t H,
+                    const int32_t* cu_nuggets, const int32_t* cu_local, const Variant& v, int32_t B, int32_t H,
                     int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local, int64_t Kt,
                     float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws, size_t ws_bytes,
                     void* stream) {
@@ -50,11 +58,11 @@ int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* K
 
   AttnParams p;
   p.Q = Q; p.Kn = Kn; p.Vn = Vn; p.Kl = Kl; p.Vl = Vl;
-  p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.nug_len = nug_len; p.cu_local = cu_local;
-  p.nug_idx = nug_idx; p.cu_ctx = cu_ctx; p.max_n = max_n;
+  p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.nug_len = v.nug_len; p.cu_local = cu_local; p.loc_len = v.loc_len;
+  p.nug_idx = v.nug_idx; p.cu_ctx = v.cu_ctx; p.max_n = v.max_n;
   p.B = B; p.H = H; p.H_kv = H_kv; p.d_h = d_h; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
-  if (nug_idx != nullptr) {
-    p.nug_tok_stride = ctx_stride;
+  if (v.nug_idx != nullptr) {
+    p.nug_tok_stride = v.ctx_stride;
     p.nug_head_stride = d_h;
   } else if (layout == DODO_LAYOUT_TOKEN_MAJOR) {
     p.nug_tok_stride = static_cast<int64_t>(H_kv) * d_h;
@@ -79,9 +87,8 @@ extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* 
                                      int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
                                      int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout,
                                      void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
-  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nullptr, cu_local, nullptr, nullptr, 0, 0, B, H, H_kv,
-                               d_h, max_q, max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes,
-                               stream);
+  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, dodo::Variant{}, B, H, H_kv, d_h, max_q,
+                               max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
 }
 
 extern "C" int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, const void* Kl,
@@ -91,9 +98,10 @@ extern "C" int dodo_nugget_attention_cached(const void* Q, const void* Kn, const
                                             int64_t Kt, float softmax_scale, int dtype, int layout, void* O, float* lse,
                                             void* ws, size_t ws_bytes, void* stream) {
   if (B > 0 && max_q > 0 && !nugget_len) return DODO_ERR_INVALID_ARG;
-  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, nugget_start, nugget_len, cu_local, nullptr, nullptr, 0, 0, B, H,
-                               H_kv, d_h, max_q, max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes,
-                               stream);
+  dodo::Variant v;
+  v.nug_len = nugget_len;
+  return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, nugget_start, cu_local, v, B, H, H_kv, d_h, max_q, max_k,
+                               max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
 }
 
 extern "C" int dodo_nugget_attention_indexed(const void* Q, const void* K, const void* V, const int32_t* nugget_idx,
@@ -107,9 +115,28 @@ extern "C" int dodo_nugget_attention_indexed(const void* Q, const void* K, const
   if (H_kv > 0 && d_h > 0 && token_stride < static_cast<int64_t>(H_kv) * d_h) return DODO_ERR_INVALID_ARG;
   if (B > 0 && max_q > 0 && max_k > 0 && (!nugget_idx || !cu_seqlens)) return DODO_ERR_INVALID_ARG;
   if (dodo::dtype_ok(dtype) && (token_stride * dodo::elem_bytes(dtype)) % 16 != 0) return DODO_ERR_UNSUPPORTED;
-  // without nuggets the call is the plain one (nothing is read through the index list)
-  const bool indexed = max_k > 0;
-  return dodo::attention_entry(Q, K, V, Kl, Vl, cu_q, cu_nuggets, nullptr, cu_local, indexed ? nugget_idx : nullptr,
-                               indexed ? cu_seqlens : nullptr, token_stride, max_n, B, H, H_kv, d_h, max_q, max_k,
-                               max_local, 0, softmax_scale, dtype, DODO_LAYOUT_TOKEN_MAJOR, O, lse, ws, ws_bytes, stream);
+  dodo::Variant v;
+  if (max_k > 0) {  // without nuggets the call is the plain one (nothing is read through the index list)
+    v.nug_idx = nugget_idx;
+    v.cu_ctx = cu_seqlens;
+    v.ctx_stride = token_stride;
+    v.max_n = max_n;
+  }
+  return dodo::attention_entry(Q, K, V, Kl, Vl, cu_q, cu_nuggets, cu_local, v, B, H, H_kv, d_h, max_q, max_k, max_local,
+                               0, softmax_scale, dtype, DODO_LAYOUT_TOKEN_MAJOR, O, lse, ws, ws_bytes, stream);
+}
+
+extern "C" int dodo_nugget_attention_segments(const void* Q, const void* Kn, const void* Vn, const void* K, const void* V,
+                                              const int32_t* seg_cu_q, const int32_t* seg_nug_start,
+                                              const int32_t* seg_nug_len, const int32_t* seg_loc_start,
+                                              const int32_t* seg_loc_len, int32_t n_segments, int32_t H, int32_t H_kv,
+                                              int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local, int64_t Kt,
+                                              float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  if (n_segments > 0 && max_q > 0 && (!seg_nug_len || !seg_loc_len)) return DODO_ERR_INVALID_ARG;
+  dodo::Variant v;
+  v.nug_len = seg_nug_len;
+  v.loc_len = seg_loc_len;
+  return dodo::attention_entry(Q, Kn, Vn, K, V, seg_cu_q, seg_nug_start, seg_loc_start, v, n_segments, H, H_kv, d_h,
+                               max_q, max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
 }

@@ -8,6 +8,7 @@ struct AttnParams {
   const void *Q, *Kn, *Vn, *Kl, *Vl;
   const int32_t *cu_q, *cu_nuggets, *cu_local;
   const int32_t* nug_len;  // null: nuggets of sequence b are rows cu_nuggets[b] .. cu_nuggets[b+1]; else cu_nuggets[b] .. + nug_len[b]
+  const int32_t* loc_len;  // null: local rows of sequence b are rows cu_local[b] .. cu_local[b+1]; else cu_local[b] .. + loc_len[b]
   // gather-free form (both null otherwise): Kn / Vn are the context's K / V, nugget j of sequence b is its token
   // cu_ctx[b] + nug_idx[cu_nuggets[b] + j]
   const int32_t *nug_idx, *cu_ctx;

@@ -253,7 +253,8 @@ __device__ __forceinline__ void attend_query_block(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ nug_idx, const int32_t* __restrict__ cu_ctx,
+    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
+    const int32_t* __restrict__ cu_ctx,
     int H, int H_kv, int bh, int qblk,
     int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse) {
@@ -268,7 +269,7 @@ __device__ __forceinline__ void attend_query_block(
   const int i0 = qblk * kBM;
   if (i0 >= q_b) return;  // uniform over the workgroup
   const int k0 = cu_nuggets[b], k_b = nug_len != nullptr ? nug_len[b] : cu_nuggets[b + 1] - k0;
-  const int l0 = cu_local[b], m_b = cu_local[b + 1] - l0;
+  const int l0 = cu_local[b], m_b = loc_len != nullptr ? loc_len[b] : cu_local[b + 1] - l0;
   const int kvh = h / (H / H_kv);
 
   const int tid = threadIdx.x;
@@ -702,7 +703,8 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ nug_idx, const int32_t* __restrict__ cu_ctx,
+    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
+    const int32_t* __restrict__ cu_ctx,
     int B, int H, int H_kv, int n_qblocks, int pair, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
     uint16_t* __restrict__ O, float* __restrict__ lse) {
   const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
@@ -728,11 +730,11 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
       bh2 = bh_other;
     }
   }
-  attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, nug_idx, cu_ctx, H, H_kv, bh1, q1,
+  attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh1, q1,
                               nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
   if (q2 >= 0) {
     __syncthreads();  // the first block's use of LDS is over
-    attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, nug_idx, cu_ctx, H, H_kv, bh2,
+    attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh2,
                                 q2, nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
   }
 }
@@ -763,7 +765,7 @@ int launch_nw(const AttnParams& p) {
   hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(Cfg::kThreads), kLds, p.stream,
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
-                     static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.nug_idx, p.cu_ctx, p.B, p.H, p.H_kv,
+                     static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.nug_idx, p.cu_ctx, p.B, p.H, p.H_kv,
                      n_qblocks, pair,
                      p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, static_cast<uint16_t*>(p.O), p.lse);
   return launch_status();

@@ -55,7 +55,8 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const void* __restrict__ Q, const void* __restrict__ Kn, const void* __restrict__ Vn,
     const void* __restrict__ Kl, const void* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ nug_idx, const int32_t* __restrict__ cu_ctx,
+    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
+    const int32_t* __restrict__ cu_ctx,
     int H, int H_kv, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
     void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws) {
   using VT = Vec16<DTYPE>;
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   const int q_b = cu_q[b + 1] - q0;
   if (i >= q_b) return;  // uniform over the workgroup
   const int k0 = cu_nuggets[b], k_b = nug_len != nullptr ? nug_len[b] : cu_nuggets[b + 1] - k0;
-  const int l0 = cu_local[b], m_b = cu_local[b + 1] - l0;
+  const int l0 = cu_local[b], m_b = loc_len != nullptr ? loc_len[b] : cu_local[b + 1] - l0;
   const int n_local = max(0, min(m_b, m_b - q_b + i + 1));  // causal rule, bottom-right aligned
   const int n_vis = k_b + n_local;
   const int chunk = (n_vis + nsplit - 1) / nsplit;
@@ -292,12 +293,12 @@ int launch_t(const AttnParams& p, int nsplit) {
   const bool wide = rows * nsplit <= 512 && static_cast<int64_t>(p.max_k) + p.max_local >= 512;
   if (wide) {
     hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
-                       dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local,
+                       dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
                        p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws));
   } else {
     hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
-                       dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local,
+                       dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
                        p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws));
   }

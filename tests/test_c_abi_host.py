@@ -29,7 +29,7 @@ def test_header_symbols_are_exported(lib):
             "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
             "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets", "dodo_score_mlp",
             "dodo_score_mlp_workspace_bytes", "dodo_gather_nuggets_layers",
-            "dodo_nugget_attention_indexed"} <= set(names)
+            "dodo_nugget_attention_indexed", "dodo_segment_plan", "dodo_nugget_attention_segments"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
@@ -158,3 +158,12 @@ def test_indexed_attention_argument_validation(lib):
     assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 256, 7681, 5, 9000, 512, 0.1, 1, P, 0, 0, 0, 0) == -2
     assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 64, 4097, 5, 9000, 512, 0.1, 1, P, 0, 0, 0, 0) == -2
     assert A(P, P, P, P, P, P, P, P, P, P, 2, 4, 4, 128, 256, 10, 5, 3000000, 512, 0.1, 1, P, 0, 0, 0, 0) == -2
+
+
+def test_segment_plan_argument_validation(lib):
+    S = lib.dodo_segment_plan
+    assert S(P, P, P, 2, 0, 4, 8, P, P, P, P, P, 0, 0) == -1    # seg_len == 0
+    assert S(P, P, P, 2, 16, -1, 8, P, P, P, P, P, 0, 0) == -1  # tau < 0
+    assert S(P, P, P, 2, 16, 4, 8, 0, P, P, P, P, 0, 0) == -1   # no output
+    assert S(P, P, P, 2, 16, 4, 8, P, P, 0, P, P, 0, 0) == -1
+    assert S(0, P, P, 2, 16, 4, 8, P, P, P, P, P, 0, 0) == -1   # no index list
