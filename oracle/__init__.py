@@ -307,6 +307,39 @@ def attention_segment_mask(Q, Kn, Vn, K, V, nugget_idx, cu_seqlens, cu_nuggets, 
     return O, lse
 
 
+def ste_score_grad(Q, Kn, Vn, Kl, Vl, dO, cu_q, cu_nuggets, cu_local, scale: float, grad_scale: float):
+    """Gradient that the straight-through estimator hands to the scores (Sec. 2.5, Eq. 17-18) for one layer:
+    grad[i] = grad_scale * sum over heads h and query rows j of dl/dxi[j, i], where xi[j, i] is the input of the
+    softmax for query row j and nugget i, and dl/dxi = P (dP - D) with P the attention weights of Eq. 13 / Eq. 9
+    (over nuggets and the causally visible local rows), dP[j, i] = dO[j] . v_i and D[j] = dO[j] . O[j].
+    Token-major nugget cache; returns float64 [Kt]."""
+    Q, Kn, Vn, Kl, Vl, dO = (_to_f64(a) for a in (Q, Kn, Vn, Kl, Vl, dO))
+    H, H_kv = Q.shape[1], Kl.shape[1]
+    grad = np.zeros(Kn.shape[0])
+    for b in range(len(cu_q) - 1):
+        q0, q1 = int(cu_q[b]), int(cu_q[b + 1])
+        k0, k1 = int(cu_nuggets[b]), int(cu_nuggets[b + 1])
+        l0, l1 = int(cu_local[b]), int(cu_local[b + 1])
+        q_b, k_b, m_b = q1 - q0, k1 - k0, l1 - l0
+        for h in range(H):
+            kvh = h // (H // H_kv)
+            keys = np.concatenate([Kn[k0:k1, kvh], Kl[l0:l1, kvh]])
+            vals = np.concatenate([Vn[k0:k1, kvh], Vl[l0:l1, kvh]])
+            for j in range(q_b):
+                n_loc = max(0, min(m_b, m_b - q_b + j + 1))
+                vis = k_b + n_loc
+                if vis == 0 or k_b == 0:
+                    continue
+                xi = scale * (keys[:vis] @ Q[q0 + j, h])
+                p = np.exp(xi - xi.max())
+                p /= p.sum()
+                o = p @ vals[:vis]
+                d_p = vals[:k_b] @ dO[q0 + j, h]
+                big_d = dO[q0 + j, h] @ o
+                grad[k0:k1] += grad_scale * p[:k_b] * (d_p - big_d)
+    return grad
+
+
 def attention_rows(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, scale: float, rows, layout: int = TOKEN_MAJOR):
     """Nugget attention for sampled (b, h, i) triples -> (O float64 [R,d_h], lse float64 [R])."""
     Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, Kt = _attn_common(
