@@ -462,6 +462,24 @@ def main():
         gf["note"] = ("same results, bit for bit, as gather + attention; compare with gather + attn_block and "
                       "gather + attn_decode above")
         kernels["gather_free"] = gf
+        # score gradient of the straight-through estimator for this layer (backward of the block attention's
+        # nugget columns), fed with the O of the step and a fresh lse
+        if E == 2:
+            lse_b = torch.empty((g["Q"].shape[0], wl.H), dtype=torch.float32, device=dev)
+            D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k, max_m,
+                                    scale, D.TOKEN_MAJOR, O, lse=lse_b)
+            dO = W.normal(wl.seed, 99, tuple(g["Q"].shape), 1.0, wl.dtype, dev)
+            ste_ws = torch.empty(D.dodo_ste_score_grad_workspace_bytes(g["Q"].shape[0], wl.H, Kt), dtype=torch.uint8,
+                                 device=dev)
+            ste_grad = torch.empty(Kt, dtype=torch.float32, device=dev)
+            a, m = _timed_us(lambda: D.dodo_ste_score_grad(g["Q"], Kn, Vn, dO, O, lse_b, g["cu_q"], cu_k, max_q, max_k,
+                                                           scale, scale, D.TOKEN_MAJOR, grad=ste_grad, ws=ste_ws))
+            ste_flop = 4.0 * sum(q * k for q, k in zip(wl.q_lens, ks)) * wl.d_h * wl.H
+            kernels["ste_score_grad"] = {"avg_us": a, "min_us": m, "TFLOPs": round(ste_flop / a * 1e-6, 1),
+                                         "frac_of_bf16_peak": round(ste_flop / a * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 3),
+                                         "note": "whole call: row dots, the MFMA kernel, the sum over heads (training "
+                                                 "path, not part of the step)"}
+            del dO, ste_ws
         # the scorer as a 2-layer feedforward network (d -> d -> 1) over the step's hidden states
         if E == 2:
             d_model = g["hidden"].shape[1]

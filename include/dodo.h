@@ -264,6 +264,30 @@ int dodo_nugget_attention_segments(const void* Q, const void* Kn, const void* Vn
                                    float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Score gradient of the straight-through estimator (Sec. 2.5, Eq. 17-18) for one layer.  The forward
+ * pass adds s_i - stopgrad(s_i) to the attention logits of nugget i, so the gradient of the loss in
+ * s_i is the sum over query rows j and heads h of its gradient in the softmax input xi[j, i]:
+ *   grad[i] (+)= grad_scale * sum_h sum_j P[j,i] * (dO[j,h].v_i - dO[j,h].O[j,h]),
+ *   P[j,i] = exp(softmax_scale * q_j.k_i - lse[j,h]).
+ * Q, dO, O are [Sq, H, d_h] of `dtype` and lse fp32 [Sq, H] exactly as dodo_nugget_attention took and
+ * returned them for this layer (lse is required there); Kn, Vn, cu_q, cu_nuggets, layout, Kt as in
+ * that call (every nugget of a sequence is visible to all of its query rows, so the local rows enter
+ * through O and lse only).  grad_scores is fp32 [Kt], packed like the nugget cache; accumulate != 0
+ * adds to it (the sum over layers of Eq. 18: one call per layer), else it is overwritten.
+ * grad_scale: softmax_scale if the score is added to the unscaled logit xi of Eq. 17, 1 if it is
+ * added to the softmax input.  Sq = total query rows (host value); max_q / max_k bound q_b / k_b.
+ * ws: dodo_ste_score_grad_workspace_bytes(Sq, H, Kt) bytes, contents irrelevant.
+ * d_h % 8 == 0; bf16 with d_h = 128 runs on the matrix cores, everything else in a plain kernel.
+ * Deterministic (fixed summation order, no atomics).
+ */
+size_t dodo_ste_score_grad_workspace_bytes(int64_t Sq, int32_t H, int64_t Kt);
+int dodo_ste_score_grad(const void* Q, const void* Kn, const void* Vn, const void* dO, const void* O, const float* lse,
+                        const int32_t* cu_q, const int32_t* cu_nuggets, int32_t B, int32_t H, int32_t H_kv,
+                        int32_t d_h, int32_t max_q, int32_t max_k, int64_t Sq, int64_t Kt, float softmax_scale,
+                        float grad_scale, int accumulate, int dtype, int layout, float* grad_scores, void* ws,
+                        size_t ws_bytes, void* stream);
+
+/*
  * Threshold of the autoregressive mode from sampled scores (Sec. 2.4: Lambda is set so that about
  * t/r of t tokens are kept, and is estimated by running the scorer on sampled tokens).  With
  * k = dodo_nugget_count(n, num, den), writes to *lambda_out (device, fp32) the (k+1)-th highest

@@ -43,6 +43,11 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_select_topk_workspace_bytes.argtypes = [i32, i32]
     L.dodo_select_topk.restype = ctypes.c_int
     L.dodo_select_topk.argtypes = [vp, vp, vp, i32, i32, i32, u32, vp, vp, sz, vp]
+    L.dodo_ste_score_grad_workspace_bytes.restype = sz
+    L.dodo_ste_score_grad_workspace_bytes.argtypes = [i64, i32, i64]
+    L.dodo_ste_score_grad.restype = ctypes.c_int
+    L.dodo_ste_score_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i64, i64, f32, f32,
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, sz, vp]
     L.dodo_segment_plan.restype = ctypes.c_int
     L.dodo_segment_plan.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.dodo_nugget_attention_segments.restype = ctypes.c_int
@@ -279,6 +284,40 @@ def dodo_nugget_attention_indexed(Q: torch.Tensor, K: torch.Tensor, V: torch.Ten
                                              _ptr(O), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
            "dodo_nugget_attention_indexed")
     return O, lse
+
+
+def dodo_ste_score_grad_workspace_bytes(Sq: int, H: int, Kt: int) -> int:
+    return int(lib.dodo_ste_score_grad_workspace_bytes(Sq, H, Kt))
+
+
+def dodo_ste_score_grad(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, dO: torch.Tensor, O: torch.Tensor,
+                        lse: torch.Tensor, cu_q: torch.Tensor, cu_nuggets: torch.Tensor, max_q: int, max_k: int,
+                        softmax_scale: Optional[float] = None, grad_scale: Optional[float] = None,
+                        layout: int = TOKEN_MAJOR, grad: Optional[torch.Tensor] = None, accumulate: bool = False,
+                        ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Score gradient of the straight-through estimator (Eq. 17-18) for one layer; returns fp32 [Kt]."""
+    _dev(Q, Kn, Vn, dO, O, lse, cu_q, cu_nuggets, grad, ws)
+    Sq, H, d_h = Q.shape
+    H_kv = Kn.shape[1] if layout == TOKEN_MAJOR else Kn.shape[0]
+    Kt = Kn.shape[0] if layout == TOKEN_MAJOR else Kn.shape[1]
+    B = cu_q.numel() - 1
+    assert dO.shape == Q.shape and O.shape == Q.shape and lse.shape == (Sq, H) and lse.dtype == torch.float32
+    assert dO.dtype == Q.dtype == O.dtype == Kn.dtype == Vn.dtype
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d_h)
+    if grad_scale is None:
+        grad_scale = softmax_scale
+    if grad is None:
+        assert not accumulate
+        grad = torch.empty(Kt, dtype=torch.float32, device=Q.device)
+    need = dodo_ste_score_grad_workspace_bytes(Sq, H, Kt)
+    if need and ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    _check(lib.dodo_ste_score_grad(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(dO), _ptr(O), _ptr(lse), _ptr(cu_q),
+                                   _ptr(cu_nuggets), B, H, H_kv, d_h, max_q, max_k, Sq, Kt, float(softmax_scale),
+                                   float(grad_scale), int(bool(accumulate)), _dtype_code(Q), layout, _ptr(grad), _ptr(ws),
+                                   0 if ws is None else ws.numel(), _stream()), "dodo_ste_score_grad")
+    return grad
 
 
 def dodo_segment_plan(nugget_idx: torch.Tensor, cu_seqlens: torch.Tensor, cu_nuggets: torch.Tensor, seg_len: int,

@@ -29,7 +29,8 @@ def test_header_symbols_are_exported(lib):
             "dodo_nugget_attention_workspace_bytes", "dodo_nugget_attention_cached", "dodo_threshold_from_sample",
             "dodo_select_threshold", "dodo_stream_append", "dodo_meanpool_nuggets", "dodo_score_mlp",
             "dodo_score_mlp_workspace_bytes", "dodo_gather_nuggets_layers",
-            "dodo_nugget_attention_indexed", "dodo_segment_plan", "dodo_nugget_attention_segments"} <= set(names)
+            "dodo_nugget_attention_indexed", "dodo_segment_plan", "dodo_nugget_attention_segments",
+            "dodo_ste_score_grad", "dodo_ste_score_grad_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in dodo.h but not exported"
 
@@ -167,3 +168,17 @@ def test_segment_plan_argument_validation(lib):
     assert S(P, P, P, 2, 16, 4, 8, 0, P, P, P, P, 0, 0) == -1   # no output
     assert S(P, P, P, 2, 16, 4, 8, P, P, 0, P, P, 0, 0) == -1
     assert S(0, P, P, 2, 16, 4, 8, P, P, P, P, P, 0, 0) == -1   # no index list
+
+
+def test_ste_score_grad_argument_validation(lib):
+    G = lib.dodo_ste_score_grad
+    lib.dodo_ste_score_grad_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.dodo_ste_score_grad_workspace_bytes(ctypes.c_int64(100), 4, ctypes.c_int64(10)) == (2 * 100 * 4 + 4 * 10) * 4
+    #  Q  Kn Vn dO O lse cu_q cu_k B  H H_kv d_h mq mk  Sq  Kt  scale gscale acc dtype layout grad ws ws_bytes stream
+    i64 = ctypes.c_int64
+    assert G(P, P, P, P, P, P, P, P, 2, 4, 3, 128, 8, 8, i64(16), i64(10), 0.1, 0.1, 0, 1, 0, P, P, 1 << 20, 0) == -1  # H % H_kv
+    assert G(P, P, P, P, P, P, P, P, 2, 4, 4, 128, 8, 8, i64(16), i64(10), 0.1, 0.1, 0, 1, 5, P, P, 1 << 20, 0) == -1  # layout
+    assert G(P, P, P, P, P, P, P, P, 2, 4, 4, 100, 8, 8, i64(16), i64(10), 0.1, 0.1, 0, 1, 0, P, P, 1 << 20, 0) == -2  # d_h % 8
+    assert G(P, P, P, P, P, P, P, P, 2, 4, 4, 128, 8, 8, i64(16), i64(10), 0.1, 0.1, 0, 1, 0, P, P, 16, 0) == -3       # workspace
+    assert G(P, P, P, P, P, 0, P, P, 2, 4, 4, 128, 8, 8, i64(16), i64(10), 0.1, 0.1, 0, 1, 0, P, P, 1 << 20, 0) == -1  # lse missing
+    assert G(0, 0, 0, 0, 0, 0, 0, 0, 0, 4, 4, 128, 8, 8, i64(16), i64(10), 0.1, 0.1, 0, 1, 0, 0, 0, 0, 0) == 0         # B == 0
