@@ -102,7 +102,11 @@ int dodo_score_mlp(const void* hidden, const void* W1, const float* b1, const vo
                    int dtype, int64_t N, int32_t d, int32_t d_hid, int64_t row_stride, float* scores, void* ws,
                    size_t ws_bytes, void* stream);
 
-/* Bytes of device workspace dodo_select_topk needs for B sequences of at most max_n tokens (may be 0). */
+/* Bytes of device workspace dodo_select_topk can use for B sequences of at most max_n tokens (0 for short
+ * sequences).  With it, long sequences are split over several workgroups that exchange histograms and counts
+ * through it; without it (NULL or too small) one workgroup per sequence does the same work, more slowly.
+ * The workspace must be zero-filled before its first use; a call leaves it zero-filled, so it can be reused by
+ * the next call as it is.  It must not be shared by calls that may overlap in time. */
 size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n);
 
 /*
@@ -115,7 +119,7 @@ size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n);
  * Only integer comparisons on the score bits are used: the result is unique
  * and bit-exact.  max_n / max_k are host-side upper bounds on n_b / k_b
  * (0 < max_k <= max_n); a sequence longer than max_n is left unprocessed.
- * ws may be NULL when the workspace query returns 0.  B == 0 is a no-op.
+ * ws is optional (see dodo_select_topk_workspace_bytes); the result does not depend on it.  B == 0 is a no-op.
  */
 int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
                      int32_t max_n, int32_t max_k, uint32_t flags, int32_t* nugget_idx, void* ws, size_t ws_bytes,

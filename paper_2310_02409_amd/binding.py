@@ -167,7 +167,8 @@ def dodo_select_topk(scores: torch.Tensor, cu_seqlens: torch.Tensor, cu_nuggets:
     assert nugget_idx.dtype == torch.int32 and nugget_idx.numel() >= total_nuggets
     need = dodo_select_topk_workspace_bytes(B, max_n)
     if need and ws is None:
-        ws = torch.empty(need, dtype=torch.uint8, device=scores.device)
+        # zero-filled, as the library requires before the first use (a call leaves it zero-filled)
+        ws = torch.zeros(need, dtype=torch.uint8, device=scores.device)
     _check(lib.dodo_select_topk(_ptr(scores), _ptr(cu_seqlens), _ptr(cu_nuggets), B, max_n, max_k, flags,
                                 _ptr(nugget_idx), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
            "dodo_select_topk")

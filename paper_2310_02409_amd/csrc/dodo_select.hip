@@ -12,6 +12,12 @@
 //      wins ties).
 // One workgroup per sequence; histograms use LDS integer atomics with a
 // wavefront-level pre-aggregation so that heavy ties do not serialise.
+// Long sequences (given a workspace) are cut into chunks with a workgroup
+// each: the chunks' histograms of a pass are added up in the workspace, every
+// workgroup waits until all have contributed (bounded) and then picks the
+// digit from the same totals; the compaction hands out output offsets and the
+// tie budget in chunk (= position) order in the same way.  The result is the
+// same bit for bit; one compute unit's instruction issue no longer bounds it.
 #include "dodo_common.h"
 
 namespace dodo {
@@ -19,6 +25,12 @@ namespace {
 
 constexpr int kStagedMaxKeys = 34 * 1024;  // 136 KiB of the 160 KiB LDS
 constexpr int kCandCap = 8192;             // candidate list after the first pass: 16-bit positions, 16 KiB
+constexpr int kMultiMinKeys = 8192;        // sequences longer than this are worth several workgroups
+constexpr int kMultiChunkKeys = 4096;      // aimed-at keys per workgroup
+constexpr int kMaxChunks = 16;
+// workspace of the chunked form, per sequence: 4 histograms, 6 arrival counters (4 passes, counts, done), counts
+constexpr int kWsHist = 0, kWsArrive = 4 * 256, kWsCounts = kWsArrive + 8, kWsPerSeq = kWsCounts + 2 * kMaxChunks;
+constexpr int kMaxPolls = 1 << 17;         // bound of a wait for the other chunks (~0.1 s, never reached in a healthy run)
 
 __device__ __forceinline__ uint32_t order_key(float s) {
   uint32_t u = __float_as_uint(s);
@@ -27,18 +39,22 @@ __device__ __forceinline__ uint32_t order_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-template <int THREADS, bool STAGED>
+// MULTI: G consecutive workgroups share a sequence (chunk c = blockIdx % G); lds_keys = keys that fit in LDS.
+template <int THREADS, bool STAGED, bool MULTI>
 __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __restrict__ scores,
                                                               const int32_t* __restrict__ cu_seqlens,
                                                               const int32_t* __restrict__ cu_nuggets, uint32_t flags,
-                                                              int max_n, int32_t* __restrict__ nugget_idx) {
+                                                              int max_n, int lds_keys, int G, uint32_t* __restrict__ ws,
+                                                              int32_t* __restrict__ nugget_idx) {
   constexpr int kWaves = THREADS / kWave;
-  extern __shared__ uint32_t keys_lds[];  // max_n keys, then kCandCap 16-bit positions (STAGED only)
-  __shared__ uint32_t hist[256];
+  extern __shared__ uint32_t keys_lds[];  // lds_keys keys, then kCandCap 16-bit positions (STAGED only)
+  __shared__ uint32_t hist[256], hist_own[256];
   __shared__ uint32_t s_prefix, s_remaining, s_cand;
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
+  __shared__ int s_ok, s_out_base, s_eq_base;
 
-  const int b = blockIdx.x;
+  const int b = MULTI ? blockIdx.x / G : blockIdx.x;
+  const int chunk = MULTI ? blockIdx.x % G : 0;
   const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const int seq0 = cu_seqlens[b];
   const int n = cu_seqlens[b + 1] - seq0;
@@ -49,13 +65,40 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
   const bool force = (flags & DODO_TOPK_FORCE_LAST) != 0;
   const int n_free = force ? n - 1 : n;  // tokens that compete on score
   const int k_free = force ? k - 1 : k;
-  const float* s = scores + seq0;
   int32_t* out = nugget_idx + nug0;
+  // this workgroup's tokens: [lo, lo + n_own) of the sequence (all of them without chunks)
+  const int chunk_len = MULTI ? ((n_free + G - 1) / G + kWave - 1) / kWave * kWave : n_free;
+  const int lo = chunk * chunk_len;
+  const int n_own = max(0, min(chunk_len, n_free - lo));
+  const float* s = scores + seq0 + lo;
+  uint32_t* gws = MULTI ? ws + static_cast<int64_t>(b) * kWsPerSeq : nullptr;
+  // Waits until all G chunks have passed sync point `which` (thread 0 polls; device-scope accesses, which go to
+  // the level where all XCDs agree).  Whatever this workgroup published before is acknowledged first.
+  bool all_ok = true;
+  auto sync_chunks = [&](int which) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) {
+      __hip_atomic_fetch_add(gws + kWsArrive + which, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int polls = 0, ok = 1;
+      while (__hip_atomic_load(gws + kWsArrive + which, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(G)) {
+        if (++polls > kMaxPolls) {
+          ok = 0;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+      }
+      s_ok = ok;
+    }
+    __syncthreads();
+    all_ok = all_ok && s_ok != 0;
+  };
 
   if (k_free > 0) {
     if (STAGED) {
       // batches of 8 loads in flight per thread: one global-memory latency per batch, not per key
       constexpr int kBatch = 8;
+      const int n_free = n_own;
       for (int i0 = tid; i0 < n_free; i0 += THREADS * kBatch) {
         float v[kBatch];
 #pragma unroll
@@ -72,6 +115,8 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
       __syncthreads();
     }
     auto key_at = [&](int i) -> uint32_t { return STAGED ? keys_lds[i] : order_key(s[i]); };
+    const int n_free = n_own;  // below, "the tokens" are this workgroup's; positions are relative to lo
+    int pass_no = 0;
 
     // ---- radix select: key of the k_free-th best token ----
     // One pass: histogram of the pass's digit over the items that still match the prefix, then the
@@ -114,6 +159,21 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
           if (part[u]) atomicAdd(&hist[digit[u]], 1u);
       }
       __syncthreads();
+      if (MULTI) {
+        // add this chunk's bins to the sequence's, wait for the other chunks, continue with the totals
+        if (tid < 256) {
+          const uint32_t v = hist[tid];
+          hist_own[tid] = v;
+          if (v != 0) __hip_atomic_fetch_add(gws + kWsHist + 256 * pass_no + tid, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        sync_chunks(pass_no);
+        if (tid < 256)
+          hist[tid] = __hip_atomic_load(gws + kWsHist + 256 * pass_no + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (!all_ok && tid == 0) hist[255] = remaining;  // (a failed wait: keep the scan below well-defined)
+        __syncthreads();
+      }
+      ++pass_no;
       if (wave == 0) {
         // lane l owns bins 4l..4l+3; inclusive suffix sum over lanes
         const uint32_t b0 = hist[4 * lane], b1 = hist[4 * lane + 1], b2 = hist[4 * lane + 2], b3 = hist[4 * lane + 3];
@@ -147,7 +207,7 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
           }
           s_prefix = prefix | (static_cast<uint32_t>(4 * L + dsel) << shift);
           s_remaining = remaining - above;
-          s_cand = in_bin;  // items that carry the chosen digit
+          s_cand = MULTI ? hist_own[4 * L + dsel] : in_bin;  // this workgroup's items that carry the chosen digit
         }
       }
       __syncthreads();
@@ -159,7 +219,7 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
     const int n_cand = static_cast<int>(s_cand);
     if (STAGED && n_cand <= kCandCap) {
       // positions of the tokens that share the chosen top byte, in any order
-      uint16_t* cand = reinterpret_cast<uint16_t*>(keys_lds + max_n);
+      uint16_t* cand = reinterpret_cast<uint16_t*>(keys_lds + lds_keys);
       __syncthreads();  // everyone has read s_cand
       if (tid == 0) s_cand = 0;
       __syncthreads();
@@ -202,6 +262,35 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
     }
     __syncthreads();
     int eq_base = 0, out_base = 0;
+    if (MULTI) {
+      // the chunks' counts, then offsets and the tie budget in chunk order
+      if (tid == 0) {
+        int gt = 0, eq = 0;
+        for (int w = 0; w < kWaves; ++w) {
+          gt += wave_gt[w];
+          eq += wave_eq[w];
+        }
+        __hip_atomic_store(gws + kWsCounts + chunk, static_cast<uint32_t>(gt), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(gws + kWsCounts + kMaxChunks + chunk, static_cast<uint32_t>(eq), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      }
+      sync_chunks(4);
+      if (tid == 0) {
+        int ob = 0, eb = 0;
+        for (int c2 = 0; c2 < chunk; ++c2) {
+          const int gt = static_cast<int>(__hip_atomic_load(gws + kWsCounts + c2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          const int eq = static_cast<int>(
+              __hip_atomic_load(gws + kWsCounts + kMaxChunks + c2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          ob += gt + max(0, min(eq, need_eq - eb));
+          eb += eq;
+        }
+        s_out_base = ob;
+        s_eq_base = eb;
+      }
+      __syncthreads();
+      out_base = s_out_base;
+      eq_base = s_eq_base;
+    }
     for (int w = 0; w < wave; ++w) {
       const int e = wave_eq[w];
       out_base += wave_gt[w] + max(0, min(e, need_eq - eq_base));
@@ -215,12 +304,51 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
       const bool sel = (i < end && key > T) || (is_eq && eq_base + popc_below_lane(eq_mask) < need_eq);
       const uint64_t sel_mask = __ballot(sel);
       const int pos = out_base + popc_below_lane(sel_mask);
-      if (sel && pos < k_free) out[pos] = i;  // pos < k_free always holds; the test keeps a logic slip in bounds
+      if (sel && pos < k_free && all_ok) out[pos] = lo + i;  // pos < k_free always holds; the test keeps a logic slip in bounds
       eq_base += __popcll(eq_mask);
       out_base += __popcll(sel_mask);
     }
   }
-  if (force && tid == 0) out[k - 1] = n - 1;
+  if (force && tid == 0 && chunk == 0) out[k - 1] = n - 1;
+  if (MULTI && k_free > 0) {
+    // Leave the workspace as it was found (zeros): whoever is last to be done with it clears it.  A wait that ran
+    // out means a broken run: the sequence's list is filled with a valid index so that nothing downstream reads out
+    // of bounds, and the workspace stays dirty.
+    if (!all_ok) {
+      for (int i = tid; i < k; i += THREADS) out[i] = n - 1;
+      return;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t before = __hip_atomic_fetch_add(gws + kWsArrive + 5, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_ok = before + 1 == static_cast<uint32_t>(G);
+    }
+    __syncthreads();
+    if (s_ok) {
+      for (int i = tid; i < kWsPerSeq; i += THREADS)
+        __hip_atomic_store(gws + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+int compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+  return cus;
+}
+
+// Chunks per sequence of the chunked form, or 0 when it does not apply (short sequences, or more workgroups than
+// compute units: all chunks of a sequence must be resident at the same time, since they wait for each other).
+int chunk_count(int32_t B, int32_t max_n) {
+  if (max_n <= kMultiMinKeys) return 0;
+  int G = (max_n + kMultiChunkKeys - 1) / kMultiChunkKeys;
+  if (G > kMaxChunks) G = kMaxChunks;
+  const int room = compute_units() / B;
+  if (G > room) G = room;
+  if (G < 2) return 0;
+  const int chunk_len = ((max_n + G - 1) / G + kWave - 1) / kWave * kWave;
+  return chunk_len <= kStagedMaxKeys ? G : 0;
 }
 
 template <int THREADS>
@@ -228,17 +356,31 @@ int launch_select(const float* scores, const int32_t* cu_seqlens, const int32_t*
                   uint32_t flags, int32_t* nugget_idx, hipStream_t stream) {
   if (max_n <= kStagedMaxKeys) {
     const size_t lds = static_cast<size_t>(max_n) * sizeof(uint32_t) + kCandCap * sizeof(uint16_t);
-    auto kern = select_topk_kernel<THREADS, true>;
+    auto kern = select_topk_kernel<THREADS, true, false>;
     if (lds > 48 * 1024) {
       DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(lds)));
     }
-    hipLaunchKernelGGL(kern, dim3(B), dim3(THREADS), lds, stream, scores, cu_seqlens, cu_nuggets, flags, max_n,
-                       nugget_idx);
+    hipLaunchKernelGGL(kern, dim3(B), dim3(THREADS), lds, stream, scores, cu_seqlens, cu_nuggets, flags, max_n, max_n, 1,
+                       static_cast<uint32_t*>(nullptr), nugget_idx);
   } else {
-    hipLaunchKernelGGL((select_topk_kernel<THREADS, false>), dim3(B), dim3(THREADS), 0, stream, scores, cu_seqlens,
-                       cu_nuggets, flags, max_n, nugget_idx);
+    hipLaunchKernelGGL((select_topk_kernel<THREADS, false, false>), dim3(B), dim3(THREADS), 0, stream, scores, cu_seqlens,
+                       cu_nuggets, flags, max_n, 0, 1, static_cast<uint32_t*>(nullptr), nugget_idx);
   }
+  return launch_status();
+}
+
+int launch_select_chunked(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
+                          int32_t max_n, int G, uint32_t flags, int32_t* nugget_idx, uint32_t* ws, hipStream_t stream) {
+  const int chunk_len = ((max_n + G - 1) / G + kWave - 1) / kWave * kWave;
+  const size_t lds = static_cast<size_t>(chunk_len) * sizeof(uint32_t) + kCandCap * sizeof(uint16_t);
+  auto kern = select_topk_kernel<1024, true, true>;
+  if (lds > 48 * 1024) {
+    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     static_cast<int>(lds)));
+  }
+  hipLaunchKernelGGL(kern, dim3(B * G), dim3(1024), lds, stream, scores, cu_seqlens, cu_nuggets, flags, max_n, chunk_len, G,
+                     ws, nugget_idx);
   return launch_status();
 }
 
@@ -246,23 +388,26 @@ int launch_select(const float* scores, const int32_t* cu_seqlens, const int32_t*
 }  // namespace dodo
 
 extern "C" size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n) {
-  (void)B;
-  (void)max_n;
-  return 0;  // keys live in LDS (or are re-read from the score array); no global scratch
+  using namespace dodo;
+  if (B <= 0 || max_n <= 0) return 0;
+  return chunk_count(B, max_n) > 0 ? static_cast<size_t>(B) * kWsPerSeq * sizeof(uint32_t) : 0;
 }
 
 extern "C" int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
                                 int32_t max_n, int32_t max_k, uint32_t flags, int32_t* nugget_idx, void* ws,
                                 size_t ws_bytes, void* stream) {
   using namespace dodo;
-  (void)ws;
-  (void)ws_bytes;
   if (B < 0) return DODO_ERR_INVALID_ARG;
   if (B == 0) return DODO_OK;
   if (!scores || !cu_seqlens || !cu_nuggets || !nugget_idx) return DODO_ERR_INVALID_ARG;
   if (max_n <= 0 || max_k <= 0 || max_k > max_n) return DODO_ERR_INVALID_ARG;
   if (flags & ~DODO_TOPK_FORCE_LAST) return DODO_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // long sequences, given the workspace: several workgroups per sequence
+  const int G = chunk_count(B, max_n);
+  if (G > 0 && ws != nullptr && ws_bytes >= static_cast<size_t>(B) * kWsPerSeq * sizeof(uint32_t) &&
+      (reinterpret_cast<uintptr_t>(ws) & 3u) == 0)
+    return launch_select_chunked(scores, cu_seqlens, cu_nuggets, B, max_n, G, flags, nugget_idx, static_cast<uint32_t*>(ws), s);
   // about four keys per thread: the kernel is latency-bound (few barriers matter more than lanes)
   if (max_n <= 1024) return launch_select<256>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);
   if (max_n <= 2048) return launch_select<512>(scores, cu_seqlens, cu_nuggets, B, max_n, flags, nugget_idx, s);

@@ -129,6 +129,39 @@ def test_select_is_deterministic(D):
         assert torch.equal(D.dodo_select_topk(s, cu_s, cu_kd, max(n_lens), max(k_lens), int(cu_k[-1])), first)
 
 
+def test_select_long_sequences_over_several_workgroups(D):
+    # with the workspace, sequences beyond 8192 tokens are cut into chunks that exchange histograms and counts
+    n_lens = [20000, 9000, 33000, 70, 0]
+    B = len(n_lens)
+    need = D.dodo_select_topk_workspace_bytes(B, max(n_lens))
+    assert need > 0 and D.dodo_select_topk_workspace_bytes(B, 8192) == 0
+    ws = torch.zeros(need, dtype=torch.uint8, device=dev())  # zero-filled once, reused by every call below
+    cu_s = oracle.cu_from_lengths(n_lens)
+    base = W.normal(230, 0, (sum(n_lens),), 1.0, torch.float32)
+    spec = base.numpy().copy()
+    spec[::7] = np.nan
+    spec[3::11] = np.inf
+    spec[5::13] = -np.inf
+    spec[1::17] = 0.0
+    spec[2::19] = -0.0
+    cases = [(base.numpy(), [oracle.nugget_count(n, 1, 10) for n in n_lens]),
+             (W.quantise16(base).numpy(), [oracle.nugget_count(n, 1, 20) for n in n_lens]),
+             (spec, [1, 9000, 1, 35, 0]), (spec, [20000, 4500, 16000, 70, 0]),
+             (np.full(sum(n_lens), 2.5, np.float32), [2000, 1, 3300, 7, 0])]
+    for scores, k_lens in cases:
+        cu_k = oracle.cu_from_lengths(k_lens)
+        sd, csd, ckd = torch.from_numpy(scores).to(dev()), torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev())
+        for flags in (0, 1):
+            ref = oracle.select_topk(scores, cu_s, cu_k, flags)
+            got = D.dodo_select_topk(sd, csd, ckd, max(n_lens), max(k_lens), int(cu_k[-1]), flags, ws=ws)
+            assert np.array_equal(got.cpu().numpy(), ref)
+            assert not bool(ws.any())  # left as it was found
+            # without a (large enough) workspace: one workgroup per sequence, same result
+            one = D.dodo_select_topk(sd, csd, ckd, max(n_lens), max(k_lens), int(cu_k[-1]), flags,
+                                     ws=torch.zeros(16, dtype=torch.uint8, device=dev()))
+            assert torch.equal(got, one)
+
+
 # ---------------------------------------------------------------- gather
 @pytest.mark.parametrize("dtype,H_kv,d_h", [(torch.bfloat16, 32, 128), (torch.float32, 4, 64), (torch.bfloat16, 3, 64),
                                             (torch.bfloat16, 40, 128)])
