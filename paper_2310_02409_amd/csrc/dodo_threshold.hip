@@ -15,7 +15,9 @@ namespace dodo {
 namespace {
 
 constexpr int kSampleThreads = 1024;
-constexpr int kThreshThreads = 256;
+constexpr int kSampleBatch = 8;
+constexpr int kThreshThreads = 1024;
+constexpr int kThreshBatch = 4;  // 64-token groups per wavefront with their loads in flight together
 constexpr int kAppendThreads = 256;
 
 // Order-preserving image of an fp32 score (NaN lowest, -0 == +0) and its inverse on non-NaN keys.
@@ -44,25 +46,36 @@ __global__ __launch_bounds__(kSampleThreads) void kth_highest_kernel(const float
     const int shift = 24 - 8 * pass;
     for (int i = tid; i < 256; i += kSampleThreads) hist[i] = 0;
     __syncthreads();
-    for (int64_t i0 = static_cast<int64_t>(wave) * kWave; i0 < n; i0 += kSampleThreads) {
-      const int64_t i = i0 + lane;
-      const uint32_t key = (i < n) ? order_key(sample[i]) : 0u;
-      bool part = (i < n) && ((key & mask) == prefix);
-      const uint32_t digit = (key >> shift) & 255u;
-      // two rounds of wavefront aggregation absorb the hot bins, the rest goes lane by lane
+    // kSampleBatch 64-score groups per wavefront and iteration, their loads in flight together (the pass is bound
+    // by the latency of these loads)
+    for (int64_t i0 = static_cast<int64_t>(wave) * kWave * kSampleBatch; i0 < n; i0 += kSampleThreads * kSampleBatch) {
+      float v[kSampleBatch];
 #pragma unroll
-      for (int round = 0; round < 2; ++round) {
-        const uint64_t act = __ballot(part);
-        if (act != 0) {
-          const int leader = __ffsll(static_cast<long long>(act)) - 1;
-          const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
-          const bool same = part && digit == d0;
-          const uint64_t mm = __ballot(same);
-          if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
-          part = part && !same;
-        }
+      for (int u = 0; u < kSampleBatch; ++u) {
+        const int64_t i = i0 + u * kWave + lane;
+        v[u] = sample[i < n ? i : n - 1];
       }
-      if (part) atomicAdd(&hist[digit], 1u);
+#pragma unroll
+      for (int u = 0; u < kSampleBatch; ++u) {
+        const int64_t i = i0 + u * kWave + lane;
+        const uint32_t key = order_key(v[u]);
+        bool part = (i < n) && ((key & mask) == prefix);
+        const uint32_t digit = (key >> shift) & 255u;
+        // two rounds of wavefront aggregation absorb the hot bins, the rest goes lane by lane
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+          const uint64_t act = __ballot(part);
+          if (act != 0) {
+            const int leader = __ffsll(static_cast<long long>(act)) - 1;
+            const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
+            const bool same = part && digit == d0;
+            const uint64_t mm = __ballot(same);
+            if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
+            part = part && !same;
+          }
+        }
+        if (part) atomicAdd(&hist[digit], 1u);
+      }
     }
     __syncthreads();
     if (tid == 0) {  // 256 bins, once per pass: a plain scan from the top
@@ -106,9 +119,18 @@ __global__ __launch_bounds__(kThreshThreads) void select_threshold_kernel(
   const int start = wave * per_wave;
   const int end = min(start + per_wave, n);
   int cnt = 0;
-  for (int i0 = start; i0 < end; i0 += kWave) {
-    const int i = i0 + lane;
-    cnt += __popcll(__ballot(i < end && s[i] > lam));  // false for NaN
+  for (int i0 = start; i0 < end; i0 += kWave * kThreshBatch) {
+    float v[kThreshBatch];
+#pragma unroll
+    for (int u = 0; u < kThreshBatch; ++u) {
+      const int i = i0 + u * kWave + lane;
+      v[u] = s[i < end ? i : end - 1];  // unconditional loads: all in flight before the first use
+    }
+#pragma unroll
+    for (int u = 0; u < kThreshBatch; ++u) {
+      const int i = i0 + u * kWave + lane;
+      cnt += __popcll(__ballot(i < end && v[u] > lam));  // false for NaN
+    }
   }
   if (lane == 0) wave_cnt[wave] = cnt;
   if (!COUNT_ONLY && tid == 0) {
@@ -127,12 +149,21 @@ __global__ __launch_bounds__(kThreshThreads) void select_threshold_kernel(
     return;
   }
   int out_at = s_base + before;
-  for (int i0 = start; i0 < end; i0 += kWave) {
-    const int i = i0 + lane;
-    const bool keep = i < end && s[i] > lam;
-    const uint64_t km = __ballot(keep);
-    if (keep) nugget_idx[out_at + popc_below_lane(km)] = i;
-    out_at += __popcll(km);
+  for (int i0 = start; i0 < end; i0 += kWave * kThreshBatch) {
+    float v[kThreshBatch];
+#pragma unroll
+    for (int u = 0; u < kThreshBatch; ++u) {
+      const int i = i0 + u * kWave + lane;
+      v[u] = s[i < end ? i : end - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < kThreshBatch; ++u) {
+      const int i = i0 + u * kWave + lane;
+      const bool keep = i < end && v[u] > lam;
+      const uint64_t km = __ballot(keep);
+      if (keep) nugget_idx[out_at + popc_below_lane(km)] = i;
+      out_at += __popcll(km);
+    }
   }
   if (tid == 0) {
     cu_nuggets[b + 1] = s_base + total;
