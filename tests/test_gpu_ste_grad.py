@@ -61,6 +61,7 @@ def test_plain_kernel(D, dtype, H, H_kv, d_h):
     ([100, 37, 256, 16, 0], [13, 200, 0, 77, 9], [150, 37, 300, 16, 3], 4, 2),   # ragged, GQA, partial tiles, no queries
     ([300], [103], [300], 3, 1),
     ([33, 200], [130, 65], [0, 100], 2, 2),
+    ([1100, 70], [600, 257], [1200, 70], 2, 1),   # three nugget tiles per workgroup row, 35 query tiles
 ])
 def test_mfma_kernel_bf16(D, q_lens, k_lens, m_lens, H, H_kv):
     t, cu = _case(701, q_lens, k_lens, m_lens, H, H_kv, 128, torch.bfloat16)
