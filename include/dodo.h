@@ -93,7 +93,7 @@ size_t dodo_score_mlp_workspace_bytes(int dtype, int64_t N, int32_t d, int32_t d
  *   scores[t] = sum_j w2[j] * act( sum_c W1[j,c] * hidden[t,c] + b1[j] ) + b2
  * hidden [N, d] (row_stride elements between rows), W1 [d_hid, d] row-major and w2 [d_hid] of
  * `dtype`; b1 [d_hid] fp32; scores fp32 [N], -0 written as +0.  The paper does not name the
- * activation: `act` is one of DODO_ACT_*.  bf16 inputs with d % 32 == 0 and d_hid % 256 == 0 run on
+ * activation: `act` is one of DODO_ACT_*.  bf16 inputs with d % 64 == 0 and d_hid % 256 == 0 run on
  * the matrix cores (products bf16 x bf16, sums fp32, the N x d_hid intermediate stays in registers);
  * everything else takes a plain kernel that is correct for any shape with d <= 32768 but slow for
  * large ones.  Run-to-run deterministic.  N == 0 is a no-op.

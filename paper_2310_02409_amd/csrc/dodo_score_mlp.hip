@@ -5,20 +5,20 @@
 // The paper does not name the activation; ReLU, GELU (erf form) and tanh are
 // offered.  2 N d d_hid flop: a dense contraction, so it runs on the matrix cores.
 //
-// MFMA kernel (bf16, d % 32 == 0, d_hid % 256 == 0): a workgroup of 8 wavefronts
+// MFMA kernel (bf16, d % 64 == 0, d_hid % 256 == 0): a workgroup of 8 wavefronts
 // owns 256 tokens and walks over 256-wide tiles of hidden units; for each it
-// accumulates H^T = W1_tile X^T over d in steps of 32 channels with
+// accumulates H^T = W1_tile X^T over d in steps of 64 channels with
 // v_mfma_f32_32x32x16_bf16 (A = W1 rows, B = token rows, so that a token is a lane
 // of the accumulators and the reduction over hidden units stays inside a lane),
 // then applies bias, activation and w2 to the accumulators and adds them to the
 // tokens' partial scores.  The N x d_hid intermediate never leaves the registers.
-// X and W1 tiles stream global -> LDS with 16-byte direct loads into four 32 KiB
-// stages; rows are 64 bytes with an XOR swizzle of the 16-byte pieces that makes
-// the fragment reads conflict-free (measured: no bank-conflict cycles).  The one
-// barrier per step sits in the middle of the step: by then a wavefront holds the
-// step's second-half fragments in registers, so the stage can be refilled (for
-// three and a half steps ahead) right after the barrier, and the next step's
-// first fragments are fetched under the second half's matrix instructions.
+// X and W1 tiles stream global -> LDS with 16-byte direct loads of whole 128-byte
+// rows into two 64 KiB stages; the 16-byte pieces of a row are XOR-swizzled so
+// that the fragment reads are conflict-free (measured: no bank-conflict cycles).
+// One barrier per step, after the third of its four 16-channel parts: by then a
+// wavefront holds the last part's fragments in registers, so the stage can be
+// refilled (for the step after next) right after the barrier, and the next
+// step's first fragments are fetched under the last part's matrix instructions.
 // The hidden tiles are split over (at least four) workgroups, and the workgroups
 // resident on one XCD form a patch of token tiles x splits that share their
 // panels through that XCD's L2; a second kernel adds the partial scores in split
@@ -38,12 +38,12 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int kTokTile = 256;  // tokens per workgroup
 constexpr int kHidTile = 256;  // hidden units per tile
-constexpr int kBK = 32;        // channels per step
-constexpr int kStagesG = 4;
+constexpr int kBK = 64;        // channels per step
+constexpr int kStagesG = 2;
 constexpr int kOperandBytes = kTokTile * kBK * 2;  // 16 KiB: one operand tile of a stage (both tiles have 256 rows)
 constexpr int kStageBytesG = 2 * kOperandBytes;
 constexpr int kMlpThreads = 512;
-constexpr int kLoadsPerStep = 4;  // direct loads per wavefront per step (2 of X, 2 of W1)
+constexpr int kLoadsPerStep = 8;  // direct loads per wavefront per step (4 of X, 4 of W1)
 
 __device__ __forceinline__ float activation(float h, int act) {
   if (act == DODO_ACT_RELU) return fmaxf(h, 0.f);
@@ -89,37 +89,41 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
   const int ksteps = d / kBK;
   const int n_steps = n_tiles * ksteps;
 
-  // ---- loader: per step, wavefront w brings rows 32w .. 32w+31 of the X tile and of the W1 tile,
-  // 16 rows (1 KiB) per instruction; lane i sits at (row i/4, position i%4) and fetches the piece that
-  // the swizzle stores there: piece = pos ^ ((row >> 2) & 3)
-  const int l_row = lane >> 2, l_pos = lane & 3;
-  const uint32_t l_piece_bytes = static_cast<uint32_t>((l_pos ^ ((l_row >> 2) & 3)) * 16);
-  uint32_t x_off[2], w_off[2];
+  // ---- loader: per step, wavefront w brings rows 32w .. 32w+31 of the X tile and of the W1 tile, 8 rows of 128
+  // bytes (1 KiB, whole cache lines) per instruction; lane i sits at (row i/8, position i%8) and fetches the piece
+  // that the swizzle stores there: piece = pos ^ ((row >> 1) & 7)
+  const int l_row = lane >> 3, l_pos = lane & 7;
+  uint32_t x_off[4], w_off[4];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = 32 * wave + 16 * u + l_row;
+  for (int u = 0; u < 4; ++u) {
+    const int r = 32 * wave + 8 * u + l_row;
+    const uint32_t piece_bytes = static_cast<uint32_t>((l_pos ^ ((r >> 1) & 7)) * 16);
     const int64_t tok = min(tok0 + r, N - 1);  // rows past the end re-read the last token; nothing of them is stored
-    x_off[u] = static_cast<uint32_t>((tok - tok0) * row_stride * 2) + l_piece_bytes;
-    w_off[u] = static_cast<uint32_t>(r) * static_cast<uint32_t>(d) * 2u + l_piece_bytes;
+    x_off[u] = static_cast<uint32_t>((tok - tok0) * row_stride * 2) + piece_bytes;
+    w_off[u] = static_cast<uint32_t>(r) * static_cast<uint32_t>(d) * 2u + piece_bytes;
   }
   const uint16_t* x_base = X + tok0 * row_stride;
-  auto issue_step = [&](int step) {
-    const int st = min(step, n_steps - 1);  // past the end: re-read the last step into a stage nobody reads
+  auto issue_part = [&](int step, int q) {  // eighth q of a step's loads: (u = q / 2, operand = q % 2)
+    const int st = min(step, n_steps - 1);  // past the end: re-read the last step into a stage nobody reads any more
     const int ht = tile0 + st / ksteps, ks = st % ksteps;
     const uint32_t stage = lds_base + (step % kStagesG) * kStageBytesG;
-    const uint16_t* xb = x_base + ks * kBK;
-    const uint16_t* wb = W1 + static_cast<int64_t>(ht) * kHidTile * d + ks * kBK;
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      dma16(xb, x_off[u], __builtin_amdgcn_readfirstlane(stage + (32 * wave + 16 * u) * 64));
-      dma16(wb, w_off[u], __builtin_amdgcn_readfirstlane(stage + kOperandBytes + (32 * wave + 16 * u) * 64));
+    const int u = q >> 1;
+    if ((q & 1) == 0) {
+      dma16(x_base + ks * kBK, x_off[u], __builtin_amdgcn_readfirstlane(stage + (32 * wave + 8 * u) * 128));
+    } else {
+      dma16(W1 + static_cast<int64_t>(ht) * kHidTile * d + ks * kBK, w_off[u],
+            __builtin_amdgcn_readfirstlane(stage + kOperandBytes + (32 * wave + 8 * u) * 128));
     }
   };
+  auto issue_step = [&](int step) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_part(step, q);
+  };
 
-  // ---- fragment addresses: row r of a tile at r*64, piece p at (p ^ ((r >> 2) & 3)) * 16
-  const int f_sw = (j32 >> 2) & 3;
-  const int x_row_off = (64 * tg + j32) * 64;                     // token blocks tb = 0, 1: + 32*64*tb
-  const int w_row_off = kOperandBytes + (128 * hg + j32) * 64;    // hidden blocks hb = 0..3: + 32*64*hb
+  // ---- fragment addresses: row r of a tile at r*128, piece p at (p ^ ((r >> 1) & 7)) * 16
+  const int f_sw = (j32 >> 1) & 7;
+  const int x_row_off = (64 * tg + j32) * 128;                    // token blocks tb = 0, 1: + 32*128*tb
+  const int w_row_off = kOperandBytes + (128 * hg + j32) * 128;   // hidden blocks hb = 0..3: + 32*128*hb
 
   floatx16 acc[4][2];
   float part[2] = {0.f, 0.f};  // partial scores of tokens 64 tg + 32 tb + j32 (this lane's half of the hidden units)
@@ -133,56 +137,52 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
   };
   zero_acc();
 
-  auto issue_part = [&](int step, int q) {  // quarter q of a step's loads: (u = q / 2, operand = q % 2)
-    const int st = min(step, n_steps - 1);  // past the end: re-read the last step into a stage nobody reads any more
-    const int ht = tile0 + st / ksteps, ks = st % ksteps;
-    const uint32_t stage = lds_base + (step % kStagesG) * kStageBytesG;
-    const int u = q >> 1;
-    if ((q & 1) == 0) {
-      dma16(x_base + ks * kBK, x_off[u], __builtin_amdgcn_readfirstlane(stage + (32 * wave + 16 * u) * 64));
-    } else {
-      dma16(W1 + static_cast<int64_t>(ht) * kHidTile * d + ks * kBK, w_off[u],
-            __builtin_amdgcn_readfirstlane(stage + kOperandBytes + (32 * wave + 16 * u) * 64));
-    }
-  };
-  bf16x8 xf[2][2], wf[2][4];  // fragment sets of the two half steps
+  bf16x8 xf[2][2], wf[2][4];  // two fragment sets, used alternately by the four 16-channel parts of a step
   auto read_frags = [&](int step, int ks, bf16x8* xo, bf16x8* wo) {
     const char* stg = lds + (step % kStagesG) * kStageBytesG;
     const int piece = ((2 * ks + g) ^ f_sw) << 4;
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) xo[tb] = *reinterpret_cast<const bf16x8*>(stg + x_row_off + tb * 2048 + piece);
+    for (int tb = 0; tb < 2; ++tb) xo[tb] = *reinterpret_cast<const bf16x8*>(stg + x_row_off + tb * 4096 + piece);
 #pragma unroll
-    for (int hb = 0; hb < 4; ++hb) wo[hb] = *reinterpret_cast<const bf16x8*>(stg + w_row_off + hb * 2048 + piece);
+    for (int hb = 0; hb < 4; ++hb) wo[hb] = *reinterpret_cast<const bf16x8*>(stg + w_row_off + hb * 4096 + piece);
   };
-  if (n_steps > 0) {
-#pragma unroll
-    for (int s = 0; s < kStagesG; ++s) issue_step(s);
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kLoadsPerStep));  // step 0 has landed
-    __syncthreads();
-    read_frags(0, 0, xf[0], wf[0]);
-  }
-  for (int step = 0; step < n_steps; ++step) {
-    // first half: the second half's fragments are requested, then the matrix cores work on the first half's
-    read_frags(step, 1, xf[1], wf[1]);
+  auto mfma_set = [&](int set) {
 #pragma unroll
     for (int hb = 0; hb < 4; ++hb)
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb)
-        acc[hb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][hb], xf[0][tb], acc[hb][tb], 0, 0, 0);
-    // middle: this wavefront has read everything it needs of this step's stage, and its part of the next step
-    // has landed (two younger steps may be in flight); after the barrier that holds for every wavefront
+        acc[hb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][hb], xf[set][tb], acc[hb][tb], 0, 0, 0);
+  };
+  if (n_steps > 0) {
+    issue_step(0);
+    issue_step(1);
+    __builtin_amdgcn_s_waitcnt(0x0f70 | kLoadsPerStep);  // step 0 has landed
+    __syncthreads();
+    read_frags(0, 0, xf[0], wf[0]);
+  }
+  for (int step = 0; step < n_steps; ++step) {
+    // parts 0..2: the next part's fragments are requested, then the matrix cores work on the current part's
+    read_frags(step, 1, xf[1], wf[1]);
+    mfma_set(0);
+    read_frags(step, 2, xf[0], wf[0]);
+    mfma_set(1);
+    read_frags(step, 3, xf[1], wf[1]);
+    mfma_set(0);
+    // this wavefront has read everything it needs of this step's stage, and its part of the next step has landed;
+    // after the barrier that holds for every wavefront
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * kLoadsPerStep));
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
     __syncthreads();
     read_frags(step + 1, 0, xf[0], wf[0]);  // (after the last step: a stage that holds old data; not used)
 #pragma unroll
     for (int hb = 0; hb < 4; ++hb) {
 #pragma unroll
-      for (int tb = 0; tb < 2; ++tb)
+      for (int tb = 0; tb < 2; ++tb) {
         acc[hb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][hb], xf[1][tb], acc[hb][tb], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      issue_part(step + kStagesG, hb);  // refill this step's stage
-      __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_part(step + kStagesG, 2 * hb + tb);  // refill this step's stage
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     if ((step + 1) % ksteps == 0) {
       // a hidden tile is complete: accumulator v of block hb is hidden unit 32 hb + 8 (v/4) + 4 g + v%4

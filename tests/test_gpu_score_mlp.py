@@ -35,7 +35,7 @@ def _check(got, want):
     return float(err.max())
 
 
-@pytest.mark.parametrize("N,d,dh", [(300, 64, 256), (257, 128, 512), (1000, 256, 768), (5, 32, 256),
+@pytest.mark.parametrize("N,d,dh", [(300, 64, 256), (257, 128, 512), (1000, 256, 768), (5, 64, 256), (700, 192, 256),
                                     (300, 64, 1280)])  # 5 hidden tiles over 4 splits: one split has none
 @pytest.mark.parametrize("act", [0, 1, 2])
 def test_mfma_path_small_shapes(D, N, d, dh, act):
