@@ -106,7 +106,11 @@ int dodo_score_mlp(const void* hidden, const void* W1, const float* b1, const vo
  * sequences).  With it, long sequences are split over several workgroups that exchange histograms and counts
  * through it; without it (NULL or too small) one workgroup per sequence does the same work, more slowly.
  * The workspace must be zero-filled before its first use; a call leaves it zero-filled, so it can be reused by
- * the next call as it is.  It must not be shared by calls that may overlap in time. */
+ * the next call as it is.  It must not be shared by calls that may overlap in time.  The workgroups of a
+ * sequence wait for each other (bounded: about 0.1 s), so they must be able to run at the same time; the form is
+ * only chosen when they fit the GPU together, and work from other streams that keeps compute units busy for
+ * longer than the bound breaks it (the index lists then come out filled with the last token's index, and the
+ * workspace is left non-zero). */
 size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n);
 
 /*
