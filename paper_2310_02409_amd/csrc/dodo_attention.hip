@@ -33,6 +33,7 @@ struct Variant {
   const int32_t* cu_ctx = nullptr;   //   elements between tokens, sequences of at most max_n tokens
   int64_t ctx_stride = 0;
   int32_t max_n = 0;
+  int heavy_last = 0;                // later entries cost more: start with them
 };
 
 int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl, const int32_t* cu_q,
@@ -59,7 +60,7 @@ int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* K
   AttnParams p;
   p.Q = Q; p.Kn = Kn; p.Vn = Vn; p.Kl = Kl; p.Vl = Vl;
   p.cu_q = cu_q; p.cu_nuggets = cu_nuggets; p.nug_len = v.nug_len; p.cu_local = cu_local; p.loc_len = v.loc_len;
-  p.nug_idx = v.nug_idx; p.cu_ctx = v.cu_ctx; p.max_n = v.max_n;
+  p.nug_idx = v.nug_idx; p.cu_ctx = v.cu_ctx; p.max_n = v.max_n; p.heavy_last = v.heavy_last;
   p.B = B; p.H = H; p.H_kv = H_kv; p.d_h = d_h; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
   if (v.nug_idx != nullptr) {
     p.nug_tok_stride = v.ctx_stride;
@@ -137,6 +138,7 @@ extern "C" int dodo_nugget_attention_segments(const void* Q, const void* Kn, con
   dodo::Variant v;
   v.nug_len = seg_nug_len;
   v.loc_len = seg_loc_len;
+  v.heavy_last = 1;
   return dodo::attention_entry(Q, Kn, Vn, K, V, seg_cu_q, seg_nug_start, seg_loc_start, v, n_segments, H, H_kv, d_h,
                                max_q, max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
 }

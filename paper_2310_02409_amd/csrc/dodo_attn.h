@@ -12,6 +12,7 @@ struct AttnParams {
   // gather-free form (both null otherwise): Kn / Vn are the context's K / V, nugget j of sequence b is its token
   // cu_ctx[b] + nug_idx[cu_nuggets[b] + j]
   const int32_t *nug_idx, *cu_ctx;
+  int heavy_last;  // != 0: later entries of the batch cost more (segment plans); the query-block kernel starts with them
   int32_t max_n;  // gather-free form: host-side upper bound on the context length of a sequence
   int32_t B, H, H_kv, d_h, max_q, max_k, max_local;
   int64_t nug_tok_stride, nug_head_stride;  // elements between tokens / KV heads of the nugget cache

@@ -705,8 +705,8 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
     const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
     const int32_t* __restrict__ cu_ctx,
-    int B, int H, int H_kv, int n_qblocks, int pair, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
-    uint16_t* __restrict__ O, float* __restrict__ lse) {
+    int B, int H, int H_kv, int n_qblocks, int pair, int heavy_last, int64_t nug_tok_stride, int64_t nug_head_stride,
+    float scale_log2e, uint16_t* __restrict__ O, float* __restrict__ lse) {
   const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int j = slot / n_groups;
@@ -729,6 +729,12 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     } else {
       bh2 = bh_other;
     }
+  }
+  // heavy_last: the batch's entries grow in cost with their index (segments of a text see more and more nuggets);
+  // workgroups are handed out in index order, so the entries are walked from the back to keep the tail light
+  if (heavy_last) {
+    bh1 = B * H - 1 - bh1;
+    bh2 = B * H - 1 - bh2;
   }
   attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh1, q1,
                               nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
@@ -766,7 +772,7 @@ int launch_nw(const AttnParams& p) {
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
                      static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.nug_idx, p.cu_ctx, p.B, p.H, p.H_kv,
-                     n_qblocks, pair,
+                     n_qblocks, pair, p.heavy_last,
                      p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, static_cast<uint16_t*>(p.O), p.lse);
   return launch_status();
 }
