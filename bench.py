@@ -550,6 +550,13 @@ def main():
             ach = work[dom]["flop"] / avg * 1e-6
             roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+            # a kernel near the ridge: what the two peaks allow together at its algorithmic intensity
+            intensity = work[dom]["flop"] / work[dom]["bytes"]
+            attainable = min(MFMA_BF16_PEAK_TFLOPS, intensity * HBM_PEAK_GBS * 1e-3)
+            roof["intensity_flop_per_byte"] = round(intensity, 1)
+            roof["attainable"] = round(attainable, 1)
+            roof["frac_of_attainable"] = round(ach / attainable, 4)
+            roof["hbm_GBps_at_this_time"] = round(work[dom]["bytes"] / avg * 1e-3, 1)
         else:
             ach = work[dom]["bytes"] / avg * 1e-3
             roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
