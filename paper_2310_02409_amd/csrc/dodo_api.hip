@@ -12,6 +12,13 @@ int record_hip_error(hipError_t e) {
   g_hip_error_text[sizeof(g_hip_error_text) - 1] = '\0';
   return DODO_ERR_HIP;
 }
+
+int compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+  return cus;
+}
 }  // namespace dodo
 
 extern "C" {

@@ -745,13 +745,6 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
   }
 }
 
-int compute_units() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 256;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-  return cus;
-}
-
 template <int NW, bool IDX>
 int launch_nw(const AttnParams& p) {
   using Cfg = BlockCfg<NW>;

@@ -22,6 +22,9 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int elem_bytes(int dtype) { return dtype == DODO_DTYPE_F32 ? 4 : 2; }
 inline bool dtype_ok(int dtype) { return dtype == DODO_DTYPE_F32 || dtype == DODO_DTYPE_BF16; }
 
+// Compute units of the current device (256 if the query fails).
+int compute_units();
+
 // Checks the launch that was just enqueued.
 inline int launch_status() {
   hipError_t e = hipGetLastError();
@@ -53,6 +56,33 @@ __device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// Order-preserving image of an fp32 score as an unsigned key: NaN ranks below everything, -0 == +0.
+__device__ __forceinline__ uint32_t order_key(float s) {
+  uint32_t u = __float_as_uint(s);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Element i of an fp32 or bf16 array as fp32.
+template <int DTYPE>
+__device__ __forceinline__ float load_elem(const void* p, int64_t i) {
+  if (DTYPE == DODO_DTYPE_F32) return static_cast<const float*>(p)[i];
+  return __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t*>(p)[i]) << 16);
+}
+
+// One 16-byte-per-lane direct global->LDS load from base + voff: the lanes' data land at lds_dst + 16*lane; base
+// and lds_dst are wavefront-uniform (base is made so explicitly: the compiler may hold it in vector registers).
+// Inline assembly, so the compiler does not order later LDS reads behind it: callers keep the vmcnt bookkeeping.
+__device__ __forceinline__ void dma16_uniform(const void* base, uint32_t voff, uint32_t lds_dst) {
+  const uint64_t b = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b))));
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b >> 32))));
+  const uint64_t ub = (static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(lds_dst)
+               : "memory");
+}
 
 // number of set bits of `mask` strictly below this lane
 __device__ __forceinline__ int popc_below_lane(uint64_t mask) {

@@ -51,17 +51,6 @@ __device__ __forceinline__ float activation(float h, int act) {
   return tanhf(h);
 }
 
-// One 16-byte-per-lane direct global->LDS load (see the attention kernel for why this is inline
-// assembly): lane data land at lds_dst + 16*lane; base and lds_dst are wavefront-uniform.
-__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_dst) {
-  const uint64_t b = reinterpret_cast<uint64_t>(base);
-  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b))));
-  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b >> 32))));
-  const uint64_t ub = (static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo);
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(lds_dst)
-               : "memory");
-}
-
 __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ W1, const float* __restrict__ b1,
     const uint16_t* __restrict__ w2, float b2, int act, int64_t N, int d, int d_hid, int64_t row_stride, int hsplit,
@@ -109,9 +98,9 @@ __global__ __launch_bounds__(kMlpThreads, 1) void score_mlp_mfma_kernel(
     const uint32_t stage = lds_base + (step % kStagesG) * kStageBytesG;
     const int u = q >> 1;
     if ((q & 1) == 0) {
-      dma16(x_base + ks * kBK, x_off[u], __builtin_amdgcn_readfirstlane(stage + (32 * wave + 8 * u) * 128));
+      dma16_uniform(x_base + ks * kBK, x_off[u], __builtin_amdgcn_readfirstlane(stage + (32 * wave + 8 * u) * 128));
     } else {
-      dma16(W1 + static_cast<int64_t>(ht) * kHidTile * d + ks * kBK, w_off[u],
+      dma16_uniform(W1 + static_cast<int64_t>(ht) * kHidTile * d + ks * kBK, w_off[u],
             __builtin_amdgcn_readfirstlane(stage + kOperandBytes + (32 * wave + 8 * u) * 128));
     }
   };
@@ -246,11 +235,6 @@ __global__ void score_mlp_combine_kernel(const float* __restrict__ partial, int 
 // ---- plain kernel: `kTok` token rows in LDS, one hidden unit per wavefront at a time
 constexpr int kPlainThreads = 256;
 template <int DTYPE>
-__device__ __forceinline__ float load_elem(const void* p, int64_t i) {
-  if (DTYPE == DODO_DTYPE_F32) return static_cast<const float*>(p)[i];
-  return __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t*>(p)[i]) << 16);
-}
-template <int DTYPE>
 __global__ __launch_bounds__(kPlainThreads) void score_mlp_plain_kernel(
     const void* __restrict__ X, const void* __restrict__ W1, const float* __restrict__ b1, const void* __restrict__ w2,
     float b2, int act, int64_t N, int d, int d_hid, int64_t row_stride, int tok_per_wg, float* __restrict__ scores) {
@@ -281,13 +265,6 @@ __global__ __launch_bounds__(kPlainThreads) void score_mlp_plain_kernel(
     s += b2;
     scores[tok0 + threadIdx.x] = (s == 0.f) ? 0.f : s;
   }
-}
-
-int compute_units() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 256;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-  return cus;
 }
 
 bool mfma_path(int dtype, int64_t N, int32_t d, int32_t d_hid, int64_t row_stride, const void* X, const void* W1,

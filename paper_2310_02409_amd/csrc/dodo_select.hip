@@ -32,13 +32,6 @@ constexpr int kMaxChunks = 16;
 constexpr int kWsHist = 0, kWsArrive = 4 * 256, kWsCounts = kWsArrive + 8, kWsPerSeq = kWsCounts + 2 * kMaxChunks;
 constexpr int kMaxPolls = 1 << 17;         // bound of a wait for the other chunks (~0.1 s, never reached in a healthy run)
 
-__device__ __forceinline__ uint32_t order_key(float s) {
-  uint32_t u = __float_as_uint(s);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;  // NaN ranks below everything
-  if (u == 0x80000000u) u = 0u;                    // -0 == +0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 // MULTI: G consecutive workgroups share a sequence (chunk c = blockIdx % G); lds_keys = keys that fit in LDS.
 template <int THREADS, bool STAGED, bool MULTI>
 __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __restrict__ scores,
@@ -329,13 +322,6 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
         __hip_atomic_store(gws + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-}
-
-int compute_units() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 256;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-  return cus;
 }
 
 // Chunks per sequence of the chunked form, or 0 when it does not apply (short sequences, or more workgroups than

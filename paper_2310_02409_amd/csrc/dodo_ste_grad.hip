@@ -41,23 +41,6 @@ constexpr int kLoadsPerTileSte = 4;                // direct loads per wavefront
 constexpr int kMaxQLds = 12288;                    // query rows of a sequence whose lse and D fit in LDS next to the stages
 constexpr float kLog2e = 1.4426950408889634f;
 
-// One 16-byte-per-lane direct global->LDS load: lane data land at lds_dst + 16*lane; base and
-// lds_dst are wavefront-uniform.
-__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_dst) {
-  const uint64_t b = reinterpret_cast<uint64_t>(base);
-  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b))));
-  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b >> 32))));
-  const uint64_t ub = (static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo);
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(lds_dst)
-               : "memory");
-}
-
-template <int DTYPE>
-__device__ __forceinline__ float load_elem(const void* p, int64_t i) {
-  if (DTYPE == DODO_DTYPE_F32) return static_cast<const float*>(p)[i];
-  return __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t*>(p)[i]) << 16);
-}
-
 // D[h][row] = dO[row,h] . O[row,h] and lse2[h][row] = lse[row,h] * log2(e), head-major so that the rows of a head are
 // contiguous.  16 lanes per (row, head), 8 channels per lane and step (d_h % 8 == 0).
 template <int DTYPE>
@@ -174,8 +157,8 @@ __global__ __launch_bounds__(kGradThreads, 2) void ste_grad_mfma_kernel(
       const uint32_t voff = static_cast<uint32_t>(min(tl * kQTile + row, q_b - 1)) * static_cast<uint32_t>(row_stride * 2) +
                             ((l_pos ^ (row & 15)) << 4);
       const uint32_t dst = stage + (8 * wave + 4 * u) * kRowBytes;
-      dma16(q_base, voff, __builtin_amdgcn_readfirstlane(dst));
-      dma16(do_base, voff, __builtin_amdgcn_readfirstlane(dst + kQTile * kRowBytes));
+      dma16_uniform(q_base, voff, __builtin_amdgcn_readfirstlane(dst));
+      dma16_uniform(do_base, voff, __builtin_amdgcn_readfirstlane(dst + kQTile * kRowBytes));
     }
   };
 

@@ -20,13 +20,7 @@ constexpr int kThreshThreads = 1024;
 constexpr int kThreshBatch = 4;  // 64-token groups per wavefront with their loads in flight together
 constexpr int kAppendThreads = 256;
 
-// Order-preserving image of an fp32 score (NaN lowest, -0 == +0) and its inverse on non-NaN keys.
-__device__ __forceinline__ uint32_t order_key(float s) {
-  uint32_t u = __float_as_uint(s);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;
-  if (u == 0x80000000u) u = 0u;
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
+// Inverse of order_key on non-NaN keys.
 __device__ __forceinline__ float key_to_score(uint32_t key) {
   if (key == 0u) return -__builtin_inff();  // NaN ranks lowest: everything that can be kept is kept
   return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
