@@ -108,9 +108,14 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   for (int e = 0; e < kEPL; ++e) o[e] = 0.f;
 
   const int64_t ctx0 = INDEXED ? cu_ctx[b] : 0;
-  for (int j0 = r0; j0 < r1; j0 += kGroups * kRowsInFlight) {
+  // A batch = kRowsInFlight rows per group.  The loads of batch i+1 are issued before the arithmetic of batch i
+  // (two register sets), so that the memory latency is paid once per workgroup, not once per batch.
+  struct Batch {
     uint4 kv[kRowsInFlight], vv[kRowsInFlight];
-    bool valid[kRowsInFlight];
+    int j0;
+  };
+  auto load_batch = [&](Batch& bt, int j0) {
+    bt.j0 = j0;
     int tok[kRowsInFlight];  // INDEXED: sequence-local token of a nugget row (all index loads go out before the rows')
     if (INDEXED) {
 #pragma unroll
@@ -125,27 +130,28 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
       // loads are unconditional (rows past the end re-read the last row of the range and are
       // discarded): a branch around them would serialise the loads behind a full wait
       const int jr = j0 + u * kGroups + g;
-      valid[u] = jr < r1;
-      const int j = valid[u] ? jr : r1 - 1;
+      const int j = jr < r1 ? jr : r1 - 1;
       const bool nug = j < k_b;
       const int64_t nug_row = INDEXED ? ctx0 + tok[u] : static_cast<int64_t>(k0 + j);
       const int64_t off = nug ? (nug_row * nug_tok_stride + nug_base) * kEs
                               : (static_cast<int64_t>(l0 + j - k_b) * H_kv * DH + loc_base) * kEs;
-      kv[u] = load16_stream(static_cast<const char*>(nug ? Kn : Kl) + off);
-      vv[u] = load16_stream(static_cast<const char*>(nug ? Vn : Vl) + off);
+      bt.kv[u] = load16_stream(static_cast<const char*>(nug ? Kn : Kl) + off);
+      bt.vv[u] = load16_stream(static_cast<const char*>(nug ? Vn : Vl) + off);
     }
+  };
+  auto use_batch = [&](const Batch& bt) {
     float logit[kRowsInFlight];
     float mx = m;
 #pragma unroll
     for (int u = 0; u < kRowsInFlight; ++u) {
       float kf[kEPL];
-      VT::unpack(kv[u], kf);
+      VT::unpack(bt.kv[u], kf);
       float d = q[0] * kf[0];
 #pragma unroll
       for (int e = 1; e < kEPL; ++e) d = fmaf(q[e], kf[e], d);
 #pragma unroll
       for (int off = kLPR / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, kWave);
-      logit[u] = valid[u] ? d : kNegInf;
+      logit[u] = (bt.j0 + u * kGroups + g < r1) ? d : kNegInf;
       mx = fmaxf(mx, logit[u]);
     }
     if (mx != kNegInf) {  // uniform inside a group
@@ -157,12 +163,27 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
       for (int u = 0; u < kRowsInFlight; ++u) {
         const float p = exp2_guard(logit[u] - mx);
         float vf[kEPL];
-        VT::unpack(vv[u], vf);
+        VT::unpack(bt.vv[u], vf);
         ssum += p;
 #pragma unroll
         for (int e = 0; e < kEPL; ++e) o[e] = fmaf(p, vf[e], o[e]);
       }
       m = mx;
+    }
+  };
+  {
+    constexpr int kStep = kGroups * kRowsInFlight;
+    Batch ba, bb;
+    int j0 = r0;  // (uniform over the workgroup, like r1)
+    if (j0 < r1) load_batch(ba, j0);
+    while (j0 < r1) {
+      if (j0 + kStep < r1) load_batch(bb, j0 + kStep);
+      use_batch(ba);
+      j0 += kStep;
+      if (j0 >= r1) break;
+      if (j0 + kStep < r1) load_batch(ba, j0 + kStep);
+      use_batch(bb);
+      j0 += kStep;
     }
   }
 
