@@ -17,22 +17,12 @@ namespace {
 constexpr int kGatherThreads = 256;
 constexpr int kMaxVec = 4;  // 16-byte vectors per thread per tensor held in registers at once
 
+// Copies row src_tok of K and V (of the layer given by blockIdx.y) to row dst_tok of the nugget cache.
 template <bool HEAD_MAJOR>
-__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
-    const uint4* __restrict__ K, const uint4* __restrict__ V, const int32_t* __restrict__ nugget_idx,
-    const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt,
-    int vec_per_head, int vec_per_row, int64_t token_stride_vec, int64_t src_layer_stride_vec,
-    int64_t dst_layer_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
-  const int64_t dst_tok = blockIdx.x;
-  if (dst_tok >= cu_nuggets[B]) return;  // Kt may be an upper bound of the nugget count
-  // sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1]
-  int lo = 0, hi = B;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (cu_nuggets[mid] <= dst_tok) lo = mid; else hi = mid;
-  }
-  const int b = lo;
-  const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
+__device__ __forceinline__ void copy_row(const uint4* __restrict__ K, const uint4* __restrict__ V, int64_t src_tok,
+                                         int64_t dst_tok, int64_t Kt, int vec_per_head, int vec_per_row,
+                                         int64_t token_stride_vec, int64_t src_layer_stride_vec,
+                                         int64_t dst_layer_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
   const int64_t layer = blockIdx.y;
   const uint4* ksrc = K + layer * src_layer_stride_vec + src_tok * token_stride_vec;
   const uint4* vsrc = V + layer * src_layer_stride_vec + src_tok * token_stride_vec;
@@ -65,6 +55,40 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
       }
     }
   }
+}
+
+template <bool HEAD_MAJOR>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const int32_t* __restrict__ nugget_idx,
+    const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt,
+    int vec_per_head, int vec_per_row, int64_t token_stride_vec, int64_t src_layer_stride_vec,
+    int64_t dst_layer_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
+  const int64_t dst_tok = blockIdx.x;
+  // Sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1].  The lookups before the row copy are a chain of
+  // dependent loads, each a full memory latency; for up to 64 sequences every lane of a wavefront fetches one
+  // boundary and a ballot finds b, which leaves two levels (boundaries and index in parallel, then the sequence start).
+  int b;
+  if (B <= kWave) {
+    const int lane = lane_id();
+    const int bound = cu_nuggets[min(lane + 1, B)];  // upper boundary of sequence `lane`
+    const uint64_t above = __ballot(lane < B && bound > dst_tok);  // sequences that end after dst_tok
+    if (above == 0) return;  // dst_tok >= cu_nuggets[B]: Kt may be an upper bound of the nugget count
+    b = __ffsll(static_cast<long long>(above)) - 1;
+    const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
+    copy_row<HEAD_MAJOR>(K, V, src_tok, dst_tok, Kt, vec_per_head, vec_per_row, token_stride_vec, src_layer_stride_vec,
+                         dst_layer_stride_vec, Kn, Vn);
+    return;
+  }
+  if (dst_tok >= cu_nuggets[B]) return;
+  int lo = 0, hi = B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu_nuggets[mid] <= dst_tok) lo = mid; else hi = mid;
+  }
+  b = lo;
+  const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
+  copy_row<HEAD_MAJOR>(K, V, src_tok, dst_tok, Kt, vec_per_head, vec_per_row, token_stride_vec, src_layer_stride_vec,
+                       dst_layer_stride_vec, Kn, Vn);
 }
 
 int gather_entry(const void* K, const void* V, int dtype, const int32_t* nugget_idx, const int32_t* cu_seqlens,
