@@ -1,16 +1,20 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
 Inputs are generated once (on the GPU, for speed) and the same bits are copied to the host for the
-oracle.  Index work is compared in full and bit for bit; floating-point outputs are compared on
-sampled rows that the oracle computes one by one.
+oracle.  Scores, index lists, the gather and the attention output are compared in full, over whole tensors
+(of one layer for the workloads that have many); the output buffers are filled with NaN before every call,
+so a row that no workgroup wrote fails.  The oracle itself is single-threaded: the harness runs several
+independent instances over disjoint rows side by side.
 """
+import concurrent.futures
+
 import numpy as np
 import pytest
 import torch
 
 import oracle
 import workloads as W
-from gpu_util import dev
+from gpu_util import (check_rows, dev, nan_outputs, oracle_attention_rows_parallel, oracle_workers, slab_rows)
 
 pytestmark = pytest.mark.gpu
 
@@ -21,68 +25,85 @@ def D():
     return D
 
 
-def _sample_rows(rng, wl, n):
-    rows = []
-    for _ in range(n):
-        b = int(rng.integers(wl.B))
-        rows.append((b, int(rng.integers(wl.H)), int(rng.integers(wl.q_lens[b]))))
-    # first / last rows of the first and last sequence, and rows around the 128- and 256-row block edges
-    rows += [(0, 0, 0), (wl.B - 1, wl.H - 1, wl.q_lens[-1] - 1)]
-    for i in (127, 128, 255, 256):
-        if i < wl.q_lens[0]:
-            rows.append((0, 1 % wl.H, i))
-    return rows
+def _oracle_score_parallel(hidden, w):
+    n_workers = oracle_workers()
+    pieces = [p for p in np.array_split(np.arange(hidden.shape[0]), 4 * n_workers) if len(p)]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=n_workers) as ex:
+        outs = list(ex.map(lambda p: oracle.score(hidden[p[0]:p[-1] + 1], w), pieces))
+    return np.concatenate(outs)
 
 
-def _run_full(D, cfg, layer=0, flags=1, n_rows=40, seed=0):
-    wl = W.config(cfg)
-    g = W.make_inputs(wl, dev(), layer=layer)
+def _run_compress(D, wl, g, flags, end_to_end=True):
+    """score -> select -> gather at full size against the oracle; returns what the attention checks need."""
     ks = [oracle.nugget_count(n, wl.keep_num, wl.keep_den) for n in wl.seq_lens]
     cu_k_h = oracle.cu_from_lengths(ks)
     cu_k, ks_lib = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev())
     assert ks_lib == ks
     Kt = sum(ks)
-    scale = wl.d_h ** -0.5
-    rng = np.random.default_rng(seed)
-
-    # ---- scorer: sampled rows ----
-    s = D.dodo_score(g["hidden"], g["w"])
-    rows = np.unique(np.concatenate([rng.integers(0, wl.N, 192), [0, wl.N - 1]]))
-    hid_rows = W.to_numpy(g["hidden"][torch.from_numpy(rows).to(dev())])
-    s_ref = oracle.score(hid_rows, W.to_numpy(g["w"]))
-    s_gpu = s.cpu().numpy()
-    assert np.all(np.abs(s_gpu[rows] - s_ref) <= 1e-5 * (1 + np.abs(s_ref)))
-
-    # ---- selection on the shared score array (quantised to 16 levels for the tie-stress workload) ----
-    s_sel = W.quantise16(s) if wl.quantise_scores else s
-    idx = D.dodo_select_topk(s_sel, g["cu_seqlens"], cu_k, max(wl.seq_lens), max(ks), Kt, flags)
     cu_s_h = W.to_numpy(g["cu_seqlens"])
+
+    # ---- scorer: every row ----
+    s = D.dodo_score(g["hidden"], g["w"], scores=torch.full((wl.N,), float("nan"), device=dev()))
+    s_ref = _oracle_score_parallel(W.to_numpy(g["hidden"]), W.to_numpy(g["w"]))
+    s_gpu = s.cpu().numpy()
+    assert np.all(np.abs(s_gpu - s_ref) <= 1e-5 * (1 + np.abs(s_ref)))
+
+    # ---- selection on a shared score array, both ways (quantised to 16 levels for the tie-stress workload) ----
+    s_sel = W.quantise16(s) if wl.quantise_scores else s
+    idx = D.dodo_select_topk(s_sel, g["cu_seqlens"], cu_k, max(wl.seq_lens), max(ks), Kt, flags,
+                             nugget_idx=torch.full((Kt,), -1, dtype=torch.int32, device=dev()))
     idx_ref = oracle.select_topk(s_sel.cpu().numpy(), cu_s_h, cu_k_h, flags)
     assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    s_ref_t = torch.from_numpy(s_ref).to(dev())
+    s_ref_sel = W.quantise16(s_ref_t) if wl.quantise_scores else s_ref_t
+    idx_o = oracle.select_topk(s_ref_sel.cpu().numpy(), cu_s_h, cu_k_h, flags)
+    idx_go = D.dodo_select_topk(s_ref_sel, g["cu_seqlens"], cu_k, max(wl.seq_lens), max(ks), Kt, flags)
+    assert np.array_equal(idx_go.cpu().numpy(), idx_o)
+
+    # ---- raw hidden states to indices, each side on its own scores: the lists may differ only in a sequence
+    # where the scores around the k-th place lie closer together than the scorer's tolerance, and then only by
+    # tokens at that place (with these seeds no such sequence is expected; one that appears is reported)
+    if end_to_end:
+        free = 1 if flags & 1 else 0  # the forced last token does not compete
+        for b in range(wl.B):
+            a = set(idx_ref[cu_k_h[b]:cu_k_h[b + 1]].tolist())
+            o = set(idx_o[cu_k_h[b]:cu_k_h[b + 1]].tolist())
+            if a == o:
+                continue
+            seq = s_ref[cu_s_h[b]:cu_s_h[b + 1]].astype(np.float64)
+            kth = np.sort(seq[:len(seq) - free])[::-1][ks[b] - free - 1]
+            gaps = {i: abs(seq[i] - kth) for i in sorted(a ^ o)}
+            print(f"{wl.name}: sequence {b}: index lists from the two scorers differ at {gaps}")
+            assert all(gap <= 2e-5 for gap in gaps.values()), (b, gaps)
 
     # ---- gather: full, bit for bit ----
     Kn, Vn = D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt)
     Kn_ref, Vn_ref = oracle.gather(W.to_numpy(g["K"]), W.to_numpy(g["V"]), idx_ref, cu_s_h, cu_k_h)
     assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)
+    return Kn, Vn, Kn_ref, Vn_ref, cu_k, cu_k_h, ks
 
-    # ---- attention: sampled rows ----
-    O, lse = D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"],
-                                     max(wl.q_lens), max(ks), max(wl.local_lens), scale, want_lse=True)
-    srows = _sample_rows(rng, wl, n_rows)
+
+def _sampled_rows(rng, wl, n):
+    rows = [(int(rng.integers(wl.B)),) for _ in range(n)]
+    return [(b, int(rng.integers(wl.H)), int(rng.integers(wl.q_lens[b]))) for (b,) in rows]
+
+
+def _run_full(D, cfg, layer=0, flags=1, slabs="all", n_sampled=0, seed=0, end_to_end=True):
+    """slabs: "all" (whole tensor) or a list of (sequence, head) pairs compared over all their query rows."""
+    wl = W.config(cfg)
+    g = W.make_inputs(wl, dev(), layer=layer)
+    Kn, Vn, Kn_ref, Vn_ref, cu_k, cu_k_h, ks = _run_compress(D, wl, g, flags, end_to_end)
+    scale = wl.d_h ** -0.5
+    O, lse = nan_outputs(g["Q"], wl.H)
+    D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max(wl.q_lens), max(ks),
+                            max(wl.local_lens), scale, O=O, lse=lse)
+    assert torch.isfinite(O.float()).all() and torch.isfinite(lse).all()  # every row was written
+    if slabs == "all":
+        slabs = [(b, h) for b in range(wl.B) for h in range(wl.H)]
+    rows = slab_rows(slabs, wl.q_lens) + _sampled_rows(np.random.default_rng(seed), wl, n_sampled)
     h = {k: W.to_numpy(g[k]) for k in ("Q", "Kl", "Vl", "cu_q", "cu_local")}
-    O_ref, lse_ref = oracle.attention_rows(h["Q"], Kn_ref, Vn_ref, h["Kl"], h["Vl"], h["cu_q"], cu_k_h,
-                                           h["cu_local"], scale, srows)
-    cq = h["cu_q"]
-    got = np.stack([O[int(cq[b]) + i, hh].float().cpu().numpy() for b, hh, i in srows]).astype(np.float64)
-    got_lse = np.array([float(lse[int(cq[b]) + i, hh]) for b, hh, i in srows])
-    if wl.dtype == torch.float32:
-        assert np.max(np.abs(got - O_ref)) <= 1e-5 * np.max(np.abs(O_ref))
-        assert np.all(np.abs(got - O_ref) <= 1e-5 * np.abs(O_ref) + 1e-6)
-        assert np.max(np.abs(got_lse - lse_ref) / (1 + np.abs(lse_ref))) <= 1e-5
-    else:
-        assert np.max(np.abs(got - O_ref)) <= 2e-2, np.max(np.abs(got - O_ref))
-        assert np.max(np.abs(got_lse - lse_ref)) <= 2e-2
-    assert torch.isfinite(O.float()).all()
+    O_ref, lse_ref = oracle_attention_rows_parallel(h, Kn_ref, Vn_ref, cu_k_h, scale, rows)
+    check_rows(O, lse, h["cu_q"], rows, O_ref, lse_ref, wl.dtype)
     return wl, g, (Kn, Vn, Kn_ref, Vn_ref, cu_k, cu_k_h, ks), scale
 
 
@@ -91,31 +112,35 @@ def test_workload_1_tiny_fp32(D):
 
 
 def test_workload_2_llama7b_prefill_and_decode_token(D):
+    # whole tensor: 8 sequences x 32 heads x 512 rows (two query blocks per workgroup, cross-paired)
     wl, g, (Kn, Vn, Kn_ref, Vn_ref, cu_k, cu_k_h, ks), scale = _run_full(D, 2)
-    # the decode sub-step of the benchmark: one new token per sequence over nuggets + 641 local rows
+    # the decode sub-step of the benchmark: one new token per sequence over nuggets + 641 local rows, every head
     B = wl.B
     dec_local = [m + 1 for m in wl.local_lens]
     Qd = W.normal(wl.seed, 10, (B, wl.H, wl.d_h), 1.0, wl.dtype, dev())
     Kld = W.normal(wl.seed, 11, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev())
     Vld = W.normal(wl.seed, 12, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev())
     cu_qd, cu_ld = W.cumulative([1] * B, dev()), W.cumulative(dec_local, dev())
-    Od, _ = D.dodo_nugget_attention(Qd, Kn, Vn, Kld, Vld, cu_qd, cu_k, cu_ld, 1, max(ks), max(dec_local), scale)
-    rows = [(b, hh, 0) for b in range(B) for hh in (0, 13, 31)]
-    O_ref, _ = oracle.attention_rows(W.to_numpy(Qd), Kn_ref, Vn_ref, W.to_numpy(Kld), W.to_numpy(Vld),
-                                     W.to_numpy(cu_qd), cu_k_h, W.to_numpy(cu_ld), scale, rows)
-    got = np.stack([Od[b, hh].float().cpu().numpy() for b, hh, _ in rows])
-    assert np.max(np.abs(got - O_ref)) <= 2e-2
+    Od, lsed = nan_outputs(Qd, wl.H)
+    D.dodo_nugget_attention(Qd, Kn, Vn, Kld, Vld, cu_qd, cu_k, cu_ld, 1, max(ks), max(dec_local), scale, O=Od, lse=lsed)
+    rows = [(b, hh, 0) for b in range(B) for hh in range(wl.H)]
+    h = dict(Q=W.to_numpy(Qd), Kl=W.to_numpy(Kld), Vl=W.to_numpy(Vld), cu_q=W.to_numpy(cu_qd), cu_local=W.to_numpy(cu_ld))
+    O_ref, lse_ref = oracle_attention_rows_parallel(h, Kn_ref, Vn_ref, cu_k_h, scale, rows)
+    check_rows(Od, lsed, h["cu_q"], rows, O_ref, lse_ref, wl.dtype)
 
 
 def test_workload_3_ragged_decode_one_layer(D):
-    # batch 64, ragged contexts in [4096, 8192] at 20x, 256 local tokens + the new token, q = 1 (split-K kernel)
-    _run_full(D, 3, layer=5, n_rows=64)
+    # batch 64, ragged contexts in [4096, 8192] at 20x, 256 local tokens + the new token, q = 1 (split-K kernel):
+    # all 64 x 32 rows
+    _run_full(D, 3, layer=5)
 
 
 def test_workload_4_llama13b_autoencode_one_layer(D):
-    _run_full(D, 4, layer=3, n_rows=32)
+    # one layer, whole tensor: 16 x 40 (sequence, head) pairs of 2048 causal rows (757 GFLOP for the oracle, spread
+    # over independent single-threaded instances)
+    _run_full(D, 4, layer=3)
 
 
 def test_workload_5_long_context_tie_stress(D):
-    _run_full(D, 5, flags=0, n_rows=32)
-    _run_full(D, 5, flags=1, n_rows=8, seed=1)
+    _run_full(D, 5, flags=0, end_to_end=False)  # whole tensor: 2 x 32 x 1024 rows over 3277 nuggets
+    _run_full(D, 5, flags=1, slabs=[(0, 0), (1, 31)], n_sampled=64, seed=1, end_to_end=False)

@@ -49,3 +49,21 @@ def test_meanpool_workload_shape_sampled_rows(D):
     Kr, Vr = oracle.meanpool(W.to_numpy(g["K"][a:a + n].cpu()), W.to_numpy(g["V"][a:a + n].cpu()), _cu([n]), _cu([k]))
     o = sum(ks[:3])
     assert np.array_equal(W.to_numpy(Kn[o:o + k].cpu()), Kr) and np.array_equal(W.to_numpy(Vn[o:o + k].cpu()), Vr)
+
+
+def test_meanpool_one_rounding_where_two_would_differ(D):
+    # chunks {x, y, t, 0} whose exact mean is 2^-42 away from the midpoint of two bf16 values: rounding through
+    # single precision would tie to even; the kernel, like the oracle, rounds the double once
+    quads = [(0x3F80, 0x3F81, 0x2B80), (0x3F80, 0x3F81, 0xAB80), (0x3F81, 0x3F82, 0x2B80), (0x3F81, 0x3F82, 0xAB80),
+             (0xBF80, 0xBF81, 0xAB80), (0x3F80, 0x3F80, 0xAB80)]
+    H_kv, d_h = 2, 64
+    rows = np.array([[x, y, t, 0] for x, y, t in quads], dtype=np.uint16).reshape(-1)  # 6 chunks of 4 tokens
+    K = np.repeat(rows[:, None, None], H_kv, axis=1).repeat(d_h, axis=2)
+    cu_s, cu_k = _cu([len(rows)]), _cu([len(quads)])
+    Kn_ref, Vn_ref = oracle.meanpool(K, K, cu_s, cu_k)
+    Kt_ = torch.from_numpy(K.view(np.int16)).view(torch.bfloat16).to(dev())
+    through_fp32 = W.to_numpy(Kt_.double().view(len(quads), 4, H_kv, d_h).mean(dim=1).float().bfloat16())
+    assert not np.array_equal(through_fp32, Kn_ref)  # the inputs do sit in the trap
+    Kn, Vn = D.dodo_meanpool_nuggets(Kt_, Kt_, torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()),
+                                     len(quads))
+    assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)

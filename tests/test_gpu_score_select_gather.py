@@ -220,3 +220,36 @@ def test_gather_layers_bit_exact(D, dtype, L, H_kv, d_h, layout):
     D.dodo_gather_nuggets_layers(Kp[:, :, :H_kv], Vp[:, :, :H_kv], *args, Kn=Kbig[:, 0], Vn=Vbig[:, 0])
     assert np.array_equal(W.to_numpy(Kbig[:, 0]), Kn_ref) and np.array_equal(W.to_numpy(Vbig[:, 0]), Vn_ref)
     assert bool((Kbig[:, 1] == 7.0).all()) and bool((Vbig[:, 1] == 7.0).all())
+
+
+@pytest.mark.parametrize("B", [65, 130, 200])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_gather_many_sequences(D, B, layout):
+    # more than 64 sequences: the destination row's sequence is found by the binary search, not the ballot;
+    # empty sequences, sequences without nuggets, and (token-major) a nugget total given as an upper bound
+    n_lens = [int(v) for v in W.integers(320, 7, (B,), 0, 90)]
+    n_lens[3], n_lens[B - 1] = 0, 57
+    k_lens = [min(n, int(v)) for n, v in zip(n_lens, W.integers(320, 8, (B,), 0, 12))]
+    k_lens[5], k_lens[B - 1] = 0, 9
+    N, Kt = sum(n_lens), sum(k_lens)
+    H_kv, d_h, dtype = 6, 128, torch.bfloat16
+    K, V = W.normal(320, 0, (N, H_kv, d_h), 1.0, dtype), W.normal(320, 1, (N, H_kv, d_h), 1.0, dtype)
+    cu_s, cu_k = oracle.cu_from_lengths(n_lens), oracle.cu_from_lengths(k_lens)
+    idx = oracle.select_topk(W.normal(320, 2, (N,), 1.0, torch.float32).numpy(), cu_s, cu_k)
+    Kn_ref, Vn_ref = oracle.gather(W.to_numpy(K), W.to_numpy(V), idx, cu_s, cu_k, layout)
+    to = lambda a: torch.from_numpy(a).to(dev())
+    Kd, Vd = K.to(dev()), V.to(dev())
+    Kn, Vn = D.dodo_gather_nuggets(Kd, Vd, to(idx), to(cu_s), to(cu_k), Kt, layout)
+    assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)
+    # the same through the all-layers entry point (two layers reading the same rows)
+    K2, V2 = torch.stack([Kd, Kd]), torch.stack([Vd, Vd])
+    Kn2, Vn2 = D.dodo_gather_nuggets_layers(K2, V2, to(idx), to(cu_s), to(cu_k), Kt, layout)
+    for l in range(2):
+        assert torch.equal(Kn2[l], Kn) and torch.equal(Vn2[l], Vn)
+    if layout == 0:
+        extra = 37
+        Kb = torch.full((Kt + extra, H_kv, d_h), 7.0, dtype=dtype, device=dev())
+        Vb = torch.full_like(Kb, 7.0)
+        D.dodo_gather_nuggets(Kd, Vd, to(idx), to(cu_s), to(cu_k), Kt + extra, layout, Kn=Kb, Vn=Vb)
+        assert torch.equal(Kb[:Kt], Kn) and torch.equal(Vb[:Kt], Vn)
+        assert bool((Kb[Kt:] == 7.0).all()) and bool((Vb[Kt:] == 7.0).all())

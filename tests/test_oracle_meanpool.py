@@ -60,3 +60,47 @@ def test_head_major_layout_and_k_v_not_swapped():
     ah, bh = oracle.meanpool(K, V, _cu([20]), _cu([5]), oracle.HEAD_MAJOR)
     assert np.array_equal(ah, a.transpose(1, 0, 2)) and np.array_equal(bh, b.transpose(1, 0, 2))
     assert not np.array_equal(a, b)
+
+
+def _bf16_value(bits: int):
+    from fractions import Fraction
+    sign = -1 if bits & 0x8000 else 1
+    e, m = (bits >> 7) & 0xFF, bits & 0x7F
+    assert 0 < e < 255
+    return sign * (Fraction(128 + m, 128) * Fraction(2) ** (e - 127))
+
+
+def _nearest_bf16_bits(x):
+    """Round-to-nearest-even of an exact rational to bf16, by comparing exact distances (normal range only)."""
+    start = int(np.array([float(x)], dtype=np.float32).view(np.uint32)[0]) >> 16
+    best = None
+    for bits in range(start - 2, start + 3):
+        dist = abs(_bf16_value(bits) - x)
+        if best is None or dist < best[0] or (dist == best[0] and bits % 2 == 0):
+            best = (dist, bits)
+    return best[1]
+
+
+@pytest.mark.parametrize("x_bits,y_bits,t_exp,t_sign,trap", [
+    (0x3F80, 0x3F81, -40, +1, True),    # mean = midpoint + 2^-42: up, to the odd neighbour (two roundings: even)
+    (0x3F80, 0x3F81, -40, -1, False),   # midpoint - 2^-42: down, which is also where a tie would go
+    (0x3F81, 0x3F82, -40, +1, False),   # midpoint whose even neighbour is above: up either way
+    (0x3F81, 0x3F82, -40, -1, True),    # down, to the odd neighbour
+    (0xBF80, 0xBF81, -40, -1, True),    # negative mirror of the first case
+    (0x3F80, 0x3F80, -40, -1, False),   # just below a representable value: the fp32 rounding goes up past it
+])
+def test_one_rounding_in_the_double_rounding_trap(x_bits, y_bits, t_exp, t_sign, trap):
+    # A chunk of four bf16 rows {x, y, t, 0} whose exact mean lies 2^-42 away from the midpoint of two bf16
+    # values.  Rounding it to fp32 first lands exactly on the midpoint and a second rounding then ties to even;
+    # the pooled row is defined with ONE rounding of the exact mean.  Expected bits from exact rationals.
+    from fractions import Fraction
+    t = t_sign * Fraction(2) ** t_exp
+    t_bits = ((127 + t_exp) << 7) | (0x8000 if t_sign < 0 else 0)
+    assert _bf16_value(t_bits) == t
+    mean = (_bf16_value(x_bits) + _bf16_value(y_bits) + t) / 4
+    want = _nearest_bf16_bits(mean)
+    two_roundings = int(torch.tensor([float(mean)], dtype=torch.float64).float().bfloat16().view(torch.int16)[0]) & 0xFFFF
+    K = np.array([x_bits, y_bits, t_bits, 0], dtype=np.uint16).reshape(4, 1, 1).repeat(8, axis=2)
+    Kn, Vn = oracle.meanpool(K, K, _cu([4]), _cu([1]))
+    assert int(Kn[0, 0, 0]) == want and int(Vn[0, 0, 3]) == want
+    assert (two_roundings != want) == trap  # rounding through fp32 gets the trap cases wrong
