@@ -41,6 +41,7 @@ extern "C" {
 #define DODO_ERR_UNSUPPORTED (-2)         /* dtype / head_dim / alignment outside the supported set */
 #define DODO_ERR_WORKSPACE_TOO_SMALL (-3) /* ws_bytes below what the *_workspace_bytes query returns */
 #define DODO_ERR_HIP (-4)                 /* a HIP runtime call failed (launch error, no device) */
+#define DODO_ERR_SCRATCH_LIMIT (-5)       /* the problem needs more than the library's static scratch buffer holds */
 
 /* element types of hidden states / Q / K / V (scores are always fp32) */
 #define DODO_DTYPE_F32 0
@@ -187,6 +188,26 @@ int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const v
                           int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k, int32_t max_local,
                           int64_t Kt, float softmax_scale, int dtype, int layout, void* O, float* lse, void* ws,
                           size_t ws_bytes, void* stream);
+
+/*
+ * dodo_nugget_attention for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and kernels
+ * as dodo_nugget_attention without `ws` / `ws_bytes`: the split-K kernel's partial results and flags go
+ * to a buffer inside the library (a static device array of about 2.1 MB that every GPU the library runs
+ * on holds until the process ends); the call itself allocates and frees nothing.  The buffer has room for
+ * DODO_NOALLOC_MAX_PARTIALS partial results, i.e. (sequence, query row, head, split) combinations of a
+ * call that splits (dodo_nugget_attention_workspace_bytes / ((d_h + 3) * 4) gives the number for given
+ * bounds; 0 means the call needs no buffer at all and always fits); beyond that the call returns
+ * DODO_ERR_SCRATCH_LIMIT and launches nothing.  All calls on one GPU share that GPU's buffer: calls that
+ * may overlap in time on one GPU (different streams, different threads) race and must not be made; calls
+ * on one stream are ordered and safe.  Each call leaves the buffer's flags cleared for the next.
+ */
+#define DODO_NOALLOC_MAX_PARTIALS 4096
+int dodo_nugget_attention_noalloc(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                                  const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local, int32_t B,
+                                  int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
+                                  int32_t max_local, int64_t Kt, float softmax_scale, int dtype, int layout, void* O,
+                                  float* lse, void* stream);
 
 /*
  * Compaction of the pooling baseline the paper compares with (Sec. 5.1: the text is chunked evenly

@@ -67,6 +67,9 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_attention.restype = ctypes.c_int
     L.dodo_nugget_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
                                         ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
+    L.dodo_nugget_attention_noalloc.restype = ctypes.c_int
+    L.dodo_nugget_attention_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
+                                                ctypes.c_int, ctypes.c_int, vp, vp, vp]
     L.dodo_score_mlp_workspace_bytes.restype = sz
     L.dodo_score_mlp_workspace_bytes.argtypes = [ctypes.c_int, i64, i32, i32]
     L.dodo_score_mlp.restype = ctypes.c_int
@@ -253,6 +256,22 @@ def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, K
                                      float(softmax_scale), code, layout, _ptr(O), _ptr(lse), _ptr(ws),
                                      0 if ws is None else ws.numel(), _stream()), "dodo_nugget_attention")
     return O, lse
+
+
+def dodo_nugget_attention_noalloc(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, Kl: torch.Tensor,
+                                  Vl: torch.Tensor, cu_q: torch.Tensor, cu_nuggets: torch.Tensor,
+                                  cu_local: torch.Tensor, max_q: int, max_k: int, max_local: int, softmax_scale: float,
+                                  layout: int, O: torch.Tensor, lse: Optional[torch.Tensor] = None) -> None:
+    """dodo_nugget_attention into the caller's O (and lse) with the library's own static scratch buffer:
+    neither this wrapper nor the call allocates anything."""
+    _dev(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, O, lse)
+    Sq, H, d_h = Q.shape
+    _check(lib.dodo_nugget_attention_noalloc(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(Kl), _ptr(Vl), _ptr(cu_q),
+                                             _ptr(cu_nuggets), _ptr(cu_local), cu_q.numel() - 1, H, Kl.shape[1], d_h,
+                                             max_q, max_k, max_local,
+                                             Kn.shape[0] if layout == TOKEN_MAJOR else Kn.shape[1],
+                                             float(softmax_scale), _dtype_code(Q), layout, _ptr(O), _ptr(lse),
+                                             _stream()), "dodo_nugget_attention_noalloc")
 
 
 def dodo_nugget_attention_indexed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, nugget_idx: torch.Tensor,

@@ -32,6 +32,7 @@ const char* dodo_status_string(int status) {
     case DODO_ERR_UNSUPPORTED: return "unsupported dtype, head size or alignment";
     case DODO_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case DODO_ERR_HIP: return dodo::g_hip_error_text;
+    case DODO_ERR_SCRATCH_LIMIT: return "problem exceeds the library's static scratch buffer";
     default: return "unknown status";
   }
 }

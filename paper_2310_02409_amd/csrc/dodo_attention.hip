@@ -1,5 +1,7 @@
 // dodo_nugget_attention: argument checks and dispatch between the MFMA
 // query-block kernel and the bandwidth-bound split-K kernel.
+#include <mutex>
+
 #include "dodo_attn.h"
 
 namespace dodo {
@@ -34,6 +36,7 @@ struct Variant {
   int64_t ctx_stride = 0;
   int32_t max_n = 0;
   int heavy_last = 0;                // later entries cost more: start with them
+  void* ws_flags = nullptr;          // split-K flag words kept apart from the records in ws
 };
 
 int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl, const int32_t* cu_q,
@@ -74,7 +77,7 @@ int attention_entry(const void* Q, const void* Kn, const void* Vn, const void* K
   }
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.dtype = dtype;
-  p.O = O; p.lse = lse; p.ws = ws;
+  p.O = O; p.lse = lse; p.ws = ws; p.ws_flags = v.ws_flags;
   p.stream = static_cast<hipStream_t>(stream);
   if (use_block_kernel(dtype, d_h, max_q)) return launch_block_attention(p);
   return launch_splitk_attention(p);
@@ -90,6 +93,68 @@ extern "C" int dodo_nugget_attention(const void* Q, const void* Kn, const void* 
                                      void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
   return dodo::attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, dodo::Variant{}, B, H, H_kv, d_h, max_q,
                                max_k, max_local, Kt, softmax_scale, dtype, layout, O, lse, ws, ws_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing: the split-K kernel's partial records and flags live in a
+// file-scope device array.  Its name is only a host-side handle: the device address is looked up once per
+// device and kept, and that pointer is what the kernels get.
+namespace dodo {
+namespace {
+
+constexpr int kScratchSlots = DODO_NOALLOC_MAX_PARTIALS;            // (query row, head, split) records
+constexpr size_t kScratchFlagBytes = kScratchSlots * sizeof(uint32_t);
+constexpr size_t kScratchRecordBytes = static_cast<size_t>(kScratchSlots) * (128 + 2) * sizeof(float);
+constexpr size_t kScratchBytes = kScratchFlagBytes + kScratchRecordBytes;
+
+// flags first (zero when the library is loaded; every call leaves the flags it used at zero), records after
+// them, so that no record of an earlier call with another shape is ever read as a flag
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (each GPU has its own copy at its own address).
+int scratch_address(void** out) {
+  int dev = 0;
+  DODO_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DODO_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    DODO_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr) return DODO_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DODO_OK;
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" int dodo_nugget_attention_noalloc(const void* Q, const void* Kn, const void* Vn, const void* Kl,
+                                             const void* Vl, const int32_t* cu_q, const int32_t* cu_nuggets,
+                                             const int32_t* cu_local, int32_t B, int32_t H, int32_t H_kv, int32_t d_h,
+                                             int32_t max_q, int32_t max_k, int32_t max_local, int64_t Kt,
+                                             float softmax_scale, int dtype, int layout, void* O, float* lse,
+                                             void* stream) {
+  using namespace dodo;
+  const size_t need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, dtype);
+  Variant v;
+  void* ws = nullptr;
+  if (need > 0) {
+    // need = slots * (d_h + 3) * 4 bytes (records, then one flag each): the limit is on the slots
+    const size_t slots = need / ((static_cast<size_t>(d_h) + 3) * sizeof(float));
+    if (slots > static_cast<size_t>(kScratchSlots) || d_h > 128) return DODO_ERR_SCRATCH_LIMIT;
+    void* base = nullptr;
+    const int rc = scratch_address(&base);
+    if (rc != DODO_OK) return rc;
+    v.ws_flags = base;
+    ws = static_cast<unsigned char*>(base) + kScratchFlagBytes;
+  }
+  return attention_entry(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, v, B, H, H_kv, d_h, max_q, max_k, max_local, Kt,
+                         softmax_scale, dtype, layout, O, lse, ws, need, stream);
 }
 
 extern "C" int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, const void* Kl,

@@ -20,7 +20,8 @@ struct AttnParams {
   int dtype;
   void* O;
   float* lse;
-  void* ws;
+  void* ws;        // split-K kernel: partial records, followed by one flag word per record ...
+  void* ws_flags;  // ... unless this is set: then the flag words live here
   hipStream_t stream;
 };
 

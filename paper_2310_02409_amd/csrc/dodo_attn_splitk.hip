@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
     const int32_t* __restrict__ cu_ctx,
     int H, int H_kv, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
-    void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws) {
+    void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws, uint32_t* __restrict__ flags) {
   using VT = Vec16<DTYPE>;
   constexpr int kEPL = VT::kElems;          // elements per lane
   constexpr int kLPR = DH / kEPL;           // lanes per K/V row
@@ -225,7 +225,6 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
 
   // ---- several splits: the last one combines, in split order ----
   const int64_t slot0 = ((static_cast<int64_t>(b) * max_q + i) * H + h) * nsplit;
-  uint32_t* flags = reinterpret_cast<uint32_t*>(ws + static_cast<int64_t>(gridDim.x) * partial_floats<DH>());
   __shared__ int all_there;
   if (split + 1 < nsplit) {
     // Records and flags are written and read with device-scope atomic accesses (plain stores and
@@ -311,17 +310,21 @@ int launch_t(const AttnParams& p, int nsplit) {
   const int64_t rows = static_cast<int64_t>(p.B) * p.max_q * p.H;
   // few workgroups (about one per CU) with many rows each: 16 wavefronts per workgroup keep enough
   // loads in flight; otherwise 4 wavefronts and several workgroups per CU
+  // one flag word per record: right behind the records, unless the caller keeps them elsewhere
+  uint32_t* flags = p.ws_flags != nullptr
+                        ? static_cast<uint32_t*>(p.ws_flags)
+                        : reinterpret_cast<uint32_t*>(static_cast<float*>(p.ws) + rows * nsplit * partial_floats<DH>());
   const bool wide = rows * nsplit <= 512 && static_cast<int64_t>(p.max_k) + p.max_local >= 512;
   if (wide) {
     hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
                        dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
                        p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
-                       static_cast<float*>(p.ws));
+                       static_cast<float*>(p.ws), flags);
   } else {
     hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
                        dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
                        p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
-                       static_cast<float*>(p.ws));
+                       static_cast<float*>(p.ws), flags);
   }
   return launch_status();
 }
