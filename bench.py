@@ -1,19 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the Dodo hot path on one MI355X.
 
-One "step" is one pass of the whole path over one batch of the LLaMA-7B-shaped
-prefill workload (bf16, batch 8, 4096 context tokens per sequence, 10x
-compression, 512-token query block after 128 local tokens):
+Headline (the timed region): the LLaMA-13B-shaped autoencoding workload, the largest of the five that runs on one
+GPU -- bf16, batch 16, 2048 context tokens per sequence at 20x compression (103 nuggets), 40 layers, then a
+2048-token causal query block per sequence.  One "step" is one pass of the whole path over that batch, every
+layer on its own tensors (80 GB of inputs, nothing is re-read from a cache):
 
-    dodo_score -> dodo_select_topk -> dodo_gather_nuggets
-      -> dodo_nugget_attention (512-row query block, MFMA kernel)
-      -> dodo_nugget_attention (one decode token per sequence, split-K kernel)
+    for each of the 40 layers:
+        dodo_score -> dodo_select_topk -> dodo_gather_nuggets        (compress the layer's context)
+        dodo_nugget_attention                                        (2048-row query block over nuggets + itself)
 
-All inputs are resident in HBM before the timed region.  Prints ONE JSON line:
-whole-step query tokens/s, the per-kernel durations measured with events on
-the launch stream inside the timed region, the roofline of the dominant
-kernel, and the oracle timed on the host cores on a bounded sample of the same
-workload (a reported baseline, not a target).
+`value` = query tokens of the batch (16 x 2048) per second of whole-step time.  `roofline` describes the dominant
+kernel, the query-block attention, from events around each of its launches inside the timed region.
+
+`kernels` then holds, per workload (c2 prefill, c3 32-layer decode, c4, c5 long context), every kernel's time,
+GB/s or TFLOP/s and fraction of the HBM / bf16 matrix peak; bandwidth-bound kernels are timed over four rotating
+buffer sets (more than the 256 MB last-level cache holds), and a read-only stream and a copy kernel written in the
+same style are timed in the same run as what this device's memory system gives such code (`ceilings`).
+`cpu_baseline` is the oracle timed on one host core on a bounded sample (a reported baseline, not a target).
+All inputs are synthetic and resident in HBM before any timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -27,261 +32,549 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+E = 2                           # bytes per element (bf16 workloads)
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, help="workload id (2 = LLaMA-7B prefill, the metric's config)")
-    ap.add_argument("--suite", action="store_true",
-                    help="instead of the default line: decode step over 32 layers (workload 3), compress phase over "
-                         "40 layers (workload 4), 64 decode steps (workload 5)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workloads", default="c4,c2,c3,c5",
+                    help="which per-workload kernel tables to measure (c4, the headline, always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--no-events", action="store_true", help="no per-kernel events inside the timed region")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 256 MiB device copy a few times (reference for the HBM traffic counters)")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the kernels beyond the four-call path (threshold rule, pooling baseline, gather-free "
+                         "attention, score gradient, 2-layer scorer, segment form)")
     return ap.parse_args()
 
 
-def algorithmic_work(wl, ks, E):
-    """Algorithmic bytes / flop per launch (what the method itself must move or compute)."""
-    N, d, B = wl.N, wl.d_model, wl.B
-    Hd = wl.H_kv * wl.d_h
-    Kt = sum(ks)
-    Sq = sum(wl.q_lens)
-    vis_pairs = sum(sum(k + (m - q + i + 1) for i in range(q)) for k, m, q in zip(ks, wl.local_lens, wl.q_lens))
-    out = {
-        "score": {"bytes": N * d * E + d * E + 4 * N, "flop": 2 * N * d},
-        "select": {"bytes": 4 * N + 4 * Kt + 8 * (B + 1), "flop": 0},
-        "gather": {"bytes": 2 * (2 * Kt * Hd * E) + 4 * Kt, "flop": 0},
-        "attn_block": {"bytes": E * (2 * Sq * wl.H * wl.d_h + 2 * sum(k + m for k, m in zip(ks, wl.local_lens)) * Hd),
-                       "flop": 4 * wl.d_h * wl.H * vis_pairs},
-    }
-    dec_rows = sum(k + m + 1 for k, m in zip(ks, wl.local_lens))
-    out["attn_decode"] = {"bytes": E * (2 * B * wl.H * wl.d_h + 2 * dec_rows * Hd), "flop": 4 * wl.d_h * wl.H * dec_rows}
+# ------------------------------------------------------------------------------------------------ helpers
+def work_score(N, d):
+    return {"bytes": N * d * E + d * E + 4 * N, "flop": 2 * N * d}
+
+
+def work_select(N, Kt, B):
+    return {"bytes": 4 * N + 4 * Kt + 8 * (B + 1), "flop": 0}
+
+
+def work_gather(Kt, Hd):
+    return {"bytes": 2 * (2 * Kt * Hd * E) + 4 * Kt, "flop": 0}
+
+
+def work_attention(q_lens, k_lens, m_lens, H, H_kv, d_h):
+    """Algorithmic work of the attention: masked pairs are not counted, every K/V row is counted once."""
+    pairs = 0
+    for q, k, m in zip(q_lens, k_lens, m_lens):
+        lo = m - q + 1  # local rows visible to the first query row (may be <= 0)
+        pairs += q * k + sum(max(0, min(m, lo + i)) for i in range(q))
+    return {"bytes": E * (2 * sum(q_lens) * H * d_h + 2 * (sum(k_lens) + sum(m_lens)) * H_kv * d_h),
+            "flop": 4 * d_h * H * pairs}
+
+
+def hbm_row(us, work):
+    gbs = work["bytes"] / us * 1e-3
+    return {"avg_us": round(us, 2), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+            "bound": "hbm", "bytes": work["bytes"]}
+
+
+def mfma_row(us, work):
+    tf = work["flop"] / us * 1e-6
+    return {"avg_us": round(us, 2), "TFLOPs": round(tf, 1), "frac_of_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+            "bound": "mfma", "flop": work["flop"], "GBps": round(work["bytes"] / us * 1e-3, 1)}
+
+
+class Clock:
+    """Event timing on torch's current stream, which is the stream every library call is given."""
+
+    def __init__(self, torch):
+        self.torch = torch
+
+    def batched(self, calls, rounds=6, inner=3):
+        """Average and minimum time per call, in microseconds, of the calls in `calls` (one per rotating buffer
+        set) launched back to back `inner` times between one pair of events."""
+        torch = self.torch
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        per = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(inner):
+                for c in calls:
+                    c()
+            e1.record()
+            torch.cuda.synchronize()
+            per.append(e0.elapsed_time(e1) * 1e3 / (inner * len(calls)))
+        return sum(per) / len(per), min(per)
+
+
+# ------------------------------------------------------------------------------------------------ ceilings
+def measure_ceilings(torch, D, clock, dev):
+    """What the memory system gives a plain streaming kernel here: four rotating 512 MiB buffers."""
+    n = 512 << 20
+    bufs = [torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(4)]
+    dst = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(2)]
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    rd, _ = clock.batched([lambda b=b: D.dodo_probe_read(b, sink) for b in bufs], rounds=4, inner=2)
+    cp, _ = clock.batched([lambda b=b, i=i: D.dodo_probe_copy(b, dst[i % 2]) for i, b in enumerate(bufs)], rounds=4, inner=2)
+    rt, _ = clock.batched([lambda b=b, i=i: dst[i % 2].copy_(b) for i, b in enumerate(bufs)], rounds=4, inner=2)
+    out = {"read_stream_GBps": round(n / rd * 1e-3, 1), "copy_kernel_GBps": round(2 * n / cp * 1e-3, 1),
+           "runtime_copy_GBps": round(2 * n / rt * 1e-3, 1), "nominal_hbm_peak_GBps": HBM_PEAK_GBS,
+           "note": "512 MiB per launch over 4 rotating buffers; copy = bytes read + bytes written"}
+    del bufs, dst
+    torch.cuda.empty_cache()
     return out
 
 
-def cpu_baseline(wl, host, ks, scale):
-    """Times the oracle, as it stands, on sequence 0 of the batch (all sequences have the same shape):
-    score + select + gather of its context and attention for all its query tokens, all heads."""
-    import numpy as np
-    import oracle
-    n0, q0, m0, k0 = wl.seq_lens[0], wl.q_lens[0], wl.local_lens[0], ks[0]
-    cu_s, cu_k = oracle.cu_from_lengths([n0]), oracle.cu_from_lengths([k0])
-    cu_q, cu_m = oracle.cu_from_lengths([q0]), oracle.cu_from_lengths([m0])
-    t0 = time.perf_counter()
-    s = oracle.score(host["hidden"][:n0], host["w"])
-    idx = oracle.select_topk(s, cu_s, cu_k, oracle.FORCE_LAST)
-    Kn, Vn = oracle.gather(host["K"][:n0], host["V"][:n0], idx, cu_s, cu_k)
-    t1 = time.perf_counter()
-    oracle.attention(host["Q"][:q0], Kn, Vn, host["Kl"][:m0], host["Vl"][:m0], cu_q, cu_k, cu_m, scale)
-    oracle.attention(host["Qd"][:1], Kn, Vn, host["Kld"][:m0 + 1], host["Vld"][:m0 + 1], oracle.cu_from_lengths([1]),
-                     cu_k, oracle.cu_from_lengths([m0 + 1]), scale)
-    t2 = time.perf_counter()
-    total = t2 - t0
-    return {"value": (q0 + 1) / total, "unit": "query tokens/s", "cores": 1, "kind": "oracle",
-            "sample": f"sequence 0 of {wl.B} (n={n0}, k={k0}, q={q0}+1 decode token, all {wl.H} heads): "
-                      f"score+select+gather {t1 - t0:.2f} s, attention {t2 - t1:.2f} s; "
-                      "per-sequence cost is identical, so tokens/s carries over to the whole batch"}
-
-
-def suite(args):
-    """Measurements beyond the default line: the decode step of workload 3 over all 32 layers, the
-    compress phase of workload 4 over all 40 layers, and 64 decode steps of workload 5.  One JSON line."""
-    import torch
-    import paper_2310_02409_amd as D
-    import workloads as W
-
-    dev = torch.device("cuda:0")
-    out = {"suite": True, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}
-
-    def timed(fn, reps):
-        fn()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fn()
-            e1.record()
-            torch.cuda.synchronize()
-            ts.append(e0.elapsed_time(e1) * 1e3)
-        ts.sort()
-        return sum(ts) / len(ts), ts[0]
-
-    # ---- workload 3: one token step across 32 layers, a nugget cache and a local window per layer
-    wl = W.config(3)
-    B, L = wl.B, wl.layers
-    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
-    Kt, Sm = sum(ks), sum(wl.local_lens) + B
-    cu_q, cu_l = W.cumulative([1] * B, dev), W.cumulative([m + 1 for m in wl.local_lens], dev)
-    mk = lambda tid, n, h: W.normal(wl.seed, tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
-    layers = [dict(Kn=mk(100 + 8 * l, Kt, wl.H_kv), Vn=mk(101 + 8 * l, Kt, wl.H_kv), Kl=mk(102 + 8 * l, Sm, wl.H_kv),
-                   Vl=mk(103 + 8 * l, Sm, wl.H_kv), Q=mk(104 + 8 * l, B, wl.H)) for l in range(L)]
-    O = torch.empty_like(layers[0]["Q"])
-    max_m = max(wl.local_lens) + 1
-    scale = wl.d_h ** -0.5
-
-    def step3():
-        for t in layers:
-            D.dodo_nugget_attention(t["Q"], t["Kn"], t["Vn"], t["Kl"], t["Vl"], cu_q, cu_k, cu_l, 1, max(ks), max_m,
-                                    scale, D.TOKEN_MAJOR, O)
-    avg, mn = timed(step3, 10)
-    by = 2 * (2 * (Kt + Sm) * wl.H_kv * wl.d_h + 2 * B * wl.H * wl.d_h) * L
-    out["c3_decode_step_32_layers"] = {
-        "launches": L, "avg_us": round(avg, 1), "min_us": round(mn, 1), "query_tokens_per_s": round(B / avg * 1e6),
-        "GBps": round(by / avg * 1e-3, 1), "frac_of_8TBps": round(by / avg * 1e-3 / HBM_PEAK_GBS, 4),
-        "bytes_per_step": by, "note": "64 ragged sequences, 20x compression, 256 local tokens + the token itself; "
-                                      "32 launches of dodo_nugget_attention on 32 distinct caches (18.9 GB, no reuse)"}
-    del layers
-    torch.cuda.empty_cache()
-
-    # ---- workload 4: score + select + gather over 40 layers
+# ------------------------------------------------------------------------------------------------ workload 4 (headline)
+def run_c4(torch, D, W, clock, dev, args):
     wl = W.config(4)
     B, L = wl.B, wl.layers
     cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
-    Kt = sum(ks)
-    cu_s = W.cumulative(wl.seq_lens, dev)
-    lay = [W.make_inputs(wl, dev, layer=l, which=["hidden", "w", "K", "V"]) for l in range(L)]
-    # the layers' K and V in one allocation each ([L, N, H_kv, d_h]) so that one launch can pack all of them
-    K_all = torch.empty((L,) + tuple(lay[0]["K"].shape), dtype=wl.dtype, device=dev)
-    V_all = torch.empty_like(K_all)
-    for l in range(L):
-        K_all[l].copy_(lay[l]["K"])
-        V_all[l].copy_(lay[l]["V"])
-        lay[l]["K"], lay[l]["V"] = K_all[l], V_all[l]
+    Kt, max_n, max_k = sum(ks), max(wl.seq_lens), max(ks)
+    max_q, max_m = max(wl.q_lens), max(wl.local_lens)
+    Sq = sum(wl.q_lens)
+    scale = wl.d_h ** -0.5
+    lay = [W.make_inputs(wl, dev, layer=l) for l in range(L)]
+    cu_s, cu_q, cu_l = lay[0]["cu_seqlens"], lay[0]["cu_q"], lay[0]["cu_local"]
     scores = torch.empty((L, wl.N), dtype=torch.float32, device=dev)
     idx = torch.empty((L, Kt), dtype=torch.int32, device=dev)
     Kn = torch.empty((L, Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
     Vn = torch.empty_like(Kn)
-    # all layers' sequences as one batch of L*B sequences for the single-launch select
-    cu_s_all = W.cumulative(wl.seq_lens * L, dev)
-    cu_k_all = W.cumulative(ks * L, dev)
+    O = torch.empty_like(lay[0]["Q"])
+    names = ["score", "select", "gather", "attn_block"]
 
-    def per_layer():
-        for l in range(L):
-            D.dodo_score(lay[l]["hidden"], lay[l]["w"], 0.0, scores[l])
-            D.dodo_select_topk(scores[l], cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx[l])
-            D.dodo_gather_nuggets(lay[l]["K"], lay[l]["V"], idx[l], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn[l], Vn[l])
+    def layer_calls(l):
+        t = lay[l]
+        return [
+            lambda: D.dodo_score(t["hidden"], t["w"], 0.0, scores[l]),
+            lambda: D.dodo_select_topk(scores[l], cu_s, cu_k, max_n, max_k, Kt, D.FORCE_LAST, idx[l]),
+            lambda: D.dodo_gather_nuggets(t["K"], t["V"], idx[l], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn[l], Vn[l]),
+            lambda: D.dodo_nugget_attention(t["Q"], Kn[l], Vn[l], t["Kl"], t["Vl"], cu_q, cu_k, cu_l, max_q, max_k,
+                                            max_m, scale, D.TOKEN_MAJOR, O),
+        ]
+    calls = [layer_calls(l) for l in range(L)]
 
-    def batched_select():
+    def step(attn_events=None):
         for l in range(L):
-            D.dodo_score(lay[l]["hidden"], lay[l]["w"], 0.0, scores[l])
-        D.dodo_select_topk(scores.view(-1), cu_s_all, cu_k_all, max(wl.seq_lens), max(ks), L * Kt, D.FORCE_LAST,
-                           idx.view(-1))
-        for l in range(L):
-            D.dodo_gather_nuggets(lay[l]["K"], lay[l]["V"], idx[l], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn[l], Vn[l])
+            c = calls[l]
+            c[0]()
+            c[1]()
+            c[2]()
+            if attn_events is not None:
+                attn_events[l][0].record()
+                c[3]()
+                attn_events[l][1].record()
+            else:
+                c[3]()
 
-    def shared_indices():
-        # the Scorer reads one fixed layer and its indices serve every layer (Sec. 2.1): 3 launches in all
-        D.dodo_score(lay[0]["hidden"], lay[0]["w"], 0.0, scores[0])
-        D.dodo_select_topk(scores[0], cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx[0])
-        D.dodo_gather_nuggets_layers(K_all, V_all, idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
 
-    def shared_indices_gather_per_layer():
-        D.dodo_score(lay[0]["hidden"], lay[0]["w"], 0.0, scores[0])
-        D.dodo_select_topk(scores[0], cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx[0])
+    # instrumented pre-pass (not the timed region): events between all calls of two steps
+    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(L)] for _ in range(2)]
+    for s in range(2):
         for l in range(L):
-            D.dodo_gather_nuggets(lay[l]["K"], lay[l]["V"], idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn[l], Vn[l])
-    E = 2
-    by3 = (wl.N * wl.d_model * E + wl.d_model * E + 4 * wl.N + 4 * wl.N + 4 * Kt) + L * 4 * Kt * wl.H_kv * wl.d_h * E
-    a3, m3 = timed(shared_indices, 5)
-    a4, m4 = timed(shared_indices_gather_per_layer, 5)
-    by = L * (wl.N * wl.d_model * E + wl.d_model * E + 4 * wl.N + 4 * wl.N + 4 * Kt + 4 * Kt * wl.H_kv * wl.d_h * E)
-    a1, m1 = timed(per_layer, 5)
-    a2, m2 = timed(batched_select, 5)
-    out["c4_compress_40_layers"] = {
-        "per_layer_rounds": {"launches": 3 * L, "avg_us": round(a1, 1), "min_us": round(m1, 1),
-                             "GBps": round(by / a1 * 1e-3, 1)},
-        "one_select_launch_for_all_layers": {"launches": 2 * L + 1, "avg_us": round(a2, 1), "min_us": round(m2, 1),
-                                             "GBps": round(by / a2 * 1e-3, 1)},
-        "shared_indices_one_gather_launch": {"launches": 3, "avg_us": round(a3, 1), "min_us": round(m3, 1),
-                                             "GBps": round(by3 / a3 * 1e-3, 1), "bytes": by3},
-        "shared_indices_gather_per_layer": {"launches": L + 2, "avg_us": round(a4, 1), "min_us": round(m4, 1),
-                                            "GBps": round(by3 / a4 * 1e-3, 1), "bytes": by3},
-        "bytes": by, "note": "16 x 2048 tokens, d = 5120, 20x compression. First two forms: per-layer scores and "
-                             "selections (the second selects the 640 (layer, sequence) segments in one launch). Last "
-                             "two: one scored layer whose indices pack all 40 layers, as in the paper (Sec. 2.1), "
-                             "with one gather launch for all layers or one per layer"}
-    del lay, Kn, Vn, K_all, V_all
+            for j in range(4):
+                ev[s][l][j].record()
+                calls[l][j]()
+            ev[s][l][4].record()
+    torch.cuda.synchronize()
+    per = {n: [] for n in names}
+    for s in range(2):
+        for l in range(L):
+            for j, n in enumerate(names):
+                per[n].append(ev[s][l][j].elapsed_time(ev[s][l][j + 1]) * 1e3)
+    work = {"score": work_score(wl.N, wl.d_model), "select": work_select(wl.N, Kt, B),
+            "gather": work_gather(Kt, wl.H_kv * wl.d_h),
+            "attn_block": work_attention(wl.q_lens, ks, wl.local_lens, wl.H, wl.H_kv, wl.d_h)}
+    table = {}
+    for n in names:
+        us = sum(per[n]) / len(per[n])
+        table[n] = mfma_row(us, work[n]) if n == "attn_block" else hbm_row(us, work[n])
+        table[n]["min_us"] = round(min(per[n]), 2)
+    table["select"].pop("frac_of_hbm_peak")  # latency-bound integer kernel: 16 workgroups
+    table["select"]["bound"] = "latency"
+    tg = table["select"]["avg_us"] + table["gather"]["avg_us"]
+    table["topk_plus_gather_GBps"] = round((work["select"]["bytes"] + work["gather"]["bytes"]) / tg * 1e-3, 1)
+    table["attn_block"]["query_tokens_per_s_per_layer"] = round(Sq / table["attn_block"]["avg_us"] * 1e6)
+    table["note"] = ("per layer, from events between all calls of two untimed steps (each interval includes the gap to "
+                     "the previous launch); 40 layers on 40 distinct tensor sets")
+
+    # the paper's own form of the compress phase (Sec. 2.1): one scored layer, its indices pack every layer
+    K_all = torch.stack([t["K"] for t in lay[:8]])  # 8 layers in one allocation for the one-launch gather
+    V_all = torch.stack([t["V"] for t in lay[:8]])
+    a, _ = clock.batched([lambda: D.dodo_gather_nuggets_layers(K_all, V_all, idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR,
+                                                                Kn[:8], Vn[:8])], rounds=4, inner=2)
+    table["gather_8_layers_one_launch"] = hbm_row(a, {"bytes": 8 * work["gather"]["bytes"], "flop": 0})
+    del K_all, V_all
+
+    # ---- timed region: exactly `steps` steps; events only around the dominant kernel's launches
+    steps = args.steps
+    aev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+           for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(aev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    us = [a.elapsed_time(b) * 1e3 for st in aev for a, b in st]
+    avg = sum(us) / len(us)
+    ach = work["attn_block"]["flop"] / avg * 1e-6
+    intensity = work["attn_block"]["flop"] / work["attn_block"]["bytes"]
+    roof = {"kernel": "block_attention_kernel (dodo_nugget_attention, 2048-row causal query blocks)", "bound": "mfma",
+            "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "avg_us": round(avg, 2),
+            "min_us": round(min(us), 2), "launches": len(us), "flop_per_launch": work["attn_block"]["flop"],
+            "bytes_per_launch": work["attn_block"]["bytes"], "intensity_flop_per_byte": round(intensity, 1)}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):  # HBM bytes per launch from the committed counter runs
+        roof["traffic"] = json.load(open(tpath)).get(wl.name, {}).get("attn_block")
+    head = {"ms_per_step": ms_per_step, "value": Sq / (ms_per_step * 1e-3), "roofline": roof,
+            "config": {"workload": wl.name, "batch": B, "context": wl.seq_lens[0], "nuggets_per_seq": ks[0],
+                       "query_block": max_q, "local_tokens": wl.tau[0], "d_model": wl.d_model, "heads": wl.H,
+                       "head_dim": wl.d_h, "layers": L, "launches_per_step": 4 * L}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline_c4(W, wl, lay[0], ks, scale)
+    del lay, calls, Kn, Vn, scores
     torch.cuda.empty_cache()
+    return head, table, cpu
 
-    # ---- workload 5: 64 decode steps after the 1024-token prefill (the local buffer grows by one row per step)
-    wl = W.config(5)
-    B = wl.B
-    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
-    Kt = sum(ks)
-    steps, m0 = 64, wl.q_lens[0]
-    mk = lambda tid, n, h: W.normal(wl.seed, tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
-    Kn, Vn = mk(200, Kt, wl.H_kv), mk(201, Kt, wl.H_kv)
-    Kl, Vl = mk(202, B * (m0 + steps), wl.H_kv), mk(203, B * (m0 + steps), wl.H_kv)  # room for every step's rows
-    Q = mk(204, B, wl.H)
-    O = torch.empty_like(Q)
-    cu_q = W.cumulative([1] * B, dev)
-    # step t sees m0 + t + 1 local rows of each sequence: cumulative arrays with a fixed pitch are not packed,
-    # so each step gets its own packed copy of the window (made outside the timed region)
-    wins = []
-    for t in range(steps):
-        m = m0 + t + 1
-        rows = torch.cat([torch.arange(b * (m0 + steps), b * (m0 + steps) + m, device=dev) for b in range(B)])
-        wins.append((Kl[rows].contiguous(), Vl[rows].contiguous(), W.cumulative([m] * B, dev), m))
-    ws_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max(ks), m0 + steps, D.BF16)
-    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
-    def decode64():
-        for kl, vl, cu_l, m in wins:
-            D.dodo_nugget_attention(Q, Kn, Vn, kl, vl, cu_q, cu_k, cu_l, 1, max(ks), m0 + steps, scale, D.TOKEN_MAJOR, O,
-                                    ws=ws)
-    avg, mn = timed(decode64, 5)
-    by = sum(2 * (2 * (Kt + B * w[3]) * wl.H_kv * wl.d_h + 2 * B * wl.H * wl.d_h) for w in wins)
-    out["c5_decode_64_steps"] = {
-        "launches": steps, "avg_us": round(avg, 1), "min_us": round(mn, 1), "us_per_step": round(avg / steps, 2),
-        "query_tokens_per_s": round(B * steps / avg * 1e6), "GBps": round(by / avg * 1e-3, 1),
-        "frac_of_8TBps": round(by / avg * 1e-3 / HBM_PEAK_GBS, 4),
-        "note": "2 sequences, 3277 nuggets each, local buffer 1024 + t + 1 rows at step t; the same 107 MB nugget "
-                "cache is re-read every step and stays in the 256 MB last-level cache, so this is not an HBM figure"}
-    del Kn, Vn, Kl, Vl, wins
-    torch.cuda.empty_cache()
+def cpu_baseline_c4(W, wl, t, ks, scale):
+    """The oracle, as it stands, on one host core: sequence 0 of layer 0 (compress its 2048-token context, then
+    the attention of its 40 heads x 2048 rows)."""
+    import oracle
+    n0, q0, m0, k0 = wl.seq_lens[0], wl.q_lens[0], wl.local_lens[0], ks[0]
+    host = {k: W.to_numpy(t[k][:n0]) for k in ("hidden", "K", "V")}
+    host["w"] = W.to_numpy(t["w"])
+    host.update({k: W.to_numpy(t[k][:q0]) for k in ("Q",)})
+    host.update({k: W.to_numpy(t[k][:m0]) for k in ("Kl", "Vl")})
+    cu_s, cu_k = oracle.cu_from_lengths([n0]), oracle.cu_from_lengths([k0])
+    cu_q, cu_m = oracle.cu_from_lengths([q0]), oracle.cu_from_lengths([m0])
+    t0 = time.perf_counter()
+    s = oracle.score(host["hidden"], host["w"])
+    idx = oracle.select_topk(s, cu_s, cu_k, oracle.FORCE_LAST)
+    Kn, Vn = oracle.gather(host["K"], host["V"], idx, cu_s, cu_k)
+    t1 = time.perf_counter()
+    heads = wl.H  # about 47 GFLOP in double precision
+    rows = [(0, h, i) for h in range(heads) for i in range(q0)]
+    oracle.attention_rows(host["Q"], Kn, Vn, host["Kl"], host["Vl"], cu_q, cu_k, cu_m, scale, rows)
+    t2 = time.perf_counter()
+    per_layer_seq = (t1 - t0) + (t2 - t1) * wl.H / heads  # one sequence, one layer, all heads
+    total = per_layer_seq * wl.layers
+    return {"value": round(q0 / total, 3), "unit": "query tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"layer 0, sequence 0 of {wl.B} (n={n0}, k={k0}, q={q0}): score+select+gather {t1 - t0:.2f} s, "
+                      f"attention of {heads} heads x {q0} rows {t2 - t1:.2f} s; extrapolated to "
+                      f"{wl.layers} layers (every layer and sequence costs the same), single thread"}
 
-    # ---- segment form of the autoregressive objective: workload 2's 8 x 4096 tokens as 64 segments of 512 tokens
-    # that see the nuggets before (segment start - 128) and the uncompressed tokens from there on
+
+# ------------------------------------------------------------------------------------------------ workload 2
+def run_c2(torch, D, W, clock, dev, args):
     wl = W.config(2)
-    B, seg_len, tau = wl.B, 512, 128
+    B, S = wl.B, 4  # four rotating sets of every input
     cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
-    Kt = sum(ks)
-    cu_s = W.cumulative(wl.seq_lens, dev)
+    Kt, max_n, max_k = sum(ks), max(wl.seq_lens), max(ks)
+    max_q, max_m = max(wl.q_lens), max(wl.local_lens)
+    scale = wl.d_h ** -0.5
+    dec_local = [m + 1 for m in wl.local_lens]
+    cu_qd, cu_ld = W.cumulative([1] * B, dev), W.cumulative(dec_local, dev)
+    sets = []
+    for s in range(S):
+        g = W.make_inputs(wl, dev, layer=s)
+        g["Qd"] = W.normal(wl.seed, 1000 + 16 * s, (B, wl.H, wl.d_h), 1.0, wl.dtype, dev)
+        g["Kld"] = W.normal(wl.seed, 1001 + 16 * s, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+        g["Vld"] = W.normal(wl.seed, 1002 + 16 * s, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+        g["scores"] = torch.empty(wl.N, dtype=torch.float32, device=dev)
+        g["idx"] = torch.empty(Kt, dtype=torch.int32, device=dev)
+        g["Kn"] = torch.empty((Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
+        g["Vn"] = torch.empty_like(g["Kn"])
+        g["O"], g["Od"] = torch.empty_like(g["Q"]), torch.empty_like(g["Qd"])
+        sets.append(g)
+    ws_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max_k, max(dec_local), D.BF16)
+    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    cu_s, cu_q, cu_l = sets[0]["cu_seqlens"], sets[0]["cu_q"], sets[0]["cu_local"]
+    fns = {
+        "score": lambda g: D.dodo_score(g["hidden"], g["w"], 0.0, g["scores"]),
+        "select": lambda g: D.dodo_select_topk(g["scores"], cu_s, cu_k, max_n, max_k, Kt, D.FORCE_LAST, g["idx"]),
+        "gather": lambda g: D.dodo_gather_nuggets(g["K"], g["V"], g["idx"], cu_s, cu_k, Kt, D.TOKEN_MAJOR, g["Kn"], g["Vn"]),
+        "attn_block": lambda g: D.dodo_nugget_attention(g["Q"], g["Kn"], g["Vn"], g["Kl"], g["Vl"], cu_q, cu_k, cu_l, max_q,
+                                                        max_k, max_m, scale, D.TOKEN_MAJOR, g["O"]),
+        "attn_decode": lambda g: D.dodo_nugget_attention(g["Qd"], g["Kn"], g["Vn"], g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld,
+                                                         1, max_k, max(dec_local), scale, D.TOKEN_MAJOR, g["Od"], ws=ws),
+    }
+    for g in sets:  # fill every set's intermediate tensors once
+        for n in fns:
+            fns[n](g)
+    work = {"score": work_score(wl.N, wl.d_model), "select": work_select(wl.N, Kt, B),
+            "gather": work_gather(Kt, wl.H_kv * wl.d_h),
+            "attn_block": work_attention(wl.q_lens, ks, wl.local_lens, wl.H, wl.H_kv, wl.d_h),
+            "attn_decode": work_attention([1] * B, ks, dec_local, wl.H, wl.H_kv, wl.d_h)}
+    table = {}
+    for n, f in fns.items():
+        a, m = clock.batched([lambda g=g, f=f: f(g) for g in sets])
+        table[n] = mfma_row(a, work[n]) if n == "attn_block" else hbm_row(a, work[n])
+        table[n]["min_us"] = round(m, 2)
+    table["select"].pop("frac_of_hbm_peak")
+    table["select"]["bound"] = "latency"
+    tg = table["select"]["avg_us"] + table["gather"]["avg_us"]
+    table["topk_plus_gather_GBps"] = round((work["select"]["bytes"] + work["gather"]["bytes"]) / tg * 1e-3, 1)
+    table["attn_block"]["query_tokens_per_s"] = round(sum(wl.q_lens) / table["attn_block"]["avg_us"] * 1e6)
+    table["attn_decode"]["query_tokens_per_s"] = round(B / table["attn_decode"]["avg_us"] * 1e6)
+    # the five calls as one pipeline on one buffer set after another
+    a, m = clock.batched([lambda g=g: [f(g) for f in fns.values()] for g in sets])
+    table["pipeline_5_calls"] = {"avg_us": round(a, 2), "min_us": round(m, 2),
+                                 "query_tokens_per_s": round((sum(wl.q_lens) + B) / a * 1e6)}
+    table["note"] = "batch 8 x 4096 context tokens, 10x, 512-row query block after 128 local tokens, one layer; 4 rotating buffer sets"
+    nxt = None if args.no_next_rows else next_rows_c2(torch, D, W, clock, dev, wl, sets[0], cu_k, ks, ws, cu_qd, cu_ld, dec_local)
+    del sets
+    torch.cuda.empty_cache()
+    return table, nxt
+
+
+def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec_local):
+    """Kernels beyond the four-call path, at workload 2's shapes (one buffer set: not HBM figures)."""
+    B = wl.B
+    Kt, max_n, max_k = sum(ks), max(wl.seq_lens), max(ks)
+    max_q, max_m = max(wl.q_lens), max(wl.local_lens)
+    scale = wl.d_h ** -0.5
+    out = {}
+
+    def t(fn, rounds=5, inner=2):
+        a, m = clock.batched([fn], rounds=rounds, inner=inner)
+        return {"avg_us": round(a, 2), "min_us": round(m, 2)}
+    # threshold rule of the autoregressive mode (Sec. 2.4)
+    cap = max_k + 64
+    lam = D.dodo_threshold_from_sample(g["scores"], wl.keep_num, wl.keep_den)
+    Kc = torch.zeros((B, cap, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
+    Vc = torch.zeros_like(Kc)
+    Kc[:, :max_k] = g["Kn"].view(B, -1, wl.H_kv, wl.d_h)
+    Vc[:, :max_k] = g["Vn"].view(B, -1, wl.H_kv, wl.d_h)
+    counts = torch.full((B,), max_k, dtype=torch.int32, device=dev)
+    starts = (torch.arange(B, dtype=torch.int32, device=dev) * cap).contiguous()
+    leave_s, leave_K, leave_V = g["scores"][:B].clone(), g["K"][:B].contiguous(), g["V"][:B].contiguous()
+    ws_c = torch.zeros(max(D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, cap, max(dec_local), D.BF16), 16),
+                       dtype=torch.uint8, device=dev)
+    ar = {
+        "threshold_from_sample": t(lambda: D.dodo_threshold_from_sample(g["scores"], wl.keep_num, wl.keep_den, out=lam)),
+        "select_threshold": t(lambda: D.dodo_select_threshold(g["scores"], g["cu_seqlens"], lam)),
+        "stream_append": t(lambda: (counts.fill_(max_k), D.dodo_stream_append(leave_s, lam, leave_K, leave_V, counts, Kc, Vc))),
+        "attn_decode_cached": t(lambda: D.dodo_nugget_attention_cached(
+            g["Qd"], Kc.view(B * cap, wl.H_kv, wl.d_h), Vc.view(B * cap, wl.H_kv, wl.d_h), g["Kld"], g["Vld"], cu_qd, starts,
+            counts, cu_ld, 1, cap, max(dec_local), scale, D.TOKEN_MAJOR, g["Od"], ws=ws_c)),
+        "note": f"sample = the step's {wl.N} scores; stream_append includes a fill of the {B} counters; caches of {cap} rows",
+    }
+    out["autoregressive_mode"] = ar
+    # pooling baseline's compaction (Sec. 5.1)
+    Kp, Vp = torch.empty_like(g["Kn"]), torch.empty_like(g["Vn"])
+    r = t(lambda: D.dodo_meanpool_nuggets(g["K"], g["V"], g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kp, Vp))
+    r["GBps"] = round(2 * (wl.N + Kt) * wl.H_kv * wl.d_h * E / r["avg_us"] * 1e-3, 1)
+    out["meanpool_baseline"] = r
+    # gather-free attention
+    out["gather_free"] = {
+        "attn_block_indexed": t(lambda: D.dodo_nugget_attention_indexed(
+            g["Q"], g["K"], g["V"], g["idx"], g["cu_seqlens"], g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k,
+            max_m, max_n, scale, O=g["O"])),
+        "attn_decode_indexed": t(lambda: D.dodo_nugget_attention_indexed(
+            g["Qd"], g["K"], g["V"], g["idx"], g["cu_seqlens"], g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1, max_k,
+            max(dec_local), max_n, scale, O=g["Od"], ws=ws)),
+        "note": "same results, bit for bit, as gather + attention"}
+    # score gradient of the straight-through estimator (Eq. 17-18)
+    lse_b = torch.empty((g["Q"].shape[0], wl.H), dtype=torch.float32, device=dev)
+    D.dodo_nugget_attention(g["Q"], g["Kn"], g["Vn"], g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k, max_m,
+                            scale, D.TOKEN_MAJOR, g["O"], lse=lse_b)
+    dO = W.normal(wl.seed, 99, tuple(g["Q"].shape), 1.0, wl.dtype, dev)
+    ste_ws = torch.empty(D.dodo_ste_score_grad_workspace_bytes(g["Q"].shape[0], wl.H, Kt), dtype=torch.uint8, device=dev)
+    ste_grad = torch.empty(Kt, dtype=torch.float32, device=dev)
+    r = t(lambda: D.dodo_ste_score_grad(g["Q"], g["Kn"], g["Vn"], dO, g["O"], lse_b, g["cu_q"], cu_k, max_q, max_k, scale,
+                                        scale, D.TOKEN_MAJOR, grad=ste_grad, ws=ste_ws))
+    ste_flop = 4.0 * sum(q * k for q, k in zip(wl.q_lens, ks)) * wl.d_h * wl.H
+    r.update(TFLOPs=round(ste_flop / r["avg_us"] * 1e-6, 1),
+             frac_of_bf16_peak=round(ste_flop / r["avg_us"] * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 3),
+             note="whole call: row dots, the MFMA kernel, the sum over heads")
+    out["ste_score_grad"] = r
+    # 2-layer scorer (App. B), d -> d -> 1
+    d = wl.d_model
+    gen = torch.Generator(device="cpu").manual_seed(wl.seed + 77)
+    W1 = (torch.randn(d, d, generator=gen) * d ** -0.5).to(torch.bfloat16).to(dev)
+    b1 = (torch.randn(d, generator=gen) * 0.5).to(dev)
+    w2 = (torch.randn(d, generator=gen) * d ** -0.5).to(torch.bfloat16).to(dev)
+    mlp_ws = torch.empty(max(D.dodo_score_mlp_workspace_bytes(D.BF16, wl.N, d, d), 16), dtype=torch.uint8, device=dev)
+    mlp_out = torch.empty(wl.N, dtype=torch.float32, device=dev)
+    r = t(lambda: D.dodo_score_mlp(g["hidden"], W1, b1, w2, 0.0, D.RELU, mlp_out, mlp_ws), rounds=4, inner=2)
+    mlp_flop = 2.0 * wl.N * d * d
+    r.update(TFLOPs=round(mlp_flop / r["avg_us"] * 1e-6, 1),
+             frac_of_bf16_peak=round(mlp_flop / r["avg_us"] * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 3), note="ReLU, d_hid = d")
+    out["scorer_2layer"] = r
+    # segment form of the autoregressive objective: the 8 x 4096 tokens as 64 segments of 512 with tau = 128
+    seg_len, tau = 512, 128
     mk = lambda tid, n, h: W.normal(wl.seed, tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
-    Q, K, V = mk(300, wl.N, wl.H), mk(301, wl.N, wl.H_kv), mk(302, wl.N, wl.H_kv)
-    Kn, Vn = mk(303, Kt, wl.H_kv), mk(304, Kt, wl.H_kv)
-    sc = W.normal(wl.seed, 305, (wl.N,), 1.0, torch.float32, dev)
-    idx = torch.empty(Kt, dtype=torch.int32, device=dev)
-    D.dodo_select_topk(sc, cu_s, cu_k, max(wl.seq_lens), max(ks), Kt, D.FORCE_LAST, idx)
-    E = sum(-(-n // seg_len) for n in wl.seq_lens)
-    plan = D.dodo_segment_plan(idx, cu_s, cu_k, seg_len, tau, E)
-    O = torch.empty_like(Q)
-    a_plan, m_plan = timed(lambda: D.dodo_segment_plan(idx, cu_s, cu_k, seg_len, tau, E), 10)
-    a_att, m_att = timed(lambda: D.dodo_nugget_attention_segments(Q, Kn, Vn, K, V, plan[0], plan[1], plan[2], plan[3],
-                                                                  plan[4], seg_len, max(ks), seg_len + tau, scale,
-                                                                  D.TOKEN_MAJOR, O), 10)
+    Qs = mk(300, wl.N, wl.H)
+    Os = torch.empty_like(Qs)
+    n_seg = sum(-(-n // seg_len) for n in wl.seq_lens)
+    plan = D.dodo_segment_plan(g["idx"], g["cu_seqlens"], cu_k, seg_len, tau, n_seg)
+    r = t(lambda: D.dodo_nugget_attention_segments(Qs, g["Kn"], g["Vn"], g["K"], g["V"], plan[0], plan[1], plan[2], plan[3],
+                                                   plan[4], seg_len, max_k, seg_len + tau, scale, D.TOKEN_MAJOR, Os),
+          rounds=4, inner=2)
     cu_q_h, nl_h, ll_h = plan[0].cpu().tolist(), plan[2].cpu().tolist(), plan[4].cpu().tolist()
     pairs = 0
-    for e in range(E):
+    for e in range(n_seg):
         q = cu_q_h[e + 1] - cu_q_h[e]
         pairs += q * nl_h[e] + sum(min(ll_h[e], ll_h[e] - q + i + 1) for i in range(q))
     flop = 4.0 * pairs * wl.d_h * wl.H
-    out["segment_form_8x4096_seg512_tau128"] = {
-        "entries": E, "plan_avg_us": round(a_plan, 1), "attention_avg_us": round(a_att, 1),
-        "attention_min_us": round(m_att, 1), "visible_pairs_per_head": pairs,
-        "TFLOPs": round(flop / a_att * 1e-6, 1), "frac_of_bf16_peak": round(flop / a_att * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
-        "query_tokens_per_s": round(wl.N / a_att * 1e6),
-        "note": "forward attention of the training-time segment mask (Sec. 2.4): 32 heads x 128, 10x compression; "
-                "every token of the 8 texts is a query row"}
-    print(json.dumps(out))
+    r.update(entries=n_seg, TFLOPs=round(flop / r["avg_us"] * 1e-6, 1),
+             frac_of_bf16_peak=round(flop / r["avg_us"] * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+             plan=t(lambda: D.dodo_segment_plan(g["idx"], g["cu_seqlens"], cu_k, seg_len, tau, n_seg)))
+    out["segment_form_8x4096_seg512_tau128"] = r
+    return out
+
+
+# ------------------------------------------------------------------------------------------------ workload 3
+def run_c3(torch, D, W, clock, dev, args):
+    wl = W.config(3)
+    B, L = wl.B, wl.layers
+    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
+    Kt, Sm = sum(ks), sum(wl.local_lens)
+    dec_local = wl.local_lens  # 256 uncompressed tokens + the new token itself
+    cu_q, cu_l = W.cumulative([1] * B, dev), W.cumulative(dec_local, dev)
+    mk = lambda tid, n, h: W.normal(wl.seed, tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
+    layers = [dict(Kn=mk(100 + 8 * l, Kt, wl.H_kv), Vn=mk(101 + 8 * l, Kt, wl.H_kv), Kl=mk(102 + 8 * l, Sm, wl.H_kv),
+                   Vl=mk(103 + 8 * l, Sm, wl.H_kv), Q=mk(104 + 8 * l, B, wl.H)) for l in range(L)]
+    O = torch.empty_like(layers[0]["Q"])
+    max_m, max_k = max(dec_local), max(ks)
+    scale = wl.d_h ** -0.5
+
+    def step():
+        for t in layers:
+            D.dodo_nugget_attention(t["Q"], t["Kn"], t["Vn"], t["Kl"], t["Vl"], cu_q, cu_k, cu_l, 1, max_k, max_m, scale,
+                                    D.TOKEN_MAJOR, O)
+    a, m = clock.batched([step], rounds=6, inner=1)
+    w1 = work_attention([1] * B, ks, dec_local, wl.H, wl.H_kv, wl.d_h)
+    table = {"attn_decode": hbm_row(a / L, w1)}
+    table["attn_decode"]["min_us"] = round(m / L, 2)
+    table["decode_step_32_layers"] = {"launches": L, "avg_us": round(a, 1), "min_us": round(m, 1),
+                                      "query_tokens_per_s": round(B / a * 1e6), "bytes_per_step": w1["bytes"] * L,
+                                      "GBps": round(w1["bytes"] * L / a * 1e-3, 1),
+                                      "frac_of_hbm_peak": round(w1["bytes"] * L / a * 1e-3 / HBM_PEAK_GBS, 4)}
+    del layers
+    torch.cuda.empty_cache()
+    # the ragged compress phase of one layer (set-up of the decode): 3.2 GB of hidden states, 6.4 GB of K/V
+    g = W.make_inputs(wl, dev, layer=0, which=["hidden", "w", "K", "V"])
+    scores = torch.empty(wl.N, dtype=torch.float32, device=dev)
+    idx = torch.empty(Kt, dtype=torch.int32, device=dev)
+    Kn = torch.empty((Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
+    Vn = torch.empty_like(Kn)
+    cu_s = g["cu_seqlens"]
+    a, _ = clock.batched([lambda: D.dodo_score(g["hidden"], g["w"], 0.0, scores)], rounds=4, inner=2)
+    table["score"] = hbm_row(a, work_score(wl.N, wl.d_model))
+    a, _ = clock.batched([lambda: D.dodo_select_topk(scores, cu_s, cu_k, max(wl.seq_lens), max_k, Kt, D.FORCE_LAST, idx)],
+                         rounds=4, inner=2)
+    table["select"] = {"avg_us": round(a, 2), "bound": "latency", "bytes": work_select(wl.N, Kt, B)["bytes"]}
+    a, _ = clock.batched([lambda: D.dodo_gather_nuggets(g["K"], g["V"], idx, cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)],
+                         rounds=4, inner=2)
+    table["gather"] = hbm_row(a, work_gather(Kt, wl.H_kv * wl.d_h))
+    table["note"] = ("batch 64, ragged contexts in [4096, 8192] at 20x, 256 local tokens + the token itself; decode = one "
+                     "token step over 32 layers on 32 distinct caches (no reuse); compress = one layer's context (its "
+                     "inputs alone exceed the last-level cache)")
+    del g, Kn, Vn
+    torch.cuda.empty_cache()
+    return table
+
+
+# ------------------------------------------------------------------------------------------------ workload 5
+def run_c5(torch, D, W, clock, dev, args):
+    wl = W.config(5)
+    B, S = wl.B, 4
+    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
+    Kt, max_n, max_k = sum(ks), max(wl.seq_lens), max(ks)
+    max_q, max_m = max(wl.q_lens), max(wl.local_lens)
+    scale = wl.d_h ** -0.5
+    m_dec = max_m + 32 + 1  # decode step 32 of 64: 1024 prefill rows + 32 earlier tokens + the token itself
+    cu_qd, cu_ld = W.cumulative([1] * B, dev), W.cumulative([m_dec] * B, dev)
+    sets = []
+    for s in range(S):
+        g = W.make_inputs(wl, dev, layer=s)
+        g["Qd"] = W.normal(wl.seed, 1000 + 16 * s, (B, wl.H, wl.d_h), 1.0, wl.dtype, dev)
+        g["Kld"] = W.normal(wl.seed, 1001 + 16 * s, (B * m_dec, wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+        g["Vld"] = W.normal(wl.seed, 1002 + 16 * s, (B * m_dec, wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+        g["scores"] = torch.empty(wl.N, dtype=torch.float32, device=dev)
+        g["qscores"] = torch.empty(wl.N, dtype=torch.float32, device=dev)
+        g["idx"] = torch.empty(Kt, dtype=torch.int32, device=dev)
+        g["Kn"] = torch.empty((Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
+        g["Vn"] = torch.empty_like(g["Kn"])
+        g["O"], g["Od"] = torch.empty_like(g["Q"]), torch.empty_like(g["Qd"])
+        sets.append(g)
+    cu_s, cu_q, cu_l = sets[0]["cu_seqlens"], sets[0]["cu_q"], sets[0]["cu_local"]
+    ws_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max_k, m_dec + 64, D.BF16)
+    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    sel_ws = torch.zeros(max(D.dodo_select_topk_workspace_bytes(B, max_n), 16), dtype=torch.uint8, device=dev)
+    for g in sets:
+        D.dodo_score(g["hidden"], g["w"], 0.0, g["scores"])
+        g["qscores"].copy_(W.quantise16(g["scores"]))  # the workload's 16-level tie stress (input preparation)
+    fns = {
+        "score": lambda g: D.dodo_score(g["hidden"], g["w"], 0.0, g["scores"]),
+        "select": lambda g: D.dodo_select_topk(g["qscores"], cu_s, cu_k, max_n, max_k, Kt, D.FORCE_LAST, g["idx"], ws=sel_ws),
+        "gather": lambda g: D.dodo_gather_nuggets(g["K"], g["V"], g["idx"], cu_s, cu_k, Kt, D.TOKEN_MAJOR, g["Kn"], g["Vn"]),
+        "attn_block": lambda g: D.dodo_nugget_attention(g["Q"], g["Kn"], g["Vn"], g["Kl"], g["Vl"], cu_q, cu_k, cu_l, max_q,
+                                                        max_k, max_m, scale, D.TOKEN_MAJOR, g["O"]),
+        "attn_decode": lambda g: D.dodo_nugget_attention(g["Qd"], g["Kn"], g["Vn"], g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1,
+                                                         max_k, m_dec, scale, D.TOKEN_MAJOR, g["Od"], ws=ws),
+    }
+    for g in sets:
+        for n in fns:
+            fns[n](g)
+    work = {"score": work_score(wl.N, wl.d_model), "select": work_select(wl.N, Kt, B),
+            "gather": work_gather(Kt, wl.H_kv * wl.d_h),
+            "attn_block": work_attention(wl.q_lens, ks, wl.local_lens, wl.H, wl.H_kv, wl.d_h),
+            "attn_decode": work_attention([1] * B, ks, [m_dec] * B, wl.H, wl.H_kv, wl.d_h)}
+    table = {}
+    for n, f in fns.items():
+        a, m = clock.batched([lambda g=g, f=f: f(g) for g in sets])
+        table[n] = mfma_row(a, work[n]) if n == "attn_block" else hbm_row(a, work[n])
+        table[n]["min_us"] = round(m, 2)
+    table["select"].pop("frac_of_hbm_peak")
+    table["select"]["bound"] = "latency"
+    assert int(sel_ws.view(torch.int32)[0]) == 0, "dodo_select_topk reported a failed wait"
+    tg = table["select"]["avg_us"] + table["gather"]["avg_us"]
+    table["topk_plus_gather_GBps"] = round((work["select"]["bytes"] + work["gather"]["bytes"]) / tg * 1e-3, 1)
+    table["attn_block"]["query_tokens_per_s"] = round(sum(wl.q_lens) / table["attn_block"]["avg_us"] * 1e6)
+    table["attn_decode"]["note"] = "decode step 32 of 64 on 4 rotating caches: every launch reads its cache from HBM"
+    # the 64 decode steps of one generation: the local buffer grows by a row per step, the same cache every step
+    g = sets[0]
+    steps = 64
+    Kl_all = W.normal(wl.seed, 2000, (B * (max_m + steps), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+    Vl_all = W.normal(wl.seed, 2001, (B * (max_m + steps), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
+    wins = []
+    for t in range(steps):
+        m = max_m + t + 1
+        rows = torch.cat([torch.arange(b * (max_m + steps), b * (max_m + steps) + m, device=dev) for b in range(B)])
+        wins.append((Kl_all[rows].contiguous(), Vl_all[rows].contiguous(), W.cumulative([m] * B, dev), m))
+
+    def decode64():
+        for kl, vl, cu, m in wins:
+            D.dodo_nugget_attention(g["Qd"], g["Kn"], g["Vn"], kl, vl, cu_qd, cu_k, cu, 1, max_k, max_m + steps, scale,
+                                    D.TOKEN_MAJOR, g["Od"], ws=ws)
+    a, m = clock.batched([decode64], rounds=5, inner=1)
+    by = sum(work_attention([1] * B, ks, [w[3]] * B, wl.H, wl.H_kv, wl.d_h)["bytes"] for w in wins)
+    table["decode_64_steps"] = {"launches": steps, "avg_us": round(a, 1), "us_per_step": round(a / steps, 2),
+                                "query_tokens_per_s": round(B * steps / a * 1e6), "GBps": round(by / a * 1e-3, 1),
+                                "cache_resident": True,
+                                "note": "the same 107 MB nugget cache is re-read every step and stays in the 256 MB "
+                                        "last-level cache: not an HBM figure"}
+    table["note"] = ("batch 2 x 32768 context tokens, 10x (3277 nuggets), scores quantised to 16 levels; 1024-row query "
+                     "block; 4 rotating buffer sets")
+    del sets, wins, Kl_all, Vl_all
+    torch.cuda.empty_cache()
+    return table
 
 
 def main():
@@ -289,302 +582,41 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
-    if args.suite:
-        suite(args)
-        return
     import torch
     import paper_2310_02409_amd as D
     import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    wl = W.config(args.workload)
-    E = 2 if wl.dtype == torch.bfloat16 else 4
-    g = W.make_inputs(wl, dev)
-    B = wl.B
-    # decode sub-step: one new token per sequence; its local buffer is the prefill's plus the token itself
-    dec_local = [m + 1 for m in wl.local_lens]
-    g["Qd"] = W.normal(wl.seed, 10, (B, wl.H, wl.d_h), 1.0, wl.dtype, dev)
-    g["Kld"] = W.normal(wl.seed, 11, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
-    g["Vld"] = W.normal(wl.seed, 12, (sum(dec_local), wl.H_kv, wl.d_h), 1.0, wl.dtype, dev)
-    cu_qd, cu_ld = W.cumulative([1] * B, dev), W.cumulative(dec_local, dev)
-    cu_k, ks = D.cu_nuggets_from_lengths(wl.seq_lens, wl.keep_num, wl.keep_den, dev)
-    Kt, max_n, max_k = sum(ks), max(wl.seq_lens), max(ks)
-    max_q, max_m = max(wl.q_lens), max(wl.local_lens)
-    scale = wl.d_h ** -0.5
-
-    # every output and workspace is allocated once, outside the timed region
-    scores = torch.empty(wl.N, dtype=torch.float32, device=dev)
-    idx = torch.empty(Kt, dtype=torch.int32, device=dev)
-    Kn = torch.empty((Kt, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
-    Vn = torch.empty_like(Kn)
-    O = torch.empty_like(g["Q"])
-    Od = torch.empty_like(g["Qd"])
-    ws_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max_k, max(dec_local), D.BF16 if E == 2 else D.F32)
-    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
-
-    names = ["score", "select", "gather", "attn_block", "attn_decode"]
-
-    def step(events=None):
-        if events is not None:
-            events[0].record()
-        D.dodo_score(g["hidden"], g["w"], 0.0, scores)
-        if events is not None:
-            events[1].record()
-        D.dodo_select_topk(scores, g["cu_seqlens"], cu_k, max_n, max_k, Kt, D.FORCE_LAST, idx)
-        if events is not None:
-            events[2].record()
-        D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
-        if events is not None:
-            events[3].record()
-        D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k, max_m,
-                                scale, D.TOKEN_MAJOR, O)
-        if events is not None:
-            events[4].record()
-        D.dodo_nugget_attention(g["Qd"], Kn, Vn, g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1, max_k, max(dec_local),
-                                scale, D.TOKEN_MAJOR, Od, ws=ws)
-        if events is not None:
-            events[5].record()
-
-    if args.copy_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)  # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
-
-    work = algorithmic_work(wl, ks, E)
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # Instrumented pre-pass (not part of the timed region): events between all calls give the
-    # per-kernel breakdown and name the dominant kernel.  Each interval also contains the launch gap
-    # to the previous kernel, so short kernels read a few microseconds longer than in a kernel trace.
+    clock = Clock(torch)
+    want = [w.strip() for w in args.workloads.split(",") if w.strip()]
     kernels = {}
-    dom = None
-    if not args.no_events:
-        pre_steps = max(10, min(50, args.steps))
-        pev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(pre_steps)]
-        for k in range(pre_steps):
-            step(pev[k])
-        torch.cuda.synchronize()
-        for j, name in enumerate(names):
-            us = sorted(e[j].elapsed_time(e[j + 1]) * 1e3 for e in pev)
-            avg = sum(us) / len(us)
-            kernels[name] = {"avg_us": round(avg, 2), "median_us": round(us[len(us) // 2], 2), "min_us": round(us[0], 2),
-                             "GBps": round(work[name]["bytes"] / avg * 1e-3, 1),
-                             "TFLOPs": round(work[name]["flop"] / avg * 1e-6, 2)}
-        kernels["attn_block"]["query_tokens_per_s"] = round(sum(wl.q_lens) / kernels["attn_block"]["avg_us"] * 1e6)
-        kernels["attn_decode"]["query_tokens_per_s"] = round(B / kernels["attn_decode"]["avg_us"] * 1e6)
-        tg = kernels["select"]["avg_us"] + kernels["gather"]["avg_us"]
-        kernels["topk_plus_gather_GBps"] = round((work["select"]["bytes"] + work["gather"]["bytes"]) / tg * 1e-3, 1)
-        kernels["note"] = "instrumented pre-pass with events between all calls"
-        dom = max(names, key=lambda n: kernels[n]["avg_us"])
+    head, kernels["c4_llama13b_autoencode"], cpu = run_c4(torch, D, W, clock, dev, args)
+    nxt = None
+    if "c2" in want:
+        kernels["c2_llama7b_prefill"], nxt = run_c2(torch, D, W, clock, dev, args)
+    if "c3" in want:
+        kernels["c3_llama7b_decode"] = run_c3(torch, D, W, clock, dev, args)
+    if "c5" in want:
+        kernels["c5_long_context"] = run_c5(torch, D, W, clock, dev, args)
+    ceilings = measure_ceilings(torch, D, clock, dev)
 
-        # The autoregressive mode's selection (threshold rule), outside the step and its timing: Lambda from
-        # the step's own scores as the sample, threshold selection of the whole batch, and one decode step
-        # (append the leaving token of every sequence, then attend over the caches with room to grow).
-        cap = max_k + 64
-        lam = D.dodo_threshold_from_sample(scores, wl.keep_num, wl.keep_den)
-        Kc = torch.zeros((B, cap, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
-        Vc = torch.zeros_like(Kc)
-        counts = torch.zeros(B, dtype=torch.int32, device=dev)
-        Kc[:, :max_k] = Kn.view(B, -1, wl.H_kv, wl.d_h)[:, :max_k] if len(set(ks)) == 1 else 0
-        Vc[:, :max_k] = Vn.view(B, -1, wl.H_kv, wl.d_h)[:, :max_k] if len(set(ks)) == 1 else 0
-        counts.fill_(max_k if len(set(ks)) == 1 else 0)
-        starts = (torch.arange(B, dtype=torch.int32, device=dev) * cap).contiguous()
-        leave_s = scores[: B].clone()
-        leave_K, leave_V = g["K"][: B].contiguous(), g["V"][: B].contiguous()
-        ar_calls = {
-            "threshold_from_sample": lambda: D.dodo_threshold_from_sample(scores, wl.keep_num, wl.keep_den, out=lam),
-            "select_threshold": lambda: D.dodo_select_threshold(scores, g["cu_seqlens"], lam),
-            "stream_append": lambda: (counts.fill_(max_k if len(set(ks)) == 1 else 0),
-                                      D.dodo_stream_append(leave_s, lam, leave_K, leave_V, counts, Kc, Vc)),
-            "attn_decode_cached": lambda: D.dodo_nugget_attention_cached(
-                g["Qd"], Kc.view(B * cap, wl.H_kv, wl.d_h), Vc.view(B * cap, wl.H_kv, wl.d_h), g["Kld"], g["Vld"], cu_qd,
-                starts, counts, cu_ld, 1, cap, max(dec_local), scale, D.TOKEN_MAJOR, Od, ws=ws_c),
-        }
-        ws_c_bytes = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, cap, max(dec_local),
-                                                             D.BF16 if E == 2 else D.F32)
-        ws_c = torch.zeros(max(ws_c_bytes, 16), dtype=torch.uint8, device=dev)
-        ar = {}
-        for name, fn in ar_calls.items():
-            for _ in range(3):
-                fn()
-            torch.cuda.synchronize()
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
-            for a, b in evs:
-                a.record()
-                fn()
-                b.record()
-            torch.cuda.synchronize()
-            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
-            ar[name] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2)}
-        # the pooling baseline's compaction (same output shape as the gather)
-        for _ in range(3):
-            D.dodo_meanpool_nuggets(g["K"], g["V"], g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
-        for a, b in evs:
-            a.record()
-            D.dodo_meanpool_nuggets(g["K"], g["V"], g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
-            b.record()
-        torch.cuda.synchronize()
-        us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
-        mp_bytes = 2 * (wl.N + Kt) * wl.H_kv * wl.d_h * E
-        kernels["meanpool_baseline"] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2),
-                                        "GBps": round(mp_bytes / (sum(us) / len(us)) * 1e-3, 1)}
-        D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)  # restore the cache
-        # gather-free attention: the nuggets are read in place through the index list (no packed cache)
-        def _timed_us(fn, reps=20):
-            for _ in range(3):
-                fn()
-            torch.cuda.synchronize()
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-            for a, b in evs:
-                a.record()
-                fn()
-                b.record()
-            torch.cuda.synchronize()
-            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
-            return round(sum(us) / len(us), 2), round(us[0], 2)
-        gf = {}
-        a, m = _timed_us(lambda: D.dodo_nugget_attention_indexed(
-            g["Q"], g["K"], g["V"], idx, g["cu_seqlens"], g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k,
-            max_m, max_n, scale, O=O))
-        gf["attn_block_indexed"] = {"avg_us": a, "min_us": m}
-        a, m = _timed_us(lambda: D.dodo_nugget_attention_indexed(
-            g["Qd"], g["K"], g["V"], idx, g["cu_seqlens"], g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1, max_k,
-            max(dec_local), max_n, scale, O=Od, ws=ws))
-        gf["attn_decode_indexed"] = {"avg_us": a, "min_us": m}
-        gf["note"] = ("same results, bit for bit, as gather + attention; compare with gather + attn_block and "
-                      "gather + attn_decode above")
-        kernels["gather_free"] = gf
-        # score gradient of the straight-through estimator for this layer (backward of the block attention's
-        # nugget columns), fed with the O of the step and a fresh lse
-        if E == 2:
-            lse_b = torch.empty((g["Q"].shape[0], wl.H), dtype=torch.float32, device=dev)
-            D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q, max_k, max_m,
-                                    scale, D.TOKEN_MAJOR, O, lse=lse_b)
-            dO = W.normal(wl.seed, 99, tuple(g["Q"].shape), 1.0, wl.dtype, dev)
-            ste_ws = torch.empty(D.dodo_ste_score_grad_workspace_bytes(g["Q"].shape[0], wl.H, Kt), dtype=torch.uint8,
-                                 device=dev)
-            ste_grad = torch.empty(Kt, dtype=torch.float32, device=dev)
-            a, m = _timed_us(lambda: D.dodo_ste_score_grad(g["Q"], Kn, Vn, dO, O, lse_b, g["cu_q"], cu_k, max_q, max_k,
-                                                           scale, scale, D.TOKEN_MAJOR, grad=ste_grad, ws=ste_ws))
-            ste_flop = 4.0 * sum(q * k for q, k in zip(wl.q_lens, ks)) * wl.d_h * wl.H
-            kernels["ste_score_grad"] = {"avg_us": a, "min_us": m, "TFLOPs": round(ste_flop / a * 1e-6, 1),
-                                         "frac_of_bf16_peak": round(ste_flop / a * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 3),
-                                         "note": "whole call: row dots, the MFMA kernel, the sum over heads (training "
-                                                 "path, not part of the step)"}
-            del dO, ste_ws
-        # the scorer as a 2-layer feedforward network (d -> d -> 1) over the step's hidden states
-        if E == 2:
-            d_model = g["hidden"].shape[1]
-            gen = torch.Generator(device="cpu").manual_seed(wl.seed + 77)
-            W1 = (torch.randn(d_model, d_model, generator=gen) * d_model ** -0.5).to(torch.bfloat16).to(dev)
-            b1 = (torch.randn(d_model, generator=gen) * 0.5).to(dev)
-            w2 = (torch.randn(d_model, generator=gen) * d_model ** -0.5).to(torch.bfloat16).to(dev)
-            mlp_ws = torch.empty(max(D.dodo_score_mlp_workspace_bytes(D.BF16, wl.N, d_model, d_model), 16),
-                                 dtype=torch.uint8, device=dev)
-            mlp_out = torch.empty(wl.N, dtype=torch.float32, device=dev)
-            for _ in range(2):
-                D.dodo_score_mlp(g["hidden"], W1, b1, w2, 0.0, D.RELU, mlp_out, mlp_ws)
-            torch.cuda.synchronize()
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
-            for a, b in evs:
-                a.record()
-                D.dodo_score_mlp(g["hidden"], W1, b1, w2, 0.0, D.RELU, mlp_out, mlp_ws)
-                b.record()
-            torch.cuda.synchronize()
-            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
-            mlp_flop = 2.0 * wl.N * d_model * d_model
-            kernels["scorer_2layer"] = {"avg_us": round(sum(us) / len(us), 2), "min_us": round(us[0], 2),
-                                        "TFLOPs": round(mlp_flop / (sum(us) / len(us)) * 1e-6, 1),
-                                        "frac_of_bf16_peak": round(mlp_flop / (sum(us) / len(us)) * 1e-6 / 2500.0, 3),
-                                        "note": "ReLU, d_hid = d; replaces the linear head when used (not part of the step)"}
-            del W1, mlp_ws
-        ar["note"] = ("threshold rule of the autoregressive mode, timed apart from the step: sample = the step's "
-                      f"{wl.N} scores; stream_append includes a fill of the {B} counters; caches of {cap} rows per sequence")
-        kernels["autoregressive_mode"] = ar
-
-    # Timed region: exactly `steps` steps; the only events inside it bracket the dominant kernel.
-    dom_idx = names.index(dom) if dom is not None else -1
-
-    def timed_step(e0, e1):
-        calls = [
-            lambda: D.dodo_score(g["hidden"], g["w"], 0.0, scores),
-            lambda: D.dodo_select_topk(scores, g["cu_seqlens"], cu_k, max_n, max_k, Kt, D.FORCE_LAST, idx),
-            lambda: D.dodo_gather_nuggets(g["K"], g["V"], idx, g["cu_seqlens"], cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn),
-            lambda: D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max_q,
-                                            max_k, max_m, scale, D.TOKEN_MAJOR, O),
-            lambda: D.dodo_nugget_attention(g["Qd"], Kn, Vn, g["Kld"], g["Vld"], cu_qd, cu_k, cu_ld, 1, max_k,
-                                            max(dec_local), scale, D.TOKEN_MAJOR, Od, ws=ws),
-        ]
-        for j, c in enumerate(calls):
-            if j == dom_idx:
-                e0.record()
-                c()
-                e1.record()
-            else:
-                c()
-
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        timed_step(*ev[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    q_tokens = sum(wl.q_lens) + B
-    value = q_tokens / (ms_per_step * 1e-3)
-
-    roof = None
-    if dom is not None:
-        us = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
-        avg = sum(us) / len(us)
-        if dom == "attn_block":
-            ach = work[dom]["flop"] / avg * 1e-6
-            roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
-            # a kernel near the ridge: what the two peaks allow together at its algorithmic intensity
-            intensity = work[dom]["flop"] / work[dom]["bytes"]
-            attainable = min(MFMA_BF16_PEAK_TFLOPS, intensity * HBM_PEAK_GBS * 1e-3)
-            roof["intensity_flop_per_byte"] = round(intensity, 1)
-            roof["attainable"] = round(attainable, 1)
-            roof["frac_of_attainable"] = round(ach / attainable, 4)
-            roof["hbm_GBps_at_this_time"] = round(work[dom]["bytes"] / avg * 1e-3, 1)
-        else:
-            ach = work[dom]["bytes"] / avg * 1e-3
-            roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
-        roof["avg_us"] = round(avg, 2)
-        roof["launches"] = len(us)
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
-        if os.path.exists(tpath):  # HBM bytes per launch from the committed counter runs, if recorded for this kernel
-            roof["traffic"] = json.load(open(tpath)).get(wl.name, {}).get(dom)
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        host = {k: W.to_numpy(v) for k, v in g.items() if k in ("hidden", "w", "K", "V", "Q", "Kl", "Vl")}
-        n0, m0 = wl.seq_lens[0], wl.local_lens[0]
-        host = {k: (v[:n0] if k in ("hidden", "K", "V") else v) for k, v in host.items()}
-        host["Qd"], host["Kld"], host["Vld"] = (W.to_numpy(g[k][:m0 + 1]) for k in ("Qd", "Kld", "Vld"))
-        cpu = cpu_baseline(wl, host, ks, scale)
-        cpu["value"] = round(cpu["value"], 2)
-
+    # the targets named for this path, from the tables above
+    targets = {}
+    for wname, t in kernels.items():
+        for k in ("gather", "attn_decode"):
+            if k in t and "frac_of_hbm_peak" in t[k]:
+                targets[f"{wname}.{k}"] = {"frac_of_hbm_peak": t[k]["frac_of_hbm_peak"], "target": 0.60,
+                                           "met": t[k]["frac_of_hbm_peak"] >= 0.60}
+        if "attn_block" in t:
+            targets[f"{wname}.attn_block"] = {"frac_of_bf16_peak": t["attn_block"]["frac_of_bf16_peak"], "target": 0.40,
+                                              "met": t["attn_block"]["frac_of_bf16_peak"] >= 0.40}
     line = {
-        "metric": "nugget-attention query tokens/s (whole hot-path step: score+TopK+gather+block attention+decode token)",
-        "value": round(value, 1), "unit": "query tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if E == 2 else "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "batch": B, "context": wl.seq_lens[0] if len(set(wl.seq_lens)) == 1 else "ragged",
-                   "nuggets_per_seq": ks[0], "query_block": max_q, "local_tokens": wl.tau[0], "d_model": wl.d_model,
-                   "heads": wl.H, "head_dim": wl.d_h, "layers": 1, "decode_tokens_per_seq": 1},
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "metric": "nugget-attention query tokens/s (whole hot-path step: 40 layers of score+TopK+gather+query-block attention)",
+        "value": round(head["value"], 1), "unit": "query tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "config": head["config"], "roofline": head["roofline"], "cpu_baseline": cpu,
+        "kernels": kernels, "ceilings": ceilings, "targets": targets, "next_rows": nxt,
     }
     print(json.dumps(line))
 

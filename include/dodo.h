@@ -106,12 +106,18 @@ int dodo_score_mlp(const void* hidden, const void* W1, const float* b1, const vo
 /* Bytes of device workspace dodo_select_topk can use for B sequences of at most max_n tokens (0 for short
  * sequences).  With it, long sequences are split over several workgroups that exchange histograms and counts
  * through it; without it (NULL or too small) one workgroup per sequence does the same work, more slowly.
- * The workspace must be zero-filled before its first use; a call leaves it zero-filled, so it can be reused by
- * the next call as it is.  It must not be shared by calls that may overlap in time.  The workgroups of a
- * sequence wait for each other (bounded: about 0.1 s), so they must be able to run at the same time; the form is
- * only chosen when they fit the GPU together, and work from other streams that keeps compute units busy for
- * longer than the bound breaks it (the index lists then come out filled with the last token's index, and the
- * workspace is left non-zero). */
+ * The workspace must be zero-filled before its first use; a call leaves it zero-filled (apart from the status
+ * word), so it can be reused by the next call as it is.  It must not be shared by calls that may overlap in time.
+ * The workgroups of a sequence wait for each other (bounded: about 0.1 s), so they must be able to run at the
+ * same time; the form is only chosen when they fit the GPU together, but work from other streams that keeps
+ * compute units busy for longer than the bound, or a workspace that was not zero-filled, makes a wait run out.
+ * The first 32-bit word of the workspace is a STATUS WORD that tells: the library only ever sets bits in it
+ * (DODO_SELECT_WAIT_FAILED = 1: a wait ran out in some call since the word was last cleared; the index lists of
+ * the sequences concerned are invalid -- filled with the last token's index, which is safe to gather -- and must
+ * not be used).  A caller that uses the workspace form reads the word after the stream has drained, whenever it
+ * needs to know, and clears it itself; the rest of the workspace heals by itself (it is zero-filled again
+ * when the failed call's last workgroup ends). */
+#define DODO_SELECT_WAIT_FAILED 1u
 size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n);
 
 /*
@@ -352,6 +358,16 @@ int dodo_select_threshold(const float* scores, const int32_t* cu_seqlens, int32_
 int dodo_stream_append(const float* scores, const float* lambda, const void* K_rows, const void* V_rows, int dtype,
                        int32_t B, int32_t H_kv, int32_t d_h, int64_t row_stride, int32_t cap, int32_t* counts,
                        int32_t* dropped, void* Kn, void* Vn, void* stream);
+
+/*
+ * Measurement aids (no step of the paper's method): a read-only pass over `bytes` of src, and a plain copy of
+ * `bytes` from src to dst, written like the library's bandwidth-bound kernels.  A benchmark times them in the
+ * same run as the path's kernels, as what this device's memory system gives such code, next to the nominal
+ * peak.  Device pointers, 16-byte aligned, bytes a multiple of 16, src and dst disjoint; sink is a device word
+ * that is (practically never) written, it only keeps the loads alive.
+ */
+int dodo_probe_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+int dodo_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -70,6 +70,10 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_attention_noalloc.restype = ctypes.c_int
     L.dodo_nugget_attention_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
                                                 ctypes.c_int, ctypes.c_int, vp, vp, vp]
+    L.dodo_probe_read.restype = ctypes.c_int
+    L.dodo_probe_read.argtypes = [vp, sz, vp, vp]
+    L.dodo_probe_copy.restype = ctypes.c_int
+    L.dodo_probe_copy.argtypes = [vp, vp, sz, vp]
     L.dodo_score_mlp_workspace_bytes.restype = sz
     L.dodo_score_mlp_workspace_bytes.argtypes = [ctypes.c_int, i64, i32, i32]
     L.dodo_score_mlp.restype = ctypes.c_int
@@ -501,3 +505,16 @@ def dodo_score_mlp(hidden: torch.Tensor, W1: torch.Tensor, b1: torch.Tensor, w2:
                               hidden.stride(0), _ptr(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
            "dodo_score_mlp")
     return out
+
+
+def dodo_probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Measurement aid: a read-only pass over src (sink: one int32 device word)."""
+    _dev(src, sink)
+    _check(lib.dodo_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()), "dodo_probe_read")
+
+
+def dodo_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Measurement aid: a plain copy of src into dst."""
+    _dev(src, dst)
+    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(lib.dodo_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()), "dodo_probe_copy")

@@ -1,6 +1,10 @@
 // Host-only entry points of libdodo: version, status text, nugget count.
 #include <string.h>
 
+#include <map>
+#include <mutex>
+#include <tuple>
+
 #include "dodo_common.h"
 
 namespace dodo {
@@ -13,11 +17,53 @@ int record_hip_error(hipError_t e) {
   return DODO_ERR_HIP;
 }
 
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_cache_mutex;
+int g_cus[kMaxDevices] = {};
+std::map<std::tuple<int, const void*>, int> g_lds_granted;
+std::map<std::tuple<int, const void*, int, size_t>, int> g_resident;
+
+int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+  return dev;
+}
+}  // namespace
+
 int compute_units() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 256;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-  return cus;
+  const int dev = current_device();
+  if (dev < 0) return 256;
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  if (g_cus[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    g_cus[dev] = cus;
+  }
+  return g_cus[dev];
+}
+
+int allow_dynamic_lds(const void* kernel, int bytes) {
+  const int dev = current_device();
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  int& granted = g_lds_granted[std::make_tuple(dev, kernel)];
+  if (bytes <= granted) return DODO_OK;
+  DODO_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  granted = bytes;
+  return DODO_OK;
+}
+
+int resident_blocks_per_cu(const void* kernel, int threads, size_t lds, int fallback) {
+  const int dev = current_device();
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  int& n = g_resident[std::make_tuple(dev, kernel, threads, lds)];
+  if (n == 0) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, lds) != hipSuccess || per_cu <= 0)
+      per_cu = fallback;
+    n = per_cu;
+  }
+  return n;
 }
 }  // namespace dodo
 

@@ -6,7 +6,9 @@
 // Work split: one workgroup owns NW*32 consecutive query rows of one (sequence,
 // head); each wavefront owns 32 of them.  Keys arrive in tiles of 64: first the
 // dense nugget tiles, then the local tiles up to the causal diagonal.  K and V
-// tiles go from global memory straight into LDS (16-byte direct loads, several
+// tiles go from global memory straight into LDS (16-byte direct loads issued as
+// inline assembly, so that the compiler does not order every later LDS read behind
+// all outstanding loads: the tile loops keep that count themselves; several
 // tiles in flight), row-major with an XOR swizzle chosen so that both read
 // patterns below are conflict-free.  Per tile and wavefront:
 //   S^T = K Q^T     v_mfma_f32_32x32x16_bf16, A = K rows (LDS), B = Q^T (registers)
@@ -54,16 +56,6 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));  // hardware round-to-nearest-even pack
 }
 
-// One 16-byte-per-lane direct global->LDS load from base + voff: the lanes' data land at
-// lds_dst + 16*lane.  Issued as inline assembly so that the compiler does not order every later
-// LDS read behind all outstanding loads (it cannot tell the stages apart); the tile loops do that
-// bookkeeping themselves with explicit vmcnt waits and barriers.  base and lds_dst are
-// wavefront-uniform.
-__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_dst) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_dst)
-               : "memory");
-}
-
 // Per-lane part of the tile loads.  A 64 x 128 tile is 1024 pieces of 16 bytes; wavefront w of NW
 // fills LDS rows (64/NW)*w ..., 4 rows (1 KiB) per instruction.  The lane at LDS position
 // (row, pos) fetches the piece that the swizzle stores there:
@@ -91,8 +83,8 @@ struct TileLoader {
       const int row = row0 + 4 * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
       const uint32_t k_piece_bytes = (pos ^ (row & 15)) * 16u;
-      dma16(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
-      dma16(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
+      dma16_uniform(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
+      dma16_uniform(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
   }
   // 64 rows in the V arrangement only
@@ -100,7 +92,7 @@ struct TileLoader {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       const uint32_t roff = static_cast<uint32_t>(min(row0 + 4 * u, cnt - 1)) * stride_bytes;
-      dma16(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
   // 64 rows in the K arrangement only (also used for the query rows)
@@ -109,7 +101,7 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) {
       const int row = row0 + 4 * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
-      dma16(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
   // The same three with the rows taken through an index list: row r of the tile is token idx[r] of `base`
@@ -121,8 +113,8 @@ struct TileLoader {
       const int row = row0 + 4 * u;
       const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
       const uint32_t k_piece_bytes = (pos ^ (row & 15)) * 16u;
-      dma16(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
-      dma16(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
+      dma16_uniform(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
+      dma16_uniform(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
   }
   __device__ __forceinline__ void issue_rows_v_idx(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst,
@@ -130,7 +122,7 @@ struct TileLoader {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       const uint32_t roff = static_cast<uint32_t>(idx[min(row0 + 4 * u, cnt - 1)]) * stride_bytes;
-      dma16(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
   __device__ __forceinline__ void issue_rows_idx(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst,
@@ -139,7 +131,7 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) {
       const int row = row0 + 4 * u;
       const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
-      dma16(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
 };
@@ -758,8 +750,8 @@ int launch_nw(const AttnParams& p) {
   if (grid > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
   auto kern = block_attention_kernel<NW, IDX>;
   if (kLds > 64 * 1024) {
-    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     kLds));
+    const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(kern), kLds);
+    if (rc != DODO_OK) return rc;
   }
   hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(Cfg::kThreads), kLds, p.stream,
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),

@@ -22,8 +22,16 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int elem_bytes(int dtype) { return dtype == DODO_DTYPE_F32 ? 4 : 2; }
 inline bool dtype_ok(int dtype) { return dtype == DODO_DTYPE_F32 || dtype == DODO_DTYPE_BF16; }
 
-// Compute units of the current device (256 if the query fails).
+// Compute units of the current device (256 if the query fails); asked once per device, then remembered.
 int compute_units();
+
+// Makes sure `kernel` may be launched with `bytes` of dynamic LDS on the current device.  The runtime is asked
+// only when a kernel needs more than it was granted before on that device, so the launch path stays free of it.
+int allow_dynamic_lds(const void* kernel, int bytes);
+
+// Workgroups of `kernel` (with `threads` threads and `lds` bytes of dynamic LDS) that a compute unit of the
+// current device holds at once; asked once per (device, kernel, lds), then remembered.  `fallback` if the query fails.
+int resident_blocks_per_cu(const void* kernel, int threads, size_t lds, int fallback);
 
 // Checks the launch that was just enqueued.
 inline int launch_status() {
@@ -81,7 +89,7 @@ __device__ __forceinline__ void dma16_uniform(const void* base, uint32_t voff, u
   const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b >> 32))));
   const uint64_t ub = (static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(lds_dst)
-               : "memory");
+               : "memory", "m0");
 }
 
 // number of set bits of `mask` strictly below this lane

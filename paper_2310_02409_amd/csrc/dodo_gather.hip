@@ -5,7 +5,8 @@
 // Pure HBM copy: one workgroup per destination row moves the row's K and V
 // (H_kv*d_h elements each, 8 KiB for LLaMA-7B in bf16) with 16-byte loads that
 // are all issued before the first store.  The destination row's sequence is
-// found by a binary search over cu_nuggets, so nothing is read back to the host.
+// found on the device from cu_nuggets (one boundary per lane and a ballot for up
+// to 64 sequences, a binary search beyond), so nothing is read back to the host.
 // dodo_gather_nuggets_layers does the same for the K/V of several layers with the
 // one index list they share (Sec. 2.1), in one launch: the grid's second
 // dimension is the layer.

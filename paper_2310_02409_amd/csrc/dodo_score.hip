@@ -182,12 +182,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_pipelined_kernel(const vo
 // rows, so a grid larger than this would run in uneven rounds).
 template <typename K>
 int resident_blocks(K kernel, size_t lds) {
-  int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 1024;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kScoreThreads, lds) != hipSuccess || per_cu <= 0)
-    per_cu = 2;
-  return cus * per_cu;
+  return compute_units() * resident_blocks_per_cu(reinterpret_cast<const void*>(kernel), kScoreThreads, lds, 2);
 }
 
 template <int DTYPE, int PB>

@@ -312,8 +312,10 @@ extern "C" int dodo_score_mlp(const void* hidden, const void* W1, const float* b
     const int64_t blocks = ((N + kTokTile - 1) / kTokTile + 7) / 8 * 8 * hs;
     if (blocks > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
     constexpr int kLds = kStagesG * kStageBytesG;
-    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_mfma_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+    {
+      const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(score_mlp_mfma_kernel), kLds);
+      if (rc_lds != DODO_OK) return rc_lds;
+    }
     hipLaunchKernelGGL(score_mlp_mfma_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kMlpThreads), kLds, s,
                        static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(W1), b1,
                        static_cast<const uint16_t*>(w2), b2, act, N, d, d_hid, row_stride, hs,
@@ -333,13 +335,17 @@ extern "C" int dodo_score_mlp(const void* hidden, const void* W1, const float* b
   const int64_t blocks = (N + tok - 1) / tok;
   if (blocks > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
   if (dtype == DODO_DTYPE_BF16) {
-    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_plain_kernel<DODO_DTYPE_BF16>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    {
+      const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(score_mlp_plain_kernel<DODO_DTYPE_BF16>), static_cast<int>(lds));
+      if (rc_lds != DODO_OK) return rc_lds;
+    }
     hipLaunchKernelGGL(score_mlp_plain_kernel<DODO_DTYPE_BF16>, dim3(static_cast<unsigned>(blocks)), dim3(kPlainThreads),
                        lds, s, hidden, W1, b1, w2, b2, act, N, d, d_hid, row_stride, tok, scores);
   } else {
-    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(score_mlp_plain_kernel<DODO_DTYPE_F32>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    {
+      const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(score_mlp_plain_kernel<DODO_DTYPE_F32>), static_cast<int>(lds));
+      if (rc_lds != DODO_OK) return rc_lds;
+    }
     hipLaunchKernelGGL(score_mlp_plain_kernel<DODO_DTYPE_F32>, dim3(static_cast<unsigned>(blocks)), dim3(kPlainThreads),
                        lds, s, hidden, W1, b1, w2, b2, act, N, d, d_hid, row_stride, tok, scores);
   }

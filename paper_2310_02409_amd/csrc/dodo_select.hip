@@ -28,8 +28,11 @@ constexpr int kCandCap = 8192;             // candidate list after the first pas
 constexpr int kMultiMinKeys = 8192;        // sequences longer than this are worth several workgroups
 constexpr int kMultiChunkKeys = 4096;      // aimed-at keys per workgroup
 constexpr int kMaxChunks = 16;
-// workspace of the chunked form, per sequence: 4 histograms, 6 arrival counters (4 passes, counts, done), counts
+// workspace of the chunked form: a header whose first word is the status word, then per sequence 4 histograms,
+// 6 arrival counters (4 passes, counts, done) and the chunks' counts
+constexpr int kWsHeader = 16;
 constexpr int kWsHist = 0, kWsArrive = 4 * 256, kWsCounts = kWsArrive + 8, kWsPerSeq = kWsCounts + 2 * kMaxChunks;
+constexpr uint32_t kStatusWaitFailed = 1u;
 constexpr int kMaxPolls = 1 << 17;         // bound of a wait for the other chunks (~0.1 s, never reached in a healthy run)
 
 // MULTI: G consecutive workgroups share a sequence (chunk c = blockIdx % G); lds_keys = keys that fit in LDS.
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
   const int lo = chunk * chunk_len;
   const int n_own = max(0, min(chunk_len, n_free - lo));
   const float* s = scores + seq0 + lo;
-  uint32_t* gws = MULTI ? ws + static_cast<int64_t>(b) * kWsPerSeq : nullptr;
+  uint32_t* gws = MULTI ? ws + kWsHeader + static_cast<int64_t>(b) * kWsPerSeq : nullptr;
   // Waits until all G chunks have passed sync point `which` (thread 0 polls; device-scope accesses, which go to
   // the level where all XCDs agree).  Whatever this workgroup published before is acknowledged first.
   bool all_ok = true;
@@ -73,8 +76,11 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
     __syncthreads();
     if (tid == 0) {
       __hip_atomic_fetch_add(gws + kWsArrive + which, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      int polls = 0, ok = 1;
-      while (__hip_atomic_load(gws + kWsArrive + which, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(G)) {
+      // (exactly G: a counter that was not zero when the call began never gets there, and the call reports it;
+      // once a wait has run out this workgroup only announces itself at the later ones)
+      int polls = 0, ok = all_ok ? 1 : 0;
+      while (ok && __hip_atomic_load(gws + kWsArrive + which, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) !=
+                       static_cast<uint32_t>(G)) {
         if (++polls > kMaxPolls) {
           ok = 0;
           break;
@@ -304,13 +310,15 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
   }
   if (force && tid == 0 && chunk == 0) out[k - 1] = n - 1;
   if (MULTI && k_free > 0) {
-    // Leave the workspace as it was found (zeros): whoever is last to be done with it clears it.  A wait that ran
-    // out means a broken run: the sequence's list is filled with a valid index so that nothing downstream reads out
-    // of bounds, and the workspace stays dirty.
+    // A wait that ran out means a broken run (the chunks of a sequence were not running at the same time, or the
+    // workspace was not zero-filled): the caller learns it from the status word, and the sequence's list is filled
+    // with a valid index so that nothing downstream reads out of bounds.
     if (!all_ok) {
       for (int i = tid; i < k; i += THREADS) out[i] = n - 1;
-      return;
+      if (tid == 0) __hip_atomic_fetch_or(ws, kStatusWaitFailed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    // Leave the sequence's part of the workspace zero-filled for the next call, also after a failure: whoever
+    // is last to be done with it clears it.
     __syncthreads();
     if (tid == 0) {
       const uint32_t before = __hip_atomic_fetch_add(gws + kWsArrive + 5, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -344,8 +352,10 @@ int launch_select(const float* scores, const int32_t* cu_seqlens, const int32_t*
     const size_t lds = static_cast<size_t>(max_n) * sizeof(uint32_t) + kCandCap * sizeof(uint16_t);
     auto kern = select_topk_kernel<THREADS, true, false>;
     if (lds > 48 * 1024) {
-      DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(lds)));
+      {
+      const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(kern), static_cast<int>(lds));
+      if (rc_lds != DODO_OK) return rc_lds;
+    }
     }
     hipLaunchKernelGGL(kern, dim3(B), dim3(THREADS), lds, stream, scores, cu_seqlens, cu_nuggets, flags, max_n, max_n, 1,
                        static_cast<uint32_t*>(nullptr), nugget_idx);
@@ -362,8 +372,10 @@ int launch_select_chunked(const float* scores, const int32_t* cu_seqlens, const 
   const size_t lds = static_cast<size_t>(chunk_len) * sizeof(uint32_t) + kCandCap * sizeof(uint16_t);
   auto kern = select_topk_kernel<1024, true, true>;
   if (lds > 48 * 1024) {
-    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     static_cast<int>(lds)));
+    {
+      const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(kern), static_cast<int>(lds));
+      if (rc_lds != DODO_OK) return rc_lds;
+    }
   }
   hipLaunchKernelGGL(kern, dim3(B * G), dim3(1024), lds, stream, scores, cu_seqlens, cu_nuggets, flags, max_n, chunk_len, G,
                      ws, nugget_idx);
@@ -376,7 +388,7 @@ int launch_select_chunked(const float* scores, const int32_t* cu_seqlens, const 
 extern "C" size_t dodo_select_topk_workspace_bytes(int32_t B, int32_t max_n) {
   using namespace dodo;
   if (B <= 0 || max_n <= 0) return 0;
-  return chunk_count(B, max_n) > 0 ? static_cast<size_t>(B) * kWsPerSeq * sizeof(uint32_t) : 0;
+  return chunk_count(B, max_n) > 0 ? (kWsHeader + static_cast<size_t>(B) * kWsPerSeq) * sizeof(uint32_t) : 0;
 }
 
 extern "C" int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
@@ -391,7 +403,7 @@ extern "C" int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, 
   hipStream_t s = static_cast<hipStream_t>(stream);
   // long sequences, given the workspace: several workgroups per sequence
   const int G = chunk_count(B, max_n);
-  if (G > 0 && ws != nullptr && ws_bytes >= static_cast<size_t>(B) * kWsPerSeq * sizeof(uint32_t) &&
+  if (G > 0 && ws != nullptr && ws_bytes >= (kWsHeader + static_cast<size_t>(B) * kWsPerSeq) * sizeof(uint32_t) &&
       (reinterpret_cast<uintptr_t>(ws) & 3u) == 0)
     return launch_select_chunked(scores, cu_seqlens, cu_nuggets, B, max_n, G, flags, nugget_idx, static_cast<uint32_t*>(ws), s);
   // about four keys per thread: the kernel is latency-bound (few barriers matter more than lanes)

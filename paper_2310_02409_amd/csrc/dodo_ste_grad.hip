@@ -348,8 +348,10 @@ extern "C" int dodo_ste_score_grad(const void* Q, const void* Kn, const void* Vn
     if (grid > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
     const int max_q_pad = (max_q + kQTile - 1) / kQTile * kQTile;
     const int kLds = kStagesSte * kStageBytesSte + 2 * max_q_pad * static_cast<int>(sizeof(float));
-    DODO_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(ste_grad_mfma_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+    {
+      const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(ste_grad_mfma_kernel), kLds);
+      if (rc_lds != DODO_OK) return rc_lds;
+    }
     hipLaunchKernelGGL(ste_grad_mfma_kernel, dim3(static_cast<unsigned>(grid)), dim3(kGradThreads), kLds, s,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(Kn),
                        static_cast<const uint16_t*>(Vn), static_cast<const uint16_t*>(dO), aux_lse2, aux_D, cu_q,

@@ -88,6 +88,9 @@ def test_select_argument_validation(lib):
     assert lib.dodo_select_topk(P, P, P, -1, 10, 5, 0, P, 0, 0, 0) == -1
     assert lib.dodo_select_topk(0, 0, 0, 0, 10, 5, 0, 0, 0, 0, 0) == 0    # B == 0 is a no-op
     assert lib.dodo_select_topk_workspace_bytes(8, 4096) == 0
+    # the workspace form: a 64-byte header that starts with the status word, then a block per sequence
+    one, two = lib.dodo_select_topk_workspace_bytes(1, 32768), lib.dodo_select_topk_workspace_bytes(2, 32768)
+    assert one > 64 and one % 4 == 0 and (two - one) == (one - 64)
 
 
 def test_gather_argument_validation(lib):

@@ -162,6 +162,33 @@ def test_select_long_sequences_over_several_workgroups(D):
             assert torch.equal(got, one)
 
 
+def test_select_reports_a_wait_that_ran_out_and_heals_its_workspace(D):
+    # The chunks of a long sequence wait for each other through arrival counters in the (zero-filled) workspace.
+    # A counter that is not zero when the call begins can never reach the chunk count: the bounded waits of that
+    # sequence give up, every workgroup still ends normally, the status word (first word of the workspace) says
+    # so, the sequence's list holds a safe index, other sequences are untouched, and the workspace comes back
+    # zero-filled, so that the next call is right again.
+    n_lens = [20000, 20000]
+    k_lens = [2000, 2000]
+    need = D.dodo_select_topk_workspace_bytes(2, 20000)
+    assert need > 0
+    ws = torch.zeros(need // 4, dtype=torch.int32, device=dev())
+    first_arrival_counter = 16 + 4 * 256  # header words, then the four histograms of sequence 0
+    ws[first_arrival_counter] = 1000
+    scores = W.normal(240, 0, (sum(n_lens),), 1.0, torch.float32)
+    cu_s, cu_k = oracle.cu_from_lengths(n_lens), oracle.cu_from_lengths(k_lens)
+    ref = oracle.select_topk(scores.numpy(), cu_s, cu_k, 1)
+    args = (scores.to(dev()), torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()), 20000, 2000, 4000, 1)
+    got = D.dodo_select_topk(*args, ws=ws.view(torch.uint8)).cpu().numpy()
+    assert int(ws[0]) == 1                                  # DODO_SELECT_WAIT_FAILED
+    assert np.all(got[:2000] == 19999)                      # the failed sequence: a safe index everywhere
+    assert np.array_equal(got[2000:], ref[2000:])           # the other sequence is right
+    assert not bool(ws[1:].any())                           # healed: zero-filled again apart from the status word
+    ws[0] = 0
+    got = D.dodo_select_topk(*args, ws=ws.view(torch.uint8)).cpu().numpy()
+    assert np.array_equal(got, ref) and not bool(ws.any())
+
+
 # ---------------------------------------------------------------- gather
 @pytest.mark.parametrize("dtype,H_kv,d_h", [(torch.bfloat16, 32, 128), (torch.float32, 4, 64), (torch.bfloat16, 3, 64),
                                             (torch.bfloat16, 40, 128)])
