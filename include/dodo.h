@@ -140,9 +140,9 @@ int dodo_select_topk(const float* scores, const int32_t* cu_seqlens, const int32
  * Sub-selection (Eq. 5): packs the chosen tokens' K and V rows into the compact
  * nugget cache, bit for bit.  K, V are [N, H_kv, d_h] with `token_stride`
  * elements between tokens (>= H_kv*d_h); nugget_idx holds sequence-local
- * indices as written by dodo_select_topk; Kt = cu_nuggets[B] is the total
- * nugget count (host value), or an upper bound of it (rows from cu_nuggets[B] on are
- * left untouched).  Output Kn, Vn: [Kt, H_kv, d_h] (token-major) or
+ * indices as written by dodo_select_topk, with room for Kt entries; Kt =
+ * cu_nuggets[B] is the total nugget count (host value), or an upper bound of it
+ * (rows from cu_nuggets[B] on are left untouched).  Output Kn, Vn: [Kt, H_kv, d_h] (token-major) or
  * [H_kv, Kt, d_h] (head-major), contiguous.  Kt == 0 is a no-op.
  */
 int dodo_gather_nuggets(const void* K, const void* V, int dtype, const int32_t* nugget_idx,

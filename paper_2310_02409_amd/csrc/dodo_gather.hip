@@ -2,8 +2,8 @@
 // the compact nugget cache (Eq. 5 of the Dodo paper: nuggets are existing token
 // states, re-used rather than recomputed).
 //
-// Pure HBM copy: one workgroup per destination row moves the row's K and V
-// (H_kv*d_h elements each, 8 KiB for LLaMA-7B in bf16) with 16-byte loads that
+// Pure HBM copy: one workgroup per destination row and tensor moves the row's K or V
+// (H_kv*d_h elements, 8 KiB for LLaMA-7B in bf16) with 16-byte loads that
 // are all issued before the first store.  The destination row's sequence is
 // found on the device from cu_nuggets (one boundary per lane and a ballot for up
 // to 64 sequences, a binary search beyond), so nothing is read back to the host.
@@ -18,27 +18,22 @@ namespace {
 constexpr int kGatherThreads = 256;
 constexpr int kMaxVec = 4;  // 16-byte vectors per thread per tensor held in registers at once
 
-// Copies row src_tok of K and V (of the layer given by blockIdx.y) to row dst_tok of the nugget cache.
+// Copies row src_tok of K or of V (of the layer given by blockIdx.y) to row dst_tok of the nugget cache.
 template <bool HEAD_MAJOR>
-__device__ __forceinline__ void copy_row(const uint4* __restrict__ K, const uint4* __restrict__ V, int64_t src_tok,
-                                         int64_t dst_tok, int64_t Kt, int vec_per_head, int vec_per_row,
-                                         int64_t token_stride_vec, int64_t src_layer_stride_vec,
-                                         int64_t dst_layer_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
+__device__ __forceinline__ void copy_row(const uint4* __restrict__ src, int64_t src_tok, int64_t dst_tok, int64_t Kt,
+                                         int vec_per_head, int vec_per_row, int64_t token_stride_vec,
+                                         int64_t src_layer_stride_vec, int64_t dst_layer_stride_vec,
+                                         uint4* __restrict__ dst_base) {
   const int64_t layer = blockIdx.y;
-  const uint4* ksrc = K + layer * src_layer_stride_vec + src_tok * token_stride_vec;
-  const uint4* vsrc = V + layer * src_layer_stride_vec + src_tok * token_stride_vec;
-  Kn += layer * dst_layer_stride_vec;
-  Vn += layer * dst_layer_stride_vec;
+  const uint4* from = src + layer * src_layer_stride_vec + src_tok * token_stride_vec;
+  uint4* to = dst_base + layer * dst_layer_stride_vec;
 
   for (int c0 = threadIdx.x; c0 < vec_per_row; c0 += kGatherThreads * kMaxVec) {
-    uint4 kk[kMaxVec], vv[kMaxVec];
+    uint4 v[kMaxVec];
 #pragma unroll
     for (int u = 0; u < kMaxVec; ++u) {
       const int c = c0 + u * kGatherThreads;
-      if (c < vec_per_row) {
-        kk[u] = load16_stream(ksrc + c);
-        vv[u] = load16_stream(vsrc + c);
-      }
+      if (c < vec_per_row) v[u] = load16_stream(from + c);
     }
 #pragma unroll
     for (int u = 0; u < kMaxVec; ++u) {
@@ -51,8 +46,7 @@ __device__ __forceinline__ void copy_row(const uint4* __restrict__ K, const uint
         } else {
           dst = dst_tok * vec_per_row + c;
         }
-        store16_stream(Kn + dst, kk[u]);
-        store16_stream(Vn + dst, vv[u]);
+        store16_stream(to + dst, v[u]);
       }
     }
   }
@@ -64,20 +58,28 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt,
     int vec_per_head, int vec_per_row, int64_t token_stride_vec, int64_t src_layer_stride_vec,
     int64_t dst_layer_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
-  const int64_t dst_tok = blockIdx.x;
-  // Sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1].  The lookups before the row copy are a chain of
-  // dependent loads, each a full memory latency; for up to 64 sequences every lane of a wavefront fetches one
-  // boundary and a ballot finds b, which leaves two levels (boundaries and index in parallel, then the sequence start).
+  // two workgroups per destination row, one for its K and one for its V: rows are few (a handful per compute
+  // unit in a launch that lasts microseconds), and halves spread more evenly over the compute units
+  const int64_t dst_tok = blockIdx.x >> 1;
+  const uint4* src = (blockIdx.x & 1) ? V : K;
+  uint4* dst = (blockIdx.x & 1) ? Vn : Kn;
+  // Sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1].  The lookups before the row copy are dependent
+  // loads, each a full memory latency, in a kernel that lasts a few of them.  For up to 64 sequences everything the
+  // row address needs is fetched at once: every lane takes one boundary of cu_nuggets and one sequence start, all
+  // lanes the index entry (nugget_idx has room for Kt entries, so the load is in bounds even when Kt is only an
+  // upper bound of the nugget count); a ballot finds b and a lane read hands over its start.
   int b;
   if (B <= kWave) {
     const int lane = lane_id();
     const int bound = cu_nuggets[min(lane + 1, B)];  // upper boundary of sequence `lane`
+    const int start = cu_seqlens[min(lane, B)];      // first token of sequence `lane`
+    const int idx = nugget_idx[dst_tok];
     const uint64_t above = __ballot(lane < B && bound > dst_tok);  // sequences that end after dst_tok
     if (above == 0) return;  // dst_tok >= cu_nuggets[B]: Kt may be an upper bound of the nugget count
     b = __ffsll(static_cast<long long>(above)) - 1;
-    const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
-    copy_row<HEAD_MAJOR>(K, V, src_tok, dst_tok, Kt, vec_per_head, vec_per_row, token_stride_vec, src_layer_stride_vec,
-                         dst_layer_stride_vec, Kn, Vn);
+    const int64_t src_tok = static_cast<int64_t>(__shfl(start, b, kWave)) + idx;
+    copy_row<HEAD_MAJOR>(src, src_tok, dst_tok, Kt, vec_per_head, vec_per_row, token_stride_vec, src_layer_stride_vec,
+                         dst_layer_stride_vec, dst);
     return;
   }
   if (dst_tok >= cu_nuggets[B]) return;
@@ -88,8 +90,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
   b = lo;
   const int64_t src_tok = static_cast<int64_t>(cu_seqlens[b]) + nugget_idx[dst_tok];
-  copy_row<HEAD_MAJOR>(K, V, src_tok, dst_tok, Kt, vec_per_head, vec_per_row, token_stride_vec, src_layer_stride_vec,
-                       dst_layer_stride_vec, Kn, Vn);
+  copy_row<HEAD_MAJOR>(src, src_tok, dst_tok, Kt, vec_per_head, vec_per_row, token_stride_vec, src_layer_stride_vec,
+                       dst_layer_stride_vec, dst);
 }
 
 int gather_entry(const void* K, const void* V, int dtype, const int32_t* nugget_idx, const int32_t* cu_seqlens,
@@ -103,7 +105,7 @@ int gather_entry(const void* K, const void* V, int dtype, const int32_t* nugget_
   if (Kt == 0 || B == 0 || L == 0) return DODO_OK;
   if (!K || !V || !nugget_idx || !cu_seqlens || !cu_nuggets || !Kn || !Vn) return DODO_ERR_INVALID_ARG;
   if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
-  if (Kt > 0x7fffffffLL || L > 65535) return DODO_ERR_UNSUPPORTED;
+  if (Kt > 0x3fffffffLL || L > 65535) return DODO_ERR_UNSUPPORTED;
   const int es = elem_bytes(dtype);
   if ((static_cast<int64_t>(d_h) * es) % 16 != 0 || (token_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
   if ((src_layer_stride * es) % 16 != 0 || (dst_layer_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
@@ -114,7 +116,7 @@ int gather_entry(const void* K, const void* V, int dtype, const int32_t* nugget_
   const int64_t stride_vec = token_stride * es / 16;
   const int64_t src_l = src_layer_stride * es / 16, dst_l = dst_layer_stride * es / 16;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const dim3 grid(static_cast<unsigned>(Kt), static_cast<unsigned>(L)), block(kGatherThreads);
+  const dim3 grid(static_cast<unsigned>(2 * Kt), static_cast<unsigned>(L)), block(kGatherThreads);
   if (layout == DODO_LAYOUT_HEAD_MAJOR) {
     hipLaunchKernelGGL(gather_kernel<true>, grid, block, 0, s, static_cast<const uint4*>(K),
                        static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,

@@ -8,18 +8,20 @@ namespace dodo {
 namespace {
 
 constexpr int kProbeThreads = 256;
-constexpr int kProbeInFlight = 8;
+constexpr int kProbeInFlight = 4;
 
+// A workgroup takes whole chunks of kProbeThreads * kProbeInFlight pieces (16 KiB), chunk after chunk with the
+// grid as the stride: every wavefront reads 1 KiB of consecutive bytes per instruction, every workgroup 16 KiB.
+// (Spreading a thread's pieces a whole grid apart instead costs a quarter of the bandwidth on this device.)
 __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const uint4* __restrict__ src, int64_t n_vec,
                                                                    uint32_t* __restrict__ sink) {
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kProbeThreads;
+  constexpr int64_t kChunk = kProbeThreads * kProbeInFlight;
   uint32_t acc = 0;
-  for (int64_t i0 = static_cast<int64_t>(blockIdx.x) * kProbeThreads + threadIdx.x; i0 < n_vec;
-       i0 += stride * kProbeInFlight) {
+  for (int64_t c0 = blockIdx.x * kChunk; c0 < n_vec; c0 += gridDim.x * kChunk) {
     uint4 v[kProbeInFlight];
 #pragma unroll
     for (int u = 0; u < kProbeInFlight; ++u) {
-      const int64_t i = i0 + u * stride;
+      const int64_t i = c0 + u * kProbeThreads + threadIdx.x;
       v[u] = load16_stream(src + (i < n_vec ? i : n_vec - 1));
     }
 #pragma unroll
@@ -31,25 +33,24 @@ __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const uint4* 
 
 __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const uint4* __restrict__ src,
                                                                    uint4* __restrict__ dst, int64_t n_vec) {
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kProbeThreads;
-  for (int64_t i0 = static_cast<int64_t>(blockIdx.x) * kProbeThreads + threadIdx.x; i0 < n_vec;
-       i0 += stride * kProbeInFlight) {
+  constexpr int64_t kChunk = kProbeThreads * kProbeInFlight;
+  for (int64_t c0 = blockIdx.x * kChunk; c0 < n_vec; c0 += gridDim.x * kChunk) {
     uint4 v[kProbeInFlight];
 #pragma unroll
     for (int u = 0; u < kProbeInFlight; ++u) {
-      const int64_t i = i0 + u * stride;
+      const int64_t i = c0 + u * kProbeThreads + threadIdx.x;
       v[u] = load16_stream(src + (i < n_vec ? i : n_vec - 1));
     }
 #pragma unroll
     for (int u = 0; u < kProbeInFlight; ++u) {
-      const int64_t i = i0 + u * stride;
+      const int64_t i = c0 + u * kProbeThreads + threadIdx.x;
       if (i < n_vec) store16_stream(dst + i, v[u]);
     }
   }
 }
 
 unsigned probe_grid(int64_t n_vec) {
-  const int64_t want = (n_vec + kProbeThreads - 1) / kProbeThreads;
+  const int64_t want = (n_vec + kProbeThreads * kProbeInFlight - 1) / (kProbeThreads * kProbeInFlight);
   const int64_t fit = static_cast<int64_t>(compute_units()) * 8;  // 2048 threads per compute unit
   return static_cast<unsigned>(want < fit ? want : fit);
 }
