@@ -478,6 +478,22 @@ def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec
              frac_of_bf16_peak=round(flop / r["avg_us"] * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
              plan=t(lambda: D.dodo_segment_plan(g["idx"], g["cu_seqlens"], cu_k, seg_len, tau, n_seg)))
     out["segment_form_8x4096_seg512_tau128"] = r
+    # grouped-query decode (8 query heads per KV head): the heads of a group run on one XCD and share the rows in its L2
+    Bg, Hg, Hkvg, kg, mg = 64, 64, 8, 410, 257
+    gsets = []
+    for s_ in range(4):
+        mk = lambda tid, n, h: W.normal(wl.seed, 3000 + 8 * s_ + tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
+        gsets.append(dict(Q=mk(0, Bg, Hg), Kn=mk(1, Bg * kg, Hkvg), Vn=mk(2, Bg * kg, Hkvg), Kl=mk(3, Bg * mg, Hkvg),
+                          Vl=mk(4, Bg * mg, Hkvg)))
+    cuq, cuk, cul = W.cumulative([1] * Bg, dev), W.cumulative([kg] * Bg, dev), W.cumulative([mg] * Bg, dev)
+    Og = torch.empty_like(gsets[0]["Q"])
+    a, m_ = clock.batched([lambda t_=t_: D.dodo_nugget_attention(t_["Q"], t_["Kn"], t_["Vn"], t_["Kl"], t_["Vl"], cuq, cuk, cul, 1,
+                                                                  kg, mg, scale, D.TOKEN_MAJOR, Og) for t_ in gsets])
+    wg = work_attention([1] * Bg, [kg] * Bg, [mg] * Bg, Hg, Hkvg, wl.d_h)
+    r = hbm_row(a, wg)
+    r.update(min_us=round(m_, 2), note=f"batch {Bg}, {Hg} query heads over {Hkvg} KV heads, {kg} nuggets + {mg} local rows; "
+                                       "algorithmic bytes count every K/V row once")
+    out["gqa_decode_64_heads_8_kv_heads"] = r
     return out
 
 

@@ -2,8 +2,11 @@
 // single-token decode and small query counts: every visible K and V row is
 // read once with 16-byte loads, a group of lanes per row.
 //
-// One workgroup handles one (query row, head, split).  Its 256 threads form
-// G = 256 / lanes-per-row groups; group g walks rows g, g+G, ... of the split,
+// One workgroup handles one (query row, head, split) -- or, under grouped-query attention, GH query heads
+// that share a KV head: its lane groups are then split between those heads, every K/V row is requested by
+// the GH heads' groups in the same instructions, and the compute unit's L1 turns that into one read of the
+// row, so the row comes from HBM once per KV head rather than once per query head.  Its 256 threads form
+// G = 256 / lanes-per-row groups; with one head, group g walks rows g, g+G, ... of the split,
 // keeping an independent online-softmax state (running max, sum, d_h partial
 // outputs spread over its lanes) in base 2.  Groups are merged through LDS in
 // group order.  With several splits every workgroup but the last of a row
@@ -57,7 +60,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
     const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
     const int32_t* __restrict__ cu_ctx,
-    int H, int H_kv, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
+    int H, int H_kv, int GH, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
     void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws, uint32_t* __restrict__ flags) {
   using VT = Vec16<DTYPE>;
   constexpr int kEPL = VT::kElems;          // elements per lane
@@ -73,7 +76,25 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   const int rows_total = gridDim.x / nsplit;
   int t = blockIdx.x % rows_total;
   const int split = blockIdx.x / rows_total;
-  const int h = t % H; t /= H;
+  // Grouped-query attention: the query heads that share a KV head read the same K/V rows.  Workgroups are handed
+  // to the 8 XCDs round-robin and every XCD has an L2 of its own.  Where the heads of a group have a workgroup each
+  // (GH == 1: few workgroups in all), they are placed a multiple of 8 workgroups apart, so that they run on one XCD
+  // at about the same time and share the rows in its L2 as far as that holds them.  (Query rows of one head are H
+  // workgroups apart, which does the same when H is a multiple of 8.)
+  // GH > 1: this workgroup serves heads head0 .. head0 + GH - 1 (one KV head); else the one head head0
+  const int HG = H / GH;
+  int head0 = t % HG;
+  t /= HG;
+  if (GH == 1) {
+    const int G = H / H_kv;
+    if (G > 1 && (H_kv & 7) == 0) {
+      head0 = ((head0 / (8 * G)) * 8 + (head0 & 7)) * G + (head0 >> 3) % G;  // KV head from the position mod 8, then the head in its group
+    } else if (G > 1 && (H_kv == 1 || H_kv == 2 || H_kv == 4)) {
+      head0 = (head0 % H_kv) * G + head0 / H_kv;
+    }
+  } else {
+    head0 *= GH;
+  }
   const int i = t % max_q;
   const int b = t / max_q;
   const int q0 = cu_q[b];
@@ -86,10 +107,13 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   const int chunk = (n_vis + nsplit - 1) / nsplit;
   const int r0 = split * chunk;
   const int r1 = min(r0 + chunk, n_vis);
-  const int kvh = h / (H / H_kv);
-
   const int g = threadIdx.x / kLPR;
   const int sub = threadIdx.x % kLPR;
+  const int gh = g % GH;      // this lane group's head among the workgroup's
+  const int rs = g / GH;      // ... and its row stream: rows rs, rs + R, ... of the split
+  const int R = kGroups / GH;
+  const int h = head0 + gh;
+  const int kvh = h / (H / H_kv);  // the same for all heads of the workgroup
   const int64_t row_id = static_cast<int64_t>(q0 + i) * H + h;
 
   float q[kEPL];
@@ -120,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     if (INDEXED) {
 #pragma unroll
       for (int u = 0; u < kRowsInFlight; ++u) {
-        const int jr = j0 + u * kGroups + g;
+        const int jr = j0 + u * R + rs;
         const int j = jr < r1 ? jr : r1 - 1;
         tok[u] = j < k_b ? nug_idx[k0 + j] : 0;
       }
@@ -129,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     for (int u = 0; u < kRowsInFlight; ++u) {
       // loads are unconditional (rows past the end re-read the last row of the range and are
       // discarded): a branch around them would serialise the loads behind a full wait
-      const int jr = j0 + u * kGroups + g;
+      const int jr = j0 + u * R + rs;
       const int j = jr < r1 ? jr : r1 - 1;
       const bool nug = j < k_b;
       const int64_t nug_row = INDEXED ? ctx0 + tok[u] : static_cast<int64_t>(k0 + j);
@@ -151,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
       for (int e = 1; e < kEPL; ++e) d = fmaf(q[e], kf[e], d);
 #pragma unroll
       for (int off = kLPR / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, kWave);
-      logit[u] = (bt.j0 + u * kGroups + g < r1) ? d : kNegInf;
+      logit[u] = (bt.j0 + u * R + rs < r1) ? d : kNegInf;
       mx = fmaxf(mx, logit[u]);
     }
     if (mx != kNegInf) {  // uniform inside a group
@@ -172,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     }
   };
   {
-    constexpr int kStep = kGroups * kRowsInFlight;
+    const int kStep = R * kRowsInFlight;
     Batch ba, bb;
     int j0 = r0;  // (uniform over the workgroup, like r1)
     if (j0 < r1) load_batch(ba, j0);
@@ -187,7 +211,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     }
   }
 
-  // ---- merge the groups in group order ----
+  // ---- merge the lane groups of each head in group order ----
   if (sub == 0) {
     part_m[g] = m;
     part_s[g] = ssum;
@@ -195,135 +219,153 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) part_o[g][sub * kEPL + e] = o[e];
   __syncthreads();
-  float Mg = kNegInf, Sg = 0.f, og = 0.f;  // this workgroup's merged partial (threads < DH: channel threadIdx.x)
-  if (threadIdx.x < DH) {
-    const int c = threadIdx.x;
-    float M = kNegInf;
-    for (int gg = 0; gg < kGroups; ++gg) M = fmaxf(M, part_m[gg]);
-    float S = 0.f, oc = 0.f;
-    if (M != kNegInf) {
-      for (int gg = 0; gg < kGroups; ++gg) {
-        const float wgt = exp2_guard(part_m[gg] - M);
-        S = fmaf(part_s[gg], wgt, S);
-        oc = fmaf(part_o[gg][c], wgt, oc);
-      }
-    }
-    Mg = M;
-    Sg = S;
-    og = oc;
-    if (nsplit == 1) {
-      const float val = (S > 0.f) ? oc / S : 0.f;
-      if (DTYPE == DODO_DTYPE_F32) {
-        static_cast<float*>(O)[row_id * DH + c] = val;
-      } else {
-        static_cast<uint16_t*>(O)[row_id * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
-      }
-      if (lse != nullptr && c == 0) lse[row_id] = (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
-    }
-  }
-  if (nsplit == 1) return;
-
-  // ---- several splits: the last one combines, in split order ----
-  const int64_t slot0 = ((static_cast<int64_t>(b) * max_q + i) * H + h) * nsplit;
   __shared__ int all_there;
-  if (split + 1 < nsplit) {
-    // Records and flags are written and read with device-scope atomic accesses (plain stores and
-    // loads that go to the level where all XCDs agree), so no cache has to be written back or
-    // invalidated as a whole; the wait makes sure that the record has arrived there before the
-    // flag is sent after it.
+  for (int hh = 0; hh < GH; ++hh) {  // one head of the workgroup after the other (uniform over the workgroup)
+    const int64_t out_row = static_cast<int64_t>(q0 + i) * H + head0 + hh;
+    float Mg = kNegInf, Sg = 0.f, og = 0.f;  // this workgroup's merged partial of the head (threads < DH: channel threadIdx.x)
     if (threadIdx.x < DH) {
-      float* rec = ws + (slot0 + split) * partial_floats<DH>();
-      if (threadIdx.x == 0) {
-        __hip_atomic_store(rec + 0, Mg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(rec + 1, Sg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int c = threadIdx.x;
+      float M = kNegInf;
+      for (int gg = hh; gg < kGroups; gg += GH) M = fmaxf(M, part_m[gg]);
+      float S = 0.f, oc = 0.f;
+      if (M != kNegInf) {
+        for (int gg = hh; gg < kGroups; gg += GH) {
+          const float wgt = exp2_guard(part_m[gg] - M);
+          S = fmaf(part_s[gg], wgt, S);
+          oc = fmaf(part_o[gg][c], wgt, oc);
+        }
       }
-      __hip_atomic_store(rec + 2 + threadIdx.x, og, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this thread's stores are acknowledged
+      Mg = M;
+      Sg = S;
+      og = oc;
+      if (nsplit == 1) {
+        const float val = (S > 0.f) ? oc / S : 0.f;
+        if (DTYPE == DODO_DTYPE_F32) {
+          static_cast<float*>(O)[out_row * DH + c] = val;
+        } else {
+          static_cast<uint16_t*>(O)[out_row * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
+        }
+        if (lse != nullptr && c == 0) lse[out_row] = (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
+      }
+    }
+    if (nsplit == 1) continue;
+
+    // ---- several splits: the last one combines, in split order ----
+    const int64_t slot0 = ((static_cast<int64_t>(b) * max_q + i) * H + head0 + hh) * nsplit;
+    if (split + 1 < nsplit) {
+      // Records and flags are written and read with device-scope atomic accesses (plain stores and
+      // loads that go to the level where all XCDs agree), so no cache has to be written back or
+      // invalidated as a whole; the wait makes sure that the record has arrived there before the
+      // flag is sent after it.
+      if (threadIdx.x < DH) {
+        float* rec = ws + (slot0 + split) * partial_floats<DH>();
+        if (threadIdx.x == 0) {
+          __hip_atomic_store(rec + 0, Mg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(rec + 1, Sg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __hip_atomic_store(rec + 2 + threadIdx.x, og, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this thread's stores are acknowledged
+      }
+      __syncthreads();
+      if (threadIdx.x == 0)
+        __hip_atomic_store(flags + slot0 + split, kPartialReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      continue;
+    }
+    if (threadIdx.x == 0) {
+      int ok = 1;
+      for (int s2 = 0; ok && s2 + 1 < nsplit; ++s2) {
+        int polls = 0;
+        while (__hip_atomic_load(flags + slot0 + s2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != kPartialReady) {
+          if (++polls > kMaxPolls) {
+            ok = 0;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(16);
+        }
+      }
+      all_there = ok;
     }
     __syncthreads();
-    if (threadIdx.x == 0)
-      __hip_atomic_store(flags + slot0 + split, kPartialReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return;
-  }
-  if (threadIdx.x == 0) {
-    int ok = 1;
-    for (int s2 = 0; ok && s2 + 1 < nsplit; ++s2) {
-      int polls = 0;
-      while (__hip_atomic_load(flags + slot0 + s2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != kPartialReady) {
-        if (++polls > kMaxPolls) {
-          ok = 0;
-          break;
+    if (threadIdx.x < DH) {
+      const int c = threadIdx.x;
+      const float* rec0 = ws + slot0 * partial_floats<DH>();
+      // splits in batches of 8 with all loads of a batch issued before the first use; the own
+      // partial (the last split) comes last, so the order of the merge is the split order
+      constexpr int kBatch = 8;
+      float M = kNegInf, S = 0.f, oc = 0.f;
+      auto merge = [&](float m1, float s1, float o1) {
+        const float mb = fmaxf(M, m1);
+        if (mb != kNegInf) {
+          const float keep = exp2_guard(M - mb), wgt = exp2_guard(m1 - mb);
+          S = fmaf(s1, wgt, S * keep);
+          oc = fmaf(o1, wgt, oc * keep);
+          M = mb;
         }
-        __builtin_amdgcn_s_sleep(16);
-      }
-    }
-    all_there = ok;
-  }
-  __syncthreads();
-  if (threadIdx.x < DH) {
-    const int c = threadIdx.x;
-    const float* rec0 = ws + slot0 * partial_floats<DH>();
-    // splits in batches of 8 with all loads of a batch issued before the first use; the own
-    // partial (the last split) comes last, so the order of the merge is the split order
-    constexpr int kBatch = 8;
-    float M = kNegInf, S = 0.f, oc = 0.f;
-    auto merge = [&](float m1, float s1, float o1) {
-      const float mb = fmaxf(M, m1);
-      if (mb != kNegInf) {
-        const float keep = exp2_guard(M - mb), wgt = exp2_guard(m1 - mb);
-        S = fmaf(s1, wgt, S * keep);
-        oc = fmaf(o1, wgt, oc * keep);
-        M = mb;
-      }
-    };
-    for (int s0 = 0; s0 + 1 < nsplit; s0 += kBatch) {
-      float mm[kBatch], sv[kBatch], ov[kBatch];
+      };
+      for (int s0 = 0; s0 + 1 < nsplit; s0 += kBatch) {
+        float mm[kBatch], sv[kBatch], ov[kBatch];
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const float* r = rec0 + min(s0 + u, nsplit - 2) * partial_floats<DH>();
-        mm[u] = __hip_atomic_load(r + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sv[u] = __hip_atomic_load(r + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ov[u] = __hip_atomic_load(r + 2 + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+        for (int u = 0; u < kBatch; ++u) {
+          const float* r = rec0 + min(s0 + u, nsplit - 2) * partial_floats<DH>();
+          mm[u] = __hip_atomic_load(r + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          sv[u] = __hip_atomic_load(r + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ov[u] = __hip_atomic_load(r + 2 + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u)
-        if (s0 + u + 1 < nsplit) merge(mm[u], sv[u], ov[u]);
+        for (int u = 0; u < kBatch; ++u)
+          if (s0 + u + 1 < nsplit) merge(mm[u], sv[u], ov[u]);
+      }
+      merge(Mg, Sg, og);
+      const bool ok = all_there != 0;
+      const float nan = __builtin_nanf("");
+      const float val = !ok ? nan : (S > 0.f) ? oc / S : 0.f;  // a partial never arrived: fail loudly
+      if (DTYPE == DODO_DTYPE_F32) {
+        static_cast<float*>(O)[out_row * DH + c] = val;
+      } else {
+        static_cast<uint16_t*>(O)[out_row * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
+      }
+      if (lse != nullptr && c == 0)
+        lse[out_row] = !ok ? nan : (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
+      // the flags are left cleared for the next call on this workspace
+      for (int f = c; f + 1 < nsplit; f += DH)
+        __hip_atomic_store(flags + slot0 + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    merge(Mg, Sg, og);
-    const bool ok = all_there != 0;
-    const float nan = __builtin_nanf("");
-    const float val = !ok ? nan : (S > 0.f) ? oc / S : 0.f;  // a partial never arrived: fail loudly
-    if (DTYPE == DODO_DTYPE_F32) {
-      static_cast<float*>(O)[row_id * DH + c] = val;
-    } else {
-      static_cast<uint16_t*>(O)[row_id * DH + c] = static_cast<uint16_t>(f32_to_bf16_bits(val));
-    }
-    if (lse != nullptr && c == 0)
-      lse[row_id] = !ok ? nan : (S > 0.f) ? (M + __log2f(S)) * 0.6931471805599453f : kNegInf;
-    // the flags are left cleared for the next call on this workspace
-    if (c + 1 < nsplit) __hip_atomic_store(flags + slot0 + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();  // all_there is reused by the next head
   }
+}
+
+// Query heads of one KV head that a workgroup serves together (a power of two that divides H / H_kv and the lane
+// groups of the smallest workgroup), as long as that still leaves two workgroups per compute unit.
+int heads_per_workgroup(const AttnParams& p, int nsplit) {
+  const int G = p.H / p.H_kv;
+  int gh = 1;
+  while (gh < 8 && G % (2 * gh) == 0) gh *= 2;
+  while (gh > 1 && static_cast<int64_t>(p.B) * p.max_q * (p.H / gh) * nsplit < 2 * compute_units()) gh /= 2;
+  return gh;
 }
 
 template <int DTYPE, int DH, bool INDEXED>
 int launch_t(const AttnParams& p, int nsplit) {
-  const int64_t rows = static_cast<int64_t>(p.B) * p.max_q * p.H;
-  // few workgroups (about one per CU) with many rows each: 16 wavefronts per workgroup keep enough
-  // loads in flight; otherwise 4 wavefronts and several workgroups per CU
-  // one flag word per record: right behind the records, unless the caller keeps them elsewhere
+  const int gh = heads_per_workgroup(p, nsplit);
+  const int64_t rows = static_cast<int64_t>(p.B) * p.max_q * (p.H / gh);  // workgroups per split
+  // one flag word per record (one record per query row, head and split): right behind the records, unless the
+  // caller keeps them elsewhere
   uint32_t* flags = p.ws_flags != nullptr
                         ? static_cast<uint32_t*>(p.ws_flags)
-                        : reinterpret_cast<uint32_t*>(static_cast<float*>(p.ws) + rows * nsplit * partial_floats<DH>());
+                        : reinterpret_cast<uint32_t*>(static_cast<float*>(p.ws) +
+                                                      static_cast<int64_t>(p.B) * p.max_q * p.H * nsplit * partial_floats<DH>());
+  // few workgroups (about one per CU) with many rows each: 16 wavefronts per workgroup keep enough
+  // loads in flight; otherwise 4 wavefronts and several workgroups per CU
   const bool wide = rows * nsplit <= 512 && static_cast<int64_t>(p.max_k) + p.max_local >= 512;
   if (wide) {
     hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
                        dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
-                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
+                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, gh, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws), flags);
   } else {
     hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
                        dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
-                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
+                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, gh, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
                        static_cast<float*>(p.ws), flags);
   }
   return launch_status();

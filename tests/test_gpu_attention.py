@@ -37,11 +37,27 @@ def _full_check(D, seed, q_lens, k_lens, m_lens, H, H_kv, d_h, dtype, scale=None
 @pytest.mark.parametrize("dtype,H,H_kv,d_h", [
     (torch.float32, 4, 4, 64), (torch.bfloat16, 32, 32, 128), (torch.bfloat16, 8, 2, 128),
     (torch.bfloat16, 4, 4, 64), (torch.float32, 4, 2, 128),
+    (torch.bfloat16, 32, 8, 128), (torch.bfloat16, 64, 8, 128), (torch.float32, 32, 16, 64), (torch.bfloat16, 12, 3, 128),
 ])
 def test_decode_ragged(D, dtype, H, H_kv, d_h):
     k_lens = [205, 410, 333, 1, 0]
     m_lens = [257, 257, 40, 3, 5]
     _full_check(D, 400, [1] * 5, k_lens, m_lens, H, H_kv, d_h, dtype)
+
+
+def test_small_query_blocks_grouped_heads(D):
+    # 2 <= q < 16 rows per sequence go through the bandwidth-bound kernel too; grouped heads in both placements
+    _full_check(D, 407, [3, 15, 1, 7], [100, 31, 200, 0], [20, 15, 64, 9], 32, 8, 128, torch.bfloat16)
+    _full_check(D, 408, [5, 2], [77, 300], [5, 40], 8, 4, 64, torch.float32)
+
+
+def test_grouped_heads_served_by_one_workgroup(D):
+    # enough (sequence, row, KV head) triples that a workgroup serves the 8 (or 4) query heads of a KV head together
+    _full_check(D, 420, [15] * 6 + [3, 1], [100, 31, 200, 0, 64, 65, 17, 300], [20, 15, 64, 9, 15, 40, 3, 1], 64, 8, 128,
+                torch.bfloat16)
+    _full_check(D, 421, [4] * 19 + [2], [50] * 10 + [7] * 10, [4, 9] * 10, 32, 4, 64, torch.float32)
+    _full_check(D, 422, [1] * 70, [33 + 3 * b for b in range(70)], [17] * 70, 64, 8, 128, torch.bfloat16)
+    _full_check(D, 423, [1] * 80, [40] * 80, [9] * 80, 16, 4, 64, torch.bfloat16)
 
 
 def test_decode_split_k_paths(D):
