@@ -1,6 +1,6 @@
 """Dodo hot-path oracle: TEST INFRASTRUCTURE, not product code.
 
-Thin numpy/ctypes front end of ``dodo_oracle.cpp`` -- the plain,
+Thin numpy/ctypes front end of ``dodo_oracle.cpp`` (every function's arithmetic is there) -- the plain,
 single-threaded, double-precision CPU statement of the Dodo compression path
 (arXiv 2310.02409: Eq. 5, 6, 8, 9, 13, 14, 15 and the count rule of Sec. 2.3).
 Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
@@ -48,6 +48,9 @@ def _load():
         lib.oracle_threshold_from_sample.restype = ctypes.c_float
         lib.oracle_stream_append.restype = ctypes.c_int32
         lib.oracle_select_threshold_indices.restype = None
+        lib.oracle_segment_plan.restype = ctypes.c_int64
+        lib.oracle_attention_segment_mask.restype = None
+        lib.oracle_ste_score_grad.restype = None
         for name in ("oracle_score", "oracle_score_mlp", "oracle_select_threshold", "oracle_gather", "oracle_meanpool", "oracle_attention",
                      "oracle_attention_rows"):
             getattr(lib, name).restype = None
@@ -261,22 +264,16 @@ def segment_plan(nugget_idx, cu_seqlens, cu_nuggets, seg_len: int, tau: int):
     """Entries of the segment form of the autoregressive objective (Sec. 2.4, "Learning"): the tokens of segment c
     of a text share the splitting index t = max(0, c seg_len - tau).  Returns int32 arrays
     (seg_cu_q [E+1], nug_start, nug_len, loc_start, loc_len [E]), texts in order, segments in order."""
-    cu_q, ns, nl, ls, ll = [], [], [], [], []
+    nugget_idx, cu_seqlens, cu_nuggets = _c(nugget_idx, np.int32), _c(cu_seqlens, np.int32), _c(cu_nuggets, np.int32)
     B = len(cu_seqlens) - 1
-    for b in range(B):
-        s0, n = int(cu_seqlens[b]), int(cu_seqlens[b + 1] - cu_seqlens[b])
-        idx = [int(i) for i in nugget_idx[cu_nuggets[b]:cu_nuggets[b + 1]]]
-        c = 0
-        while c * seg_len < n:
-            t = max(0, c * seg_len - tau)
-            cu_q.append(s0 + c * seg_len)
-            ns.append(int(cu_nuggets[b]))
-            nl.append(sum(1 for i in idx if i < t))
-            ls.append(s0 + t)
-            ll.append(min((c + 1) * seg_len, n) - t)
-            c += 1
-    cu_q.append(int(cu_seqlens[B]))
-    return tuple(np.asarray(a, dtype=np.int32) for a in (cu_q, ns, nl, ls, ll))
+    E = sum(-(-int(cu_seqlens[b + 1] - cu_seqlens[b]) // seg_len) for b in range(B))
+    cu_q = np.zeros(E + 1, dtype=np.int32)
+    ns, nl, ls, ll = (np.zeros(E, dtype=np.int32) for _ in range(4))
+    got = _load().oracle_segment_plan(_p(nugget_idx), _p(cu_seqlens), _p(cu_nuggets), ctypes.c_int32(B),
+                                      ctypes.c_int32(seg_len), ctypes.c_int32(tau), ctypes.c_int64(E), _p(cu_q), _p(ns),
+                                      _p(nl), _p(ls), _p(ll))
+    assert got == E
+    return cu_q, ns, nl, ls, ll
 
 
 def attention_segment_mask(Q, Kn, Vn, K, V, nugget_idx, cu_seqlens, cu_nuggets, seg_len: int, tau: int, scale: float):
@@ -284,26 +281,18 @@ def attention_segment_mask(Q, Kn, Vn, K, V, nugget_idx, cu_seqlens, cu_nuggets, 
     shared by the tokens of a segment), one query token at a time: token i of a text, in segment c = i // seg_len
     with t = max(0, c seg_len - tau), attends over the text's nuggets whose index is below t (rows of the packed,
     token-major Kn / Vn) and the text's own tokens t .. i (rows of K / V).  Returns (O, lse) in float64."""
-    Q, Kn, Vn, K, V = (_to_f64(a) for a in (Q, Kn, Vn, K, V))
+    Q, Kn, Vn, K, V = _c(Q), _c(Kn), _c(Vn), _c(K), _c(V)
+    assert Q.dtype == Kn.dtype == Vn.dtype == K.dtype == V.dtype and K.shape == V.shape and Kn.shape == Vn.shape
+    nugget_idx, cu_seqlens, cu_nuggets = _c(nugget_idx, np.int32), _c(cu_seqlens, np.int32), _c(cu_nuggets, np.int32)
     N, H, d_h = Q.shape
     H_kv = K.shape[1]
-    O = np.zeros((N, H, d_h))
-    lse = np.zeros((N, H))
-    for b in range(len(cu_seqlens) - 1):
-        s0, n = int(cu_seqlens[b]), int(cu_seqlens[b + 1] - cu_seqlens[b])
-        k0, k1 = int(cu_nuggets[b]), int(cu_nuggets[b + 1])
-        for i in range(n):
-            t = max(0, (i // seg_len) * seg_len - tau)
-            nug_rows = [k0 + j for j in range(k1 - k0) if nugget_idx[k0 + j] < t]
-            for h in range(H):
-                kvh = h // (H // H_kv)
-                keys = np.concatenate([Kn[nug_rows, kvh], K[s0 + t:s0 + i + 1, kvh]])
-                vals = np.concatenate([Vn[nug_rows, kvh], V[s0 + t:s0 + i + 1, kvh]])
-                logits = scale * (keys @ Q[s0 + i, h])
-                m = logits.max()
-                p = np.exp(logits - m)
-                O[s0 + i, h] = (p @ vals) / p.sum()
-                lse[s0 + i, h] = m + np.log(p.sum())
+    assert K.shape == (N, H_kv, d_h) and Kn.shape[1:] == (H_kv, d_h) and H % H_kv == 0
+    O = np.zeros((N, H, d_h), dtype=np.float64)
+    lse = np.zeros((N, H), dtype=np.float64)
+    _load().oracle_attention_segment_mask(_p(Q), _p(Kn), _p(Vn), _p(K), _p(V), _p(nugget_idx), _p(cu_seqlens),
+                                          _p(cu_nuggets), ctypes.c_int32(len(cu_seqlens) - 1), ctypes.c_int32(H),
+                                          ctypes.c_int32(H_kv), ctypes.c_int32(d_h), ctypes.c_int32(seg_len),
+                                          ctypes.c_int32(tau), ctypes.c_double(scale), _dtype_code(Q), _p(O), _p(lse))
     return O, lse
 
 
@@ -313,30 +302,18 @@ def ste_score_grad(Q, Kn, Vn, Kl, Vl, dO, cu_q, cu_nuggets, cu_local, scale: flo
     softmax for query row j and nugget i, and dl/dxi = P (dP - D) with P the attention weights of Eq. 13 / Eq. 9
     (over nuggets and the causally visible local rows), dP[j, i] = dO[j] . v_i and D[j] = dO[j] . O[j].
     Token-major nugget cache; returns float64 [Kt]."""
-    Q, Kn, Vn, Kl, Vl, dO = (_to_f64(a) for a in (Q, Kn, Vn, Kl, Vl, dO))
-    H, H_kv = Q.shape[1], Kl.shape[1]
-    grad = np.zeros(Kn.shape[0])
-    for b in range(len(cu_q) - 1):
-        q0, q1 = int(cu_q[b]), int(cu_q[b + 1])
-        k0, k1 = int(cu_nuggets[b]), int(cu_nuggets[b + 1])
-        l0, l1 = int(cu_local[b]), int(cu_local[b + 1])
-        q_b, k_b, m_b = q1 - q0, k1 - k0, l1 - l0
-        for h in range(H):
-            kvh = h // (H // H_kv)
-            keys = np.concatenate([Kn[k0:k1, kvh], Kl[l0:l1, kvh]])
-            vals = np.concatenate([Vn[k0:k1, kvh], Vl[l0:l1, kvh]])
-            for j in range(q_b):
-                n_loc = max(0, min(m_b, m_b - q_b + j + 1))
-                vis = k_b + n_loc
-                if vis == 0 or k_b == 0:
-                    continue
-                xi = scale * (keys[:vis] @ Q[q0 + j, h])
-                p = np.exp(xi - xi.max())
-                p /= p.sum()
-                o = p @ vals[:vis]
-                d_p = vals[:k_b] @ dO[q0 + j, h]
-                big_d = dO[q0 + j, h] @ o
-                grad[k0:k1] += grad_scale * p[:k_b] * (d_p - big_d)
+    Q, Kn, Vn, Kl, Vl, dO = _c(Q), _c(Kn), _c(Vn), _c(Kl), _c(Vl), _c(dO)
+    assert Q.dtype == Kn.dtype == Vn.dtype == Kl.dtype == Vl.dtype == dO.dtype and dO.shape == Q.shape
+    cu_q, cu_nuggets, cu_local = _c(cu_q, np.int32), _c(cu_nuggets, np.int32), _c(cu_local, np.int32)
+    _, H, d_h = Q.shape
+    H_kv = Kl.shape[1]
+    Kt = Kn.shape[0]
+    assert Kn.shape == Vn.shape == (Kt, H_kv, d_h) and Kt == int(cu_nuggets[-1])
+    grad = np.zeros(Kt, dtype=np.float64)
+    _load().oracle_ste_score_grad(_p(Q), _p(Kn), _p(Vn), _p(Kl), _p(Vl), _p(dO), _p(cu_q), _p(cu_nuggets), _p(cu_local),
+                                  ctypes.c_int32(len(cu_q) - 1), ctypes.c_int32(H), ctypes.c_int32(H_kv),
+                                  ctypes.c_int32(d_h), ctypes.c_double(scale), ctypes.c_double(grad_scale),
+                                  _dtype_code(Q), ctypes.c_int64(Kt), _p(grad))
     return grad
 
 

@@ -13,6 +13,8 @@
 //
 // Pins (see tests/test_oracle_*.py): every function below is pinned by closed
 // forms, brute force and library cross-checks; none is "parity unpinned".
+// sanitize_main.cpp runs all of them under AddressSanitizer and
+// UndefinedBehaviorSanitizer (tests/test_sanitizers.py).
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -387,6 +389,147 @@ void oracle_attention_rows(const void* Q, const void* Kn, const void* Vn, const 
                            double* O_rows, double* lse_rows) {
   AttnArgs a{Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, cu_local, H, H_kv, d_h, scale, dtype, layout, Kt};
   for (int64_t r = 0; r < nrows; ++r) attention_row(a, row_b[r], row_h[r], row_i[r], O_rows + r * d_h, lse_rows + r);
+}
+
+// Segment form of the autoregressive objective (Sec. 2.4, "Learning"): text b is cut into segments of seg_len
+// tokens, and the tokens of segment c share the splitting index t = max(0, c * seg_len - tau).  One entry per
+// segment, texts in order, segments in order: its first query row, the text's nugget range start, how many of
+// the text's nuggets have an index below t, the first uncompressed token it sees and how many it sees up to
+// its own end.  Returns the number of entries; arrays hold `capacity` entries (seg_cu_q one more).
+int64_t oracle_segment_plan(const int32_t* nugget_idx, const int32_t* cu_seqlens, const int32_t* cu_nuggets, int32_t B,
+                            int32_t seg_len, int32_t tau, int64_t capacity, int32_t* seg_cu_q, int32_t* nug_start,
+                            int32_t* nug_len, int32_t* loc_start, int32_t* loc_len) {
+  int64_t e = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t s0 = cu_seqlens[b], n = cu_seqlens[b + 1] - cu_seqlens[b];
+    const int32_t k0 = cu_nuggets[b], k = cu_nuggets[b + 1] - cu_nuggets[b];
+    for (int32_t c = 0; static_cast<int64_t>(c) * seg_len < n; ++c) {
+      const int32_t start = c * seg_len;
+      const int32_t t = std::max(0, start - tau);
+      int32_t below = 0;
+      for (int32_t j = 0; j < k; ++j) below += nugget_idx[k0 + j] < t ? 1 : 0;
+      if (e < capacity) {
+        seg_cu_q[e] = s0 + start;
+        nug_start[e] = k0;
+        nug_len[e] = below;
+        loc_start[e] = s0 + t;
+        loc_len[e] = std::min(start + seg_len, n) - t;
+      }
+      ++e;
+    }
+  }
+  if (e <= capacity) seg_cu_q[e] = cu_seqlens[B];
+  return e;
+}
+
+// Attention under that objective, one query token at a time (Eq. 9 with the splitting index shared by a
+// segment): token i of a text, with t = max(0, (i / seg_len) * seg_len - tau), attends over the text's nuggets
+// whose index is below t (rows of the packed token-major Kn / Vn) followed by the text's own tokens t .. i
+// (rows of K / V).  Q, O: [N, H, d_h]; K, V: [N, H_kv, d_h]; O and lse in double.
+void oracle_attention_segment_mask(const void* Q, const void* Kn, const void* Vn, const void* K, const void* V,
+                                   const int32_t* nugget_idx, const int32_t* cu_seqlens, const int32_t* cu_nuggets,
+                                   int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t seg_len, int32_t tau,
+                                   double scale, int dtype, double* O, double* lse) {
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t s0 = cu_seqlens[b], n = cu_seqlens[b + 1] - cu_seqlens[b];
+    const int64_t k0 = cu_nuggets[b], k = cu_nuggets[b + 1] - cu_nuggets[b];
+    for (int64_t i = 0; i < n; ++i) {
+      const int64_t t = std::max<int64_t>(0, (i / seg_len) * seg_len - tau);
+      for (int32_t h = 0; h < H; ++h) {
+        const int32_t kvh = h / (H / H_kv);
+        const int64_t qoff = ((s0 + i) * H + h) * d_h;
+        std::vector<double> logit;
+        std::vector<int64_t> off;      // element offset of the key / value row
+        std::vector<char> is_nugget;
+        for (int64_t j = 0; j < k; ++j) {
+          if (nugget_idx[k0 + j] < t) {
+            off.push_back(((k0 + j) * H_kv + kvh) * d_h);
+            is_nugget.push_back(1);
+          }
+        }
+        for (int64_t u = t; u <= i; ++u) {
+          off.push_back(((s0 + u) * H_kv + kvh) * d_h);
+          is_nugget.push_back(0);
+        }
+        const size_t n_vis = off.size();  // never empty: token i sees itself
+        logit.resize(n_vis);
+        for (size_t j = 0; j < n_vis; ++j) {
+          const void* kb = is_nugget[j] ? Kn : K;
+          double dot = 0.0;
+          for (int32_t c = 0; c < d_h; ++c) dot += load(Q, dtype, qoff + c) * load(kb, dtype, off[j] + c);
+          logit[j] = scale * dot;
+        }
+        double M = logit[0];
+        for (size_t j = 1; j < n_vis; ++j) M = std::max(M, logit[j]);
+        double* o = O + qoff;
+        for (int32_t c = 0; c < d_h; ++c) o[c] = 0.0;
+        double denom = 0.0;
+        for (size_t j = 0; j < n_vis; ++j) {
+          const double p = std::exp(logit[j] - M);
+          denom += p;
+          const void* vb = is_nugget[j] ? Vn : V;
+          for (int32_t c = 0; c < d_h; ++c) o[c] += p * load(vb, dtype, off[j] + c);
+        }
+        for (int32_t c = 0; c < d_h; ++c) o[c] /= denom;
+        lse[(s0 + i) * H + h] = M + std::log(denom);
+      }
+    }
+  }
+}
+
+// Gradient that the straight-through estimator hands to the scores (Sec. 2.5, Eq. 17-18) for one layer:
+//   grad[i] = grad_scale * sum over heads h and query rows j of dl/dxi[j, i],
+// where xi[j, i] is the input of the softmax of query row j at nugget i and dl/dxi = P (dP - D), with P the
+// attention weights of Eq. 13 / Eq. 9 over nuggets and the causally visible local rows, dP[j, i] = dO[j] . v_i
+// and D[j] = dO[j] . O[j].  Token-major nugget cache; grad is double [Kt], overwritten.
+void oracle_ste_score_grad(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
+                           const void* dO, const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local,
+                           int32_t B, int32_t H, int32_t H_kv, int32_t d_h, double scale, double grad_scale, int dtype,
+                           int64_t Kt, double* grad) {
+  for (int64_t i = 0; i < Kt; ++i) grad[i] = 0.0;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t q0 = cu_q[b], q_b = cu_q[b + 1] - cu_q[b];
+    const int64_t k0 = cu_nuggets[b], k_b = cu_nuggets[b + 1] - cu_nuggets[b];
+    const int64_t l0 = cu_local[b], m_b = cu_local[b + 1] - cu_local[b];
+    if (k_b == 0) continue;
+    for (int32_t h = 0; h < H; ++h) {
+      const int32_t kvh = h / (H / H_kv);
+      for (int64_t j = 0; j < q_b; ++j) {
+        int64_t n_loc = m_b - q_b + j + 1;
+        n_loc = std::max<int64_t>(0, std::min(n_loc, m_b));
+        const int64_t n_vis = k_b + n_loc;
+        const int64_t qoff = ((q0 + j) * H + h) * d_h;
+        auto row_off = [&](int64_t r) { return r < k_b ? ((k0 + r) * H_kv + kvh) * d_h : ((l0 + r - k_b) * H_kv + kvh) * d_h; };
+        std::vector<double> p(n_vis);
+        double M = -std::numeric_limits<double>::infinity();
+        for (int64_t r = 0; r < n_vis; ++r) {
+          const void* kb = r < k_b ? Kn : Kl;
+          double dot = 0.0;
+          for (int32_t c = 0; c < d_h; ++c) dot += load(Q, dtype, qoff + c) * load(kb, dtype, row_off(r) + c);
+          p[r] = scale * dot;
+          M = std::max(M, p[r]);
+        }
+        double denom = 0.0;
+        for (int64_t r = 0; r < n_vis; ++r) {
+          p[r] = std::exp(p[r] - M);
+          denom += p[r];
+        }
+        std::vector<double> o(d_h, 0.0);
+        for (int64_t r = 0; r < n_vis; ++r) {
+          p[r] /= denom;
+          const void* vb = r < k_b ? Vn : Vl;
+          for (int32_t c = 0; c < d_h; ++c) o[c] += p[r] * load(vb, dtype, row_off(r) + c);
+        }
+        double big_d = 0.0;
+        for (int32_t c = 0; c < d_h; ++c) big_d += load(dO, dtype, qoff + c) * o[c];
+        for (int64_t r = 0; r < k_b; ++r) {
+          double d_p = 0.0;
+          for (int32_t c = 0; c < d_h; ++c) d_p += load(dO, dtype, qoff + c) * load(Vn, dtype, row_off(r) + c);
+          grad[k0 + r] += grad_scale * p[r] * (d_p - big_d);
+        }
+      }
+    }
+  }
 }
 
 }  // extern "C"

@@ -99,3 +99,23 @@ def test_plan_entries_reproduce_the_rule_through_the_batched_attention_oracle():
     Vl = np.concatenate([Vx[a:a + m] for a, m in zip(ls, ll)])
     O2, lse2 = oracle.attention(Qn, Kn, Vn, Kl, Vl, cu_q, oracle.cu_from_lengths(list(nl)), oracle.cu_from_lengths(list(ll)), scale)
     assert np.allclose(O, O2, rtol=1e-12, atol=1e-13) and np.allclose(lse, lse2, rtol=1e-12)
+
+
+def test_plain_loops_equal_the_library_restatement():
+    # the C++ loops against the same definition written with numpy's routines (matrix products, exp, sums):
+    # plan bit for bit, attention to double-precision rounding; bf16 and fp32 inputs, grouped heads, ragged texts
+    import numpy_pins
+    for dtype, n_lens, seg_len, tau, H, H_kv in ((torch.float32, [37, 1, 0, 20], 8, 3, 4, 2),
+                                                 (torch.bfloat16, [50, 13], 16, 40, 2, 1)):
+        N = sum(n_lens)
+        mk = lambda tid, h: W.to_numpy(W.normal(77, tid, (N, h, 16), 1.0, dtype))
+        Q, K, V, Ke, Ve = mk(0, H), mk(1, H_kv), mk(2, H_kv), mk(3, H_kv), mk(4, H_kv)
+        k_lens = [oracle.nugget_count(n, 1, 4) for n in n_lens]
+        cu_s, cu_k = oracle.cu_from_lengths(n_lens), oracle.cu_from_lengths(k_lens)
+        idx = oracle.select_topk(W.normal(77, 5, (N,), 1.0, torch.float32).numpy(), cu_s, cu_k)
+        Kn, Vn = oracle.gather(Ke, Ve, idx, cu_s, cu_k)
+        for a, b in zip(oracle.segment_plan(idx, cu_s, cu_k, seg_len, tau), numpy_pins.segment_plan(idx, cu_s, cu_k, seg_len, tau)):
+            assert np.array_equal(a, b)
+        O, lse = oracle.attention_segment_mask(Q, Kn, Vn, K, V, idx, cu_s, cu_k, seg_len, tau, 0.3)
+        O2, lse2 = numpy_pins.attention_segment_mask(Q, Kn, Vn, K, V, idx, cu_s, cu_k, seg_len, tau, 0.3)
+        assert np.allclose(O, O2, rtol=1e-12, atol=1e-13) and np.allclose(lse, lse2, rtol=1e-12, atol=1e-13)

@@ -94,3 +94,20 @@ def test_finite_difference_of_the_loss_in_the_nugget_logits():
         e = np.zeros(5); e[i] = 1e-5
         fd = (loss(e) - loss(-e)) / 2e-5
         assert abs(fd - g[i]) < 1e-7 * max(1.0, abs(g[i]))
+
+
+def test_plain_loops_equal_the_library_restatement():
+    # the C++ loops against the same definition written with numpy's routines, bf16 and fp32, grouped heads,
+    # sequences without nuggets, without local rows and with a local buffer shorter than the query block
+    import numpy_pins
+    import workloads as W
+    for dtype in (torch.float32, torch.bfloat16):
+        q_lens, k_lens, m_lens, H, H_kv, d_h = [5, 3, 0, 4], [7, 0, 3, 2], [9, 3, 2, 1], 4, 2, 16
+        mk = lambda tid, n, h: W.to_numpy(W.normal(88, tid, (n, h, d_h), 1.0, dtype))
+        Q, dO = mk(0, sum(q_lens), H), mk(1, sum(q_lens), H)
+        Kn, Vn = mk(2, sum(k_lens), H_kv), mk(3, sum(k_lens), H_kv)
+        Kl, Vl = mk(4, sum(m_lens), H_kv), mk(5, sum(m_lens), H_kv)
+        cu = [oracle.cu_from_lengths(x) for x in (q_lens, k_lens, m_lens)]
+        got = oracle.ste_score_grad(Q, Kn, Vn, Kl, Vl, dO, *cu, 0.25, 0.7)
+        want = numpy_pins.ste_score_grad(Q, Kn, Vn, Kl, Vl, dO, *cu, 0.25, 0.7)
+        assert np.allclose(got, want, rtol=1e-11, atol=1e-13)
