@@ -245,13 +245,44 @@ def run_c4(torch, D, W, clock, dev, args):
                      "to the previous launch), 40 layers on 40 distinct tensor sets; back_to_back_us = the kernel alone, "
                      "launched back to back on 4 layers' tensors")
 
-    # the paper's own form of the compress phase (Sec. 2.1): one scored layer, its indices pack every layer
-    K_all = torch.stack([t["K"] for t in lay[:8]])  # 8 layers in one allocation for the one-launch gather
-    V_all = torch.stack([t["V"] for t in lay[:8]])
-    a, _ = clock.batched([lambda: D.dodo_gather_nuggets_layers(K_all, V_all, idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR,
-                                                                Kn[:8], Vn[:8])], rounds=4, inner=2)
-    table["gather_8_layers_one_launch"] = hbm_row(a, {"bytes": 8 * work["gather"]["bytes"], "flop": 0})
-    del K_all, V_all
+    # the compress phase of all 40 layers with the layers' tensors in one allocation each
+    H_all = torch.stack([t["hidden"] for t in lay])
+    w_all = torch.stack([t["w"] for t in lay])
+    K_all = torch.stack([t["K"] for t in lay])
+    V_all = torch.stack([t["V"] for t in lay])
+    cu_s_all, cu_k_all = W.cumulative(wl.seq_lens * L, dev), W.cumulative(ks * L, dev)
+
+    def compress_3_launches():  # per-layer scores and selections: every (layer, sequence) is a sequence of one batch
+        D.dodo_score_layers(H_all, w_all, None, scores)
+        D.dodo_select_topk(scores.view(-1), cu_s_all, cu_k_all, max_n, max_k, L * Kt, D.FORCE_LAST, idx.view(-1))
+        D.dodo_gather_nuggets(K_all.view(L * wl.N, wl.H_kv, wl.d_h), V_all.view(L * wl.N, wl.H_kv, wl.d_h), idx.view(-1),
+                              cu_s_all, cu_k_all, L * Kt, D.TOKEN_MAJOR, Kn.view(L * Kt, wl.H_kv, wl.d_h),
+                              Vn.view(L * Kt, wl.H_kv, wl.d_h))
+
+    def compress_shared_indices():  # the paper's form (Sec. 2.1): one scored layer, its indices pack every layer
+        D.dodo_score(lay[0]["hidden"], lay[0]["w"], 0.0, scores[0])
+        D.dodo_select_topk(scores[0], cu_s, cu_k, max_n, max_k, Kt, D.FORCE_LAST, idx[0])
+        D.dodo_gather_nuggets_layers(K_all, V_all, idx[0], cu_s, cu_k, Kt, D.TOKEN_MAJOR, Kn, Vn)
+
+    def compress_per_layer():
+        for l in range(L):
+            calls[l][0]()
+            calls[l][1]()
+            calls[l][2]()
+    by_all = L * (work["score"]["bytes"] + work["select"]["bytes"] + work["gather"]["bytes"])
+    by_shared = work["score"]["bytes"] + work["select"]["bytes"] + L * work["gather"]["bytes"]
+    comp = {}
+    for name, fn, by, launches in (("per_layer_calls", compress_per_layer, by_all, 3 * L),
+                                   ("layered_calls", compress_3_launches, by_all, 3),
+                                   ("shared_indices", compress_shared_indices, by_shared, 3)):
+        a, m_ = clock.batched([fn], rounds=4, inner=1)
+        comp[name] = {"launches": launches, "avg_us": round(a, 1), "min_us": round(m_, 1), "GBps": round(by / a * 1e-3, 1),
+                      "frac_of_hbm_peak": round(by / a * 1e-3 / HBM_PEAK_GBS, 4), "bytes": by}
+    comp["note"] = ("compress phase of all 40 layers: per_layer_calls = 120 launches (score, select, gather per layer); "
+                    "layered_calls = dodo_score_layers + one select and one gather over the 640 (layer, sequence) segments; "
+                    "shared_indices = one scored layer whose indices pack all 40 layers (dodo_gather_nuggets_layers)")
+    table["compress_40_layers"] = comp
+    del H_all, w_all, K_all, V_all
 
     # ---- timed region: exactly `steps` steps; events only around the dominant kernel's launches
     steps = args.steps

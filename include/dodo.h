@@ -80,6 +80,18 @@ int64_t dodo_nugget_count(int64_t n, int64_t num, int64_t den);
 int dodo_score(const void* hidden, const void* w, float bias, int dtype, int64_t N, int32_t d, int64_t row_stride,
                float* scores, void* stream);
 
+/*
+ * The same Scorer for L layers in one launch (Eq. 6 / Eq. 15 per layer; for per-layer selection, where every
+ * layer rates its own hidden states): layer l reads hidden + l * hidden_layer_stride ([N, d] with row_stride)
+ * and w + l * w_layer_stride ([d]), adds biases[l] (device fp32 [L], or NULL for no bias) and writes
+ * scores + l * scores_layer_stride (fp32 [N]).  Strides in elements; hidden_layer_stride a multiple of
+ * 16 bytes; scores_layer_stride >= N; strides may be 0 (the layers share the tensor).  L == 0 is a no-op,
+ * L <= 65535.  Bit for bit what L calls of dodo_score produce.
+ */
+int dodo_score_layers(const void* hidden, const void* w, const float* biases, int dtype, int32_t L, int64_t N, int32_t d,
+                      int64_t row_stride, int64_t hidden_layer_stride, int64_t w_layer_stride,
+                      int64_t scores_layer_stride, float* scores, void* stream);
+
 /* activations of dodo_score_mlp */
 #define DODO_ACT_RELU 0
 #define DODO_ACT_GELU 1 /* x * Phi(x), erf form */

@@ -107,6 +107,12 @@ def score(hidden: np.ndarray, w: np.ndarray, bias: float = 0.0) -> np.ndarray:
     return out
 
 
+def score_layers(hidden: np.ndarray, w: np.ndarray, biases=None) -> np.ndarray:
+    """The Scorer of Eq. 6 / Eq. 15 layer by layer: hidden [L, N, d], w [L, d], biases [L] or None -> fp32 [L, N]."""
+    assert hidden.ndim == 3 and w.shape == (hidden.shape[0], hidden.shape[2])
+    return np.stack([score(hidden[l], w[l], 0.0 if biases is None else float(biases[l])) for l in range(hidden.shape[0])])
+
+
 RELU, GELU, TANH = 0, 1, 2
 
 

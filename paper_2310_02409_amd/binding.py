@@ -39,6 +39,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_count.argtypes = [i64, i64, i64]
     L.dodo_score.restype = ctypes.c_int
     L.dodo_score.argtypes = [vp, vp, f32, ctypes.c_int, i64, i32, i64, vp, vp]
+    L.dodo_score_layers.restype = ctypes.c_int
+    L.dodo_score_layers.argtypes = [vp, vp, vp, ctypes.c_int, i32, i64, i32, i64, i64, i64, i64, vp, vp]
     L.dodo_select_topk_workspace_bytes.restype = sz
     L.dodo_select_topk_workspace_bytes.argtypes = [i32, i32]
     L.dodo_select_topk.restype = ctypes.c_int
@@ -154,6 +156,24 @@ def dodo_score(hidden: torch.Tensor, w: torch.Tensor, bias: float = 0.0,
     assert scores.dtype == torch.float32 and scores.numel() == N
     _check(lib.dodo_score(_ptr(hidden), _ptr(w), float(bias), _dtype_code(hidden), N, d, hidden.stride(0),
                           _ptr(scores), _stream()), "dodo_score")
+    return scores
+
+
+def dodo_score_layers(hidden: torch.Tensor, w: torch.Tensor, biases: Optional[torch.Tensor] = None,
+                      scores: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores[l, t] = hidden[l, t] . w[l] + biases[l] (fp32 [L, N]) for hidden [L, N, d], w [L, d], in one launch."""
+    _dev(w, biases)
+    if not hidden.is_cuda or hidden.stride(2) != 1 or (scores is not None and not scores.is_cuda):
+        raise ValueError("hidden must be a device tensor [L, N, d] with unit stride along d")
+    L, N, d = hidden.shape
+    assert w.shape == (L, d) and w.dtype == hidden.dtype
+    if scores is None:
+        scores = torch.empty((L, N), dtype=torch.float32, device=hidden.device)
+    assert scores.dtype == torch.float32 and scores.shape == (L, N) and scores.stride(1) == 1
+    assert biases is None or (biases.dtype == torch.float32 and biases.numel() == L)
+    _check(lib.dodo_score_layers(_ptr(hidden), _ptr(w), _ptr(biases), _dtype_code(hidden), L, N, d, hidden.stride(1),
+                                 hidden.stride(0), w.stride(0), scores.stride(0), _ptr(scores), _stream()),
+           "dodo_score_layers")
     return scores
 
 

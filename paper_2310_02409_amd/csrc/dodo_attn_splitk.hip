@@ -53,15 +53,17 @@ constexpr int kMaxPolls = 1 << 17;               // bound of the combiner's wait
 
 // INDEXED: Kn / Vn are the context's K / V ([N, H_kv, DH], nug_tok_stride between tokens) and nugget j of
 // sequence b is token cu_ctx[b] + nug_idx[cu_nuggets[b] + j] of it (no packed cache has been made).
-template <int DTYPE, int DH, int kThreads, bool INDEXED>
+// GROUPED: the workgroup serves GH > 1 query heads of one KV head (else GH is 1 and everything about it folds away).
+template <int DTYPE, int DH, int kThreads, bool INDEXED, bool GROUPED>
 __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const void* __restrict__ Q, const void* __restrict__ Kn, const void* __restrict__ Vn,
     const void* __restrict__ Kl, const void* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
     const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
     const int32_t* __restrict__ cu_ctx,
-    int H, int H_kv, int GH, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
+    int H, int H_kv, int GH_arg, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
     void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws, uint32_t* __restrict__ flags) {
+  const int GH = GROUPED ? GH_arg : 1;
   using VT = Vec16<DTYPE>;
   constexpr int kEPL = VT::kElems;          // elements per lane
   constexpr int kLPR = DH / kEPL;           // lanes per K/V row
@@ -357,17 +359,18 @@ int launch_t(const AttnParams& p, int nsplit) {
   // few workgroups (about one per CU) with many rows each: 16 wavefronts per workgroup keep enough
   // loads in flight; otherwise 4 wavefronts and several workgroups per CU
   const bool wide = rows * nsplit <= 512 && static_cast<int64_t>(p.max_k) + p.max_local >= 512;
+  const dim3 grid(static_cast<unsigned>(rows * nsplit));
+#define DODO_LAUNCH_SPLITK(THREADS, GROUPED)                                                                               \
+  hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, THREADS, INDEXED, GROUPED>), grid, dim3(THREADS), 0, p.stream, p.Q,  \
+                     p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.nug_idx, p.cu_ctx, p.H, \
+                     p.H_kv, gh, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,             \
+                     static_cast<float*>(p.ws), flags)
   if (wide) {
-    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 1024, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
-                       dim3(1024), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
-                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, gh, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
-                       static_cast<float*>(p.ws), flags);
+    if (gh > 1) DODO_LAUNCH_SPLITK(1024, true); else DODO_LAUNCH_SPLITK(1024, false);
   } else {
-    hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, 256, INDEXED>), dim3(static_cast<unsigned>(rows * nsplit)),
-                       dim3(256), 0, p.stream, p.Q, p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len,
-                       p.nug_idx, p.cu_ctx, p.H, p.H_kv, gh, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,
-                       static_cast<float*>(p.ws), flags);
+    if (gh > 1) DODO_LAUNCH_SPLITK(256, true); else DODO_LAUNCH_SPLITK(256, false);
   }
+#undef DODO_LAUNCH_SPLITK
   return launch_status();
 }
 

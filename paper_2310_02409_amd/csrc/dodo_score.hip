@@ -13,6 +13,13 @@ namespace {
 constexpr int kScoreThreads = 256;
 constexpr int kUnroll = 8;  // 16-byte loads in flight per lane
 
+// Layer dimension of a launch (grid y): layer l reads hidden + l * hidden_ls and w + l * w_ls (elements), writes
+// scores + l * scores_ls and adds biases[l] (or the one bias when biases is null).  A single layer: all zero.
+struct LayerDim {
+  int64_t hidden_ls, w_ls, scores_ls;
+  const float* biases;
+};
+
 template <int DTYPE>
 struct Elems;
 template <>
@@ -59,11 +66,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 template <int DTYPE>
-__global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __restrict__ hidden,
-                                                              const void* __restrict__ w, float bias, int64_t N,
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __restrict__ hidden_all,
+                                                              const void* __restrict__ w_all, float bias, int64_t N,
                                                               int d, int64_t row_stride,
-                                                              float* __restrict__ scores) {
+                                                              float* __restrict__ scores_all, LayerDim ld) {
   using E = Elems<DTYPE>;
+  const int64_t layer = blockIdx.y;
+  const size_t esz_l = DTYPE == DODO_DTYPE_F32 ? 4 : 2;
+  const void* hidden = static_cast<const char*>(hidden_all) + layer * ld.hidden_ls * esz_l;
+  const void* w = static_cast<const char*>(w_all) + layer * ld.w_ls * esz_l;
+  float* scores = scores_all + layer * ld.scores_ls;
+  if (ld.biases != nullptr) bias = ld.biases[layer];
   constexpr int kEPL = E::kPerLoad;     // elements per 16-byte load
   constexpr int kChunk = kWave * kEPL;  // elements one wave-wide load covers
   extern __shared__ __attribute__((aligned(16))) float w_lds[];
@@ -110,13 +123,19 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
 // SINGLE: the whole row is one batch (nb == 1); the weight fragments are then loop-invariant and
 // stay in registers.
 template <int DTYPE, int PB, bool SINGLE>
-__global__ __launch_bounds__(kScoreThreads) void score_pipelined_kernel(const void* __restrict__ hidden,
-                                                                        const void* __restrict__ w, float bias,
+__global__ __launch_bounds__(kScoreThreads) void score_pipelined_kernel(const void* __restrict__ hidden_all,
+                                                                        const void* __restrict__ w_all, float bias,
                                                                         int64_t N, int d, int nb_arg,
                                                                         int64_t row_stride,
-                                                                        float* __restrict__ scores) {
+                                                                        float* __restrict__ scores_all, LayerDim ld) {
   const int nb = SINGLE ? 1 : nb_arg;
   using E = Elems<DTYPE>;
+  const int64_t layer = blockIdx.y;
+  const size_t esz_l = DTYPE == DODO_DTYPE_F32 ? 4 : 2;
+  const void* hidden = static_cast<const char*>(hidden_all) + layer * ld.hidden_ls * esz_l;
+  const void* w = static_cast<const char*>(w_all) + layer * ld.w_ls * esz_l;
+  float* scores = scores_all + layer * ld.scores_ls;
+  if (ld.biases != nullptr) bias = ld.biases[layer];
   constexpr int kEPL = E::kPerLoad;
   constexpr int kChunk = kWave * kEPL;
   extern __shared__ __attribute__((aligned(16))) float w_lds[];
@@ -187,23 +206,23 @@ int resident_blocks(K kernel, size_t lds) {
 
 template <int DTYPE, int PB>
 void launch_pipelined(const void* hidden, const void* w, float bias, int64_t N, int d, int nb, int64_t row_stride,
-                      float* scores, unsigned blocks, size_t lds, hipStream_t s) {
+                      float* scores, unsigned blocks, size_t lds, hipStream_t s, int L, const LayerDim& ld) {
   if (nb == 1) {
     const int cap = resident_blocks(score_pipelined_kernel<DTYPE, PB, true>, lds);
     if (blocks > static_cast<unsigned>(cap)) blocks = cap;
-    hipLaunchKernelGGL((score_pipelined_kernel<DTYPE, PB, true>), dim3(blocks), dim3(kScoreThreads), lds, s, hidden, w,
-                       bias, N, d, nb, row_stride, scores);
+    hipLaunchKernelGGL((score_pipelined_kernel<DTYPE, PB, true>), dim3(blocks, L), dim3(kScoreThreads), lds, s, hidden, w,
+                       bias, N, d, nb, row_stride, scores, ld);
   } else {
     const int cap = resident_blocks(score_pipelined_kernel<DTYPE, PB, false>, lds);
     if (blocks > static_cast<unsigned>(cap)) blocks = cap;
-    hipLaunchKernelGGL((score_pipelined_kernel<DTYPE, PB, false>), dim3(blocks), dim3(kScoreThreads), lds, s, hidden, w,
-                       bias, N, d, nb, row_stride, scores);
+    hipLaunchKernelGGL((score_pipelined_kernel<DTYPE, PB, false>), dim3(blocks, L), dim3(kScoreThreads), lds, s, hidden, w,
+                       bias, N, d, nb, row_stride, scores, ld);
   }
 }
 
 template <int DTYPE>
 bool try_pipelined(const void* hidden, const void* w, float bias, int64_t N, int d, int64_t row_stride, float* scores,
-                   unsigned blocks, size_t lds, hipStream_t s) {
+                   unsigned blocks, size_t lds, hipStream_t s, int L, const LayerDim& ld) {
   constexpr int kChunk = kWave * Elems<DTYPE>::kPerLoad;
   if (d % kChunk != 0) return false;
   const int chunks = d / kChunk;
@@ -211,14 +230,14 @@ bool try_pipelined(const void* hidden, const void* w, float bias, int64_t N, int
   if (chunks % nb != 0) return false;
   const int pb = chunks / nb;
   switch (pb) {
-    case 1: launch_pipelined<DTYPE, 1>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 2: launch_pipelined<DTYPE, 2>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 3: launch_pipelined<DTYPE, 3>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 4: launch_pipelined<DTYPE, 4>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 5: launch_pipelined<DTYPE, 5>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 6: launch_pipelined<DTYPE, 6>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 7: launch_pipelined<DTYPE, 7>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
-    case 8: launch_pipelined<DTYPE, 8>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s); return true;
+    case 1: launch_pipelined<DTYPE, 1>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 2: launch_pipelined<DTYPE, 2>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 3: launch_pipelined<DTYPE, 3>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 4: launch_pipelined<DTYPE, 4>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 5: launch_pipelined<DTYPE, 5>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 6: launch_pipelined<DTYPE, 6>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 7: launch_pipelined<DTYPE, 7>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
+    case 8: launch_pipelined<DTYPE, 8>(hidden, w, bias, N, d, nb, row_stride, scores, blocks, lds, s, L, ld); return true;
     default: return false;
   }
 }
@@ -226,16 +245,18 @@ bool try_pipelined(const void* hidden, const void* w, float bias, int64_t N, int
 }  // namespace
 }  // namespace dodo
 
-extern "C" int dodo_score(const void* hidden, const void* w, float bias, int dtype, int64_t N, int32_t d,
-                          int64_t row_stride, float* scores, void* stream) {
-  using namespace dodo;
-  if (N < 0 || d <= 0 || row_stride < d) return DODO_ERR_INVALID_ARG;
-  if (N == 0) return DODO_OK;
+namespace dodo {
+namespace {
+
+int score_entry(const void* hidden, const void* w, float bias, int dtype, int64_t N, int32_t d, int64_t row_stride,
+                float* scores, int32_t L, const LayerDim& ld, void* stream) {
+  if (N < 0 || d <= 0 || row_stride < d || L < 0) return DODO_ERR_INVALID_ARG;
+  if (N == 0 || L == 0) return DODO_OK;
   if (!hidden || !w || !scores) return DODO_ERR_INVALID_ARG;
   if (!dtype_ok(dtype)) return DODO_ERR_UNSUPPORTED;
   const int es = elem_bytes(dtype);
-  if (d % 8 != 0 || d > 16384) return DODO_ERR_UNSUPPORTED;
-  if (!aligned16(hidden) || (row_stride * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
+  if (d % 8 != 0 || d > 16384 || L > 65535) return DODO_ERR_UNSUPPORTED;
+  if (!aligned16(hidden) || (row_stride * es) % 16 != 0 || (ld.hidden_ls * es) % 16 != 0) return DODO_ERR_UNSUPPORTED;
 
   const int waves_per_block = kScoreThreads / kWave;
   int64_t blocks = (N + waves_per_block - 1) / waves_per_block;
@@ -245,17 +266,35 @@ extern "C" int dodo_score(const void* hidden, const void* w, float bias, int dty
   hipStream_t s = static_cast<hipStream_t>(stream);
   // widths that split evenly into batches of wave-wide loads (4096, 5120, 8192, ...) take the pipelined kernel
   const unsigned nblk = static_cast<unsigned>(blocks);
-  if (dtype == DODO_DTYPE_BF16 ? try_pipelined<DODO_DTYPE_BF16>(hidden, w, bias, N, d, row_stride, scores, nblk, lds, s)
-                               : try_pipelined<DODO_DTYPE_F32>(hidden, w, bias, N, d, row_stride, scores, nblk, lds, s))
+  if (dtype == DODO_DTYPE_BF16
+          ? try_pipelined<DODO_DTYPE_BF16>(hidden, w, bias, N, d, row_stride, scores, nblk, lds, s, L, ld)
+          : try_pipelined<DODO_DTYPE_F32>(hidden, w, bias, N, d, row_stride, scores, nblk, lds, s, L, ld))
     return launch_status();
   if (dtype == DODO_DTYPE_BF16) {
     const int64_t fit = resident_blocks(score_kernel<DODO_DTYPE_BF16>, lds);
-    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_BF16>, dim3(static_cast<unsigned>(blocks < fit ? blocks : fit)),
-                       dim3(kScoreThreads), lds, s, hidden, w, bias, N, d, row_stride, scores);
+    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_BF16>, dim3(static_cast<unsigned>(blocks < fit ? blocks : fit), L),
+                       dim3(kScoreThreads), lds, s, hidden, w, bias, N, d, row_stride, scores, ld);
   } else {
     const int64_t fit = resident_blocks(score_kernel<DODO_DTYPE_F32>, lds);
-    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_F32>, dim3(static_cast<unsigned>(blocks < fit ? blocks : fit)),
-                       dim3(kScoreThreads), lds, s, hidden, w, bias, N, d, row_stride, scores);
+    hipLaunchKernelGGL(score_kernel<DODO_DTYPE_F32>, dim3(static_cast<unsigned>(blocks < fit ? blocks : fit), L),
+                       dim3(kScoreThreads), lds, s, hidden, w, bias, N, d, row_stride, scores, ld);
   }
   return launch_status();
+}
+
+}  // namespace
+}  // namespace dodo
+
+extern "C" int dodo_score(const void* hidden, const void* w, float bias, int dtype, int64_t N, int32_t d,
+                          int64_t row_stride, float* scores, void* stream) {
+  return dodo::score_entry(hidden, w, bias, dtype, N, d, row_stride, scores, 1, dodo::LayerDim{0, 0, 0, nullptr}, stream);
+}
+
+extern "C" int dodo_score_layers(const void* hidden, const void* w, const float* biases, int dtype, int32_t L, int64_t N,
+                                 int32_t d, int64_t row_stride, int64_t hidden_layer_stride, int64_t w_layer_stride,
+                                 int64_t scores_layer_stride, float* scores, void* stream) {
+  if (hidden_layer_stride < 0 || w_layer_stride < 0 || scores_layer_stride < 0) return DODO_ERR_INVALID_ARG;
+  if (L > 1 && scores_layer_stride < N) return DODO_ERR_INVALID_ARG;
+  return dodo::score_entry(hidden, w, 0.f, dtype, N, d, row_stride, scores, L,
+                           dodo::LayerDim{hidden_layer_stride, w_layer_stride, scores_layer_stride, biases}, stream);
 }

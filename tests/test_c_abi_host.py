@@ -76,6 +76,12 @@ def test_score_argument_validation(lib):
     assert lib.dodo_score(P, P, 0.0, 1, 8, 64, 32, P, 0) == -1          # stride < d
     assert lib.dodo_score(P, P, 0.0, 7, 8, 64, 64, P, 0) == -2          # dtype
     assert lib.dodo_score(P, P, 0.0, 1, 8, 60, 64, P, 0) == -2          # d not a multiple of 8
+    i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+    lib.dodo_score_layers.argtypes = [vp, vp, vp, ctypes.c_int, i32, i64, i32, i64, i64, i64, i64, vp, vp]
+    assert lib.dodo_score_layers(P, P, None, 1, 3, 8, 64, 64, 8 * 64, 64, 4, P, None) == -1   # layers of scores overlap
+    assert lib.dodo_score_layers(P, P, None, 1, 3, 8, 64, 64, -1, 64, 8, P, None) == -1       # negative stride
+    assert lib.dodo_score_layers(P, P, None, 1, 0, 8, 64, 64, 8 * 64, 64, 8, P, None) == 0    # no layers: no-op
+    assert lib.dodo_score_layers(P, P, None, 1, 70000, 8, 64, 64, 8 * 64, 64, 8, P, None) == -2
     assert lib.dodo_score(P + 2, P, 0.0, 1, 8, 64, 64, P, 0) == -2      # misaligned
     assert lib.dodo_score(0, 0, 0.0, 1, 0, 64, 64, 0, 0) == 0           # N == 0 is a no-op
 

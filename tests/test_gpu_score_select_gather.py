@@ -55,6 +55,26 @@ def test_score_is_deterministic_and_respects_row_stride(D):
         assert torch.equal(scores, first)
 
 
+@pytest.mark.parametrize("dtype,L,N,d", [(torch.bfloat16, 5, 700, 4096), (torch.float32, 3, 129, 256), (torch.bfloat16, 2, 64, 1000)])
+def test_score_layers_matches_oracle_and_the_single_layer_call(D, dtype, L, N, d):
+    x = W.normal(130, 0, (L, N, d), 1.0, dtype)
+    w = W.normal(130, 1, (L, d), d ** -0.5, dtype)
+    b = W.normal(130, 2, (L,), 1.0, torch.float32)
+    ref = oracle.score_layers(W.to_numpy(x), W.to_numpy(w), b.numpy())
+    xd, wd, bd = x.to(dev()), w.to(dev()), b.to(dev())
+    got = D.dodo_score_layers(xd, wd, bd, scores=torch.full((L, N), float("nan"), device=dev()))
+    assert np.all(np.abs(got.cpu().numpy() - ref) <= 1e-5 * (1 + np.abs(ref)))
+    for l in range(L):
+        assert torch.equal(got[l], D.dodo_score(xd[l], wd[l], float(b[l])))
+    # no biases; padded rows and room between the layers of the output
+    xp = torch.zeros((L, N + 3, d + 8), dtype=dtype, device=dev())
+    xp[:, :N, :d] = xd
+    out = torch.full((L, 2 * N), 7.0, device=dev())
+    D.dodo_score_layers(xp[:, :N, :d], wd, None, scores=out[:, :N])
+    ref0 = oracle.score_layers(W.to_numpy(x), W.to_numpy(w))
+    assert np.all(np.abs(out[:, :N].cpu().numpy() - ref0) <= 1e-5 * (1 + np.abs(ref0))) and bool((out[:, N:] == 7.0).all())
+
+
 # ---------------------------------------------------------------- select
 def _select_both(D, scores_np, n_lens, k_lens, flags=0):
     cu_s, cu_k = oracle.cu_from_lengths(n_lens), oracle.cu_from_lengths(k_lens)

@@ -71,3 +71,14 @@ def test_negative_zero_is_canonicalised():
     w = np.array([0.0, 1.0], dtype=np.float32)
     s = oracle.score(x, w)
     assert s[0] == 0 and not np.signbit(s[0])
+
+
+def test_score_layers_is_the_scorer_layer_by_layer():
+    L, N, d = 3, 17, 24
+    x = W.normal(31, 0, (L, N, d), 1.0, torch.float32)
+    w = W.normal(31, 1, (L, d), 0.3, torch.float32)
+    b = np.array([0.5, -1.25, 0.0], dtype=np.float32)
+    got = oracle.score_layers(x.numpy(), w.numpy(), b)
+    want = (torch.einsum("lnd,ld->ln", x.double(), w.double()) + torch.from_numpy(b).double()[:, None]).float().numpy()
+    assert np.array_equal(got, want)  # float64 sums of 24 products, rounded once
+    assert np.array_equal(oracle.score_layers(x.numpy(), w.numpy())[1], oracle.score(x[1].numpy(), w[1].numpy()))
