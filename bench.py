@@ -525,6 +525,19 @@ def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec
     r.update(min_us=round(m_, 2), note=f"batch {Bg}, {Hg} query heads over {Hkvg} KV heads, {kg} nuggets + {mg} local rows; "
                                        "algorithmic bytes count every K/V row once")
     out["gqa_decode_64_heads_8_kv_heads"] = r
+    # query-block attention with 64-wide heads (64 heads x 64: the same flop count as the 32 x 128 workload)
+    mk = lambda tid, n, h: W.normal(wl.seed, 3100 + tid, (n, h, 64), 1.0, wl.dtype, dev)
+    Q6, Kn6, Vn6 = mk(0, sum(wl.q_lens), 64), mk(1, Kt, 64), mk(2, Kt, 64)
+    Kl6, Vl6 = mk(3, sum(wl.local_lens), 64), mk(4, sum(wl.local_lens), 64)
+    O6 = torch.empty_like(Q6)
+    r = t(lambda: D.dodo_nugget_attention(Q6, Kn6, Vn6, Kl6, Vl6, g["cu_q"], cu_k, g["cu_local"], max_q, max_k, max_m, 0.125,
+                                          D.TOKEN_MAJOR, O6))
+    w6 = work_attention(wl.q_lens, ks, wl.local_lens, 64, 64, 64)
+    r.update(TFLOPs=round(w6["flop"] / r["avg_us"] * 1e-6, 1),
+             frac_of_bf16_peak=round(w6["flop"] / r["avg_us"] * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+             note="workload 2's shape with 64 heads of 64 channels: half the matrix work per key and query row, the same "
+                  "softmax work, so the vector pipe bounds it")
+    out["attn_block_64_wide_heads"] = r
     return out
 
 

@@ -199,7 +199,8 @@ size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, 
  * multiplied on the matrix cores with fp32 accumulation when max_q >= 16
  * (query-block kernel); smaller max_q and all fp32 inputs use the bandwidth-
  * bound split-K kernel, whose last split combines the partials in split order.  Both are deterministic.
- * Supported: d_h in {64, 128} for the split-K kernel, d_h = 128 for the block kernel.
+ * Supported: d_h in {64, 128}, fp32 or bf16.  Under grouped-query heads the split-K kernel serves the query heads of
+ * a KV head from one workgroup when there are enough (sequence, row, KV head) triples to fill the GPU that way.
  */
 int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
                           const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local, int32_t B,
@@ -261,7 +262,7 @@ int dodo_nugget_attention_cached(const void* Q, const void* Kn, const void* Vn, 
  * bit for bit; the other arguments are those of dodo_nugget_attention, and
  * dodo_nugget_attention_workspace_bytes gives the workspace for the same bounds.  max_n is a host-
  * side upper bound on the context length of a sequence.  Limits of the query-block kernel (bf16,
- * d_h = 128, max_q >= 16): max_k <= 7680 (4096 when max_q <= 128), max_n * token_stride *
+ * max_q >= 16): max_k <= 7680 (4096 when max_q <= 128), max_n * token_stride *
  * sizeof(element) < 2^31; beyond them DODO_ERR_UNSUPPORTED (pack the cache instead).
  * Meant for caches that are read once: a packed cache is cheaper to read again and lets the
  * context's K/V be freed, which is the point of the method.

@@ -10,7 +10,7 @@ namespace {
 constexpr int kBlockKernelMinQ = 16;
 
 bool use_block_kernel(int dtype, int32_t d_h, int32_t max_q) {
-  return dtype == DODO_DTYPE_BF16 && d_h == 128 && max_q >= kBlockKernelMinQ;
+  return dtype == DODO_DTYPE_BF16 && (d_h == 128 || d_h == 64) && max_q >= kBlockKernelMinQ;
 }
 
 }  // namespace

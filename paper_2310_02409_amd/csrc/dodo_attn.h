@@ -32,7 +32,7 @@ size_t splitk_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, 
 
 // fp32 or bf16, d_h in {64,128}, any max_q: one workgroup per (query row, head, split).
 int launch_splitk_attention(const AttnParams& p);
-// bf16, d_h = 128: MFMA kernel over 128-row query blocks.
+// bf16, d_h in {64,128}: MFMA kernel over 128- or 256-row query blocks.
 int launch_block_attention(const AttnParams& p);
 
 }  // namespace dodo

@@ -1,7 +1,8 @@
 // Query-block nugget attention on the matrix cores (Eq. 13 / Eq. 9 of the Dodo
 // paper): each query row attends over all nuggets of its sequence, then over
 // the causally visible part of the local (uncompressed) rows.  bf16 inputs,
-// fp32 accumulation, d_h = 128.  Inputs must be finite.
+// fp32 accumulation, d_h = 128 or 64 (a template parameter: the tile loops, LDS
+// layout and fragment counts follow from it).  Inputs must be finite.
 //
 // Work split: one workgroup owns NW*32 consecutive query rows of one (sequence,
 // head); each wavefront owns 32 of them.  Keys arrive in tiles of 64: first the
@@ -40,9 +41,17 @@ typedef __attribute__((ext_vector_type(8))) float floatx8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 constexpr int kBN = 64;   // keys per tile
-constexpr int kDH = 128;  // head size
-constexpr int kRowBytes = kDH * 2;
-constexpr int kTileBytes = kBN * kRowBytes;  // 16 KiB per K or V tile
+// What follows from the head size DH (128 or 64)
+template <int DH>
+struct HeadDims {
+  static constexpr int kRowBytes = DH * 2;
+  static constexpr int kTileBytes = kBN * kRowBytes;  // 16 KiB (DH = 128) or 8 KiB (DH = 64) per K or V tile
+  static constexpr int kPieces = kRowBytes / 16;      // 16-byte pieces of a row
+  static constexpr int kPiecesLog2 = DH == 128 ? 4 : 3;
+  static constexpr int kChannelBlocks = DH / 32;      // 32-channel blocks of O^T = 64-byte granules of a V row
+  static constexpr int kSteps = DH / 8;               // MFMAs per tile of S^T = K Q^T (2 key blocks x DH/16), and of
+                                                      // O^T += V^T P^T (4 key steps x DH/32 channel blocks)
+};
 constexpr float kNegInf = -__builtin_inff();
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -56,23 +65,26 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));  // hardware round-to-nearest-even pack
 }
 
-// Per-lane part of the tile loads.  A 64 x 128 tile is 1024 pieces of 16 bytes; wavefront w of NW
-// fills LDS rows (64/NW)*w ..., 4 rows (1 KiB) per instruction.  The lane at LDS position
+// Per-lane part of the tile loads.  A 64 x DH tile is 64 * P pieces of 16 bytes (P = 16 or 8 per row); wavefront
+// w of NW fills LDS rows (64/NW)*w ..., 64/P rows (1 KiB) per instruction.  The lane at LDS position
 // (row, pos) fetches the piece that the swizzle stores there:
-//   K: piece = pos ^ (row & 15)                 (16-byte granules, for the 16-byte row reads)
-//   V: piece = ((pos/4) ^ (row & 3))*4 + pos%4  (64-byte granules, for the transposing reads)
-template <int NW>
+//   K: piece = pos ^ (row & (P-1))                      (16-byte granules, for the 16-byte row reads)
+//   V: piece = ((pos/4) ^ (row & (P/4-1)))*4 + pos%4    (64-byte granules, for the transposing reads)
+template <int NW, int DH>
 struct TileLoader {
-  static constexpr int kPerWave = 16 / NW;  // load instructions per wavefront per tile and tensor
+  static constexpr int kP = HeadDims<DH>::kPieces;
+  static constexpr int kRowsPerInstr = 64 / kP;
+  static constexpr int kGranMask = HeadDims<DH>::kChannelBlocks - 1;
+  static constexpr int kPerWave = (kBN / kRowsPerInstr) / NW;  // load instructions per wavefront per tile and tensor
   int row0;                // LDS row of this lane in the wavefront's first instruction
   uint32_t pos;            // 16-byte position inside the row
-  uint32_t v_piece_bytes;  // (row & 3) is the same for all of the wavefront's instructions
+  uint32_t v_piece_bytes;  // (row & kGranMask) is the same for all of the wavefront's instructions
   uint32_t lds_chunk0;     // byte offset of the wavefront's first 1 KiB chunk inside a tile
 
   __device__ __forceinline__ void init(int wave, int lane) {
-    row0 = wave * kPerWave * 4 + (lane >> 4);
-    pos = lane & 15;
-    v_piece_bytes = ((((pos >> 2) ^ (row0 & 3)) << 2) | (pos & 3)) * 16u;
+    row0 = wave * kPerWave * kRowsPerInstr + (lane >> HeadDims<DH>::kPiecesLog2);
+    pos = lane & (kP - 1);
+    v_piece_bytes = ((((pos >> 2) ^ (row0 & kGranMask)) << 2) | (pos & 3)) * 16u;
     lds_chunk0 = wave * kPerWave * 1024;
   }
   // Rows past the end of the region re-read its last row (finite data, masked later).
@@ -80,9 +92,9 @@ struct TileLoader {
                                         uint32_t lds_k, uint32_t lds_v) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const int row = row0 + 4 * u;
+      const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
-      const uint32_t k_piece_bytes = (pos ^ (row & 15)) * 16u;
+      const uint32_t k_piece_bytes = (pos ^ (row & (kP - 1))) * 16u;
       dma16_uniform(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
       dma16_uniform(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
@@ -91,7 +103,7 @@ struct TileLoader {
   __device__ __forceinline__ void issue_rows_v(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const uint32_t roff = static_cast<uint32_t>(min(row0 + 4 * u, cnt - 1)) * stride_bytes;
+      const uint32_t roff = static_cast<uint32_t>(min(row0 + kRowsPerInstr * u, cnt - 1)) * stride_bytes;
       dma16_uniform(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
@@ -99,9 +111,9 @@ struct TileLoader {
   __device__ __forceinline__ void issue_rows(const uint16_t* base, uint32_t stride_bytes, int cnt, uint32_t lds_dst) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const int row = row0 + 4 * u;
+      const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
-      dma16_uniform(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + (pos ^ (row & (kP - 1))) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
   // The same three with the rows taken through an index list: row r of the tile is token idx[r] of `base`
@@ -110,9 +122,9 @@ struct TileLoader {
                                             uint32_t lds_k, uint32_t lds_v, const int32_t* idx) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const int row = row0 + 4 * u;
+      const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
-      const uint32_t k_piece_bytes = (pos ^ (row & 15)) * 16u;
+      const uint32_t k_piece_bytes = (pos ^ (row & (kP - 1))) * 16u;
       dma16_uniform(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
       dma16_uniform(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
@@ -121,7 +133,7 @@ struct TileLoader {
                                                    const int32_t* idx) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const uint32_t roff = static_cast<uint32_t>(idx[min(row0 + 4 * u, cnt - 1)]) * stride_bytes;
+      const uint32_t roff = static_cast<uint32_t>(idx[min(row0 + kRowsPerInstr * u, cnt - 1)]) * stride_bytes;
       dma16_uniform(base, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
@@ -129,9 +141,9 @@ struct TileLoader {
                                                  const int32_t* idx) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const int row = row0 + 4 * u;
+      const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
-      dma16_uniform(base, roff + (pos ^ (row & 15)) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + (pos ^ (row & (kP - 1))) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
 };
@@ -139,9 +151,9 @@ struct TileLoader {
 // Online-softmax update of one 32-row block for one 64-key tile.  acc holds the raw
 // S^T accumulators (two 32-key blocks); accumulator v of block kb <-> key 32kb + 8(v/4) + 4g + v%4.
 // Returns P^T as MFMA B operands: pf[2kb + half] = accumulators 8*half .. 8*half+7 of block kb.
-template <bool MASK>
+template <bool MASK, int NCB>
 __device__ __forceinline__ void softmax_tile(floatx16 (&acc)[2], int limit, int g, float scale_log2e, float& m_run,
-                                             float& l_run, floatx16 (&acc_o)[kDH / 32], bf16x8 (&pf)[4]) {
+                                             float& l_run, floatx16 (&acc_o)[NCB], bf16x8 (&pf)[4]) {
   float tmax = kNegInf;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
@@ -176,7 +188,7 @@ __device__ __forceinline__ void softmax_tile(floatx16 (&acc)[2], int limit, int 
   const float alpha = exp2_hw(m_run - m_use);  // m_run = -inf -> 0
   l_run *= alpha;
 #pragma unroll
-  for (int cb = 0; cb < kDH / 32; ++cb)
+  for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc_o[cb][v] *= alpha;
   m_run = m_new;
@@ -226,12 +238,12 @@ __device__ __forceinline__ void softmax_fixed(floatx16 (&acc)[2], int limit, int
 
 // NW = 4: plain loop, two workgroups per CU.  NW = 8: two groups of four wavefronts in
 // alternating MFMA / softmax phases, one workgroup per CU.
-template <int NW>
+template <int NW, int DH>
 struct BlockCfg {
   static constexpr int kThreads = NW * kWave;
   static constexpr int kBM = NW * 32;              // query rows per workgroup
   static constexpr int kStages = NW == 4 ? 2 : 4;  // K/V tiles resident in LDS
-  static constexpr int kLdsBytes = kStages * 2 * kTileBytes;
+  static constexpr int kLdsBytes = kStages * 2 * HeadDims<DH>::kTileBytes;
   static constexpr int kMinBlocks = NW == 4 ? 2 : 1;
   // gather-free form: the sequence's index list sits in LDS after the stages (160 KiB per compute unit in all)
   static constexpr int kIdxCap = NW == 4 ? 4096 : 7680;  // (the 8-wavefront kernel has 1 KiB of static LDS besides)
@@ -240,7 +252,7 @@ struct BlockCfg {
 
 // One query block (kBM rows) of one (sequence, head); called by the whole workgroup.
 // IDX: Kn / Vn are the context's K / V and nugget j of sequence b is its token cu_ctx[b] + nug_idx[cu_nuggets[b] + j].
-template <int NW, bool IDX>
+template <int NW, bool IDX, int DH>
 __device__ __forceinline__ void attend_query_block(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
@@ -250,7 +262,12 @@ __device__ __forceinline__ void attend_query_block(
     int H, int H_kv, int bh, int qblk,
     int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse) {
-  using Cfg = BlockCfg<NW>;
+  using Cfg = BlockCfg<NW, DH>;
+  using HD = HeadDims<DH>;
+  constexpr int kDH = DH, kRowBytes = HD::kRowBytes, kTileBytes = HD::kTileBytes;
+  constexpr int kP = HD::kPieces;           // 16-byte pieces of a row
+  constexpr int kNCB = HD::kChannelBlocks;  // 32-channel blocks of the output
+  constexpr int kSteps = HD::kSteps;        // MFMAs of S^T per tile, and of O^T += V^T P^T
   constexpr int kBM = Cfg::kBM;
   constexpr int kStages = Cfg::kStages;
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // stage s: K at 2s, V at 2s+1 (tiles of 16 KiB)
@@ -296,7 +313,7 @@ __device__ __forceinline__ void attend_query_block(
   const uint16_t* locK = Kl + (static_cast<int64_t>(l0) * H_kv + kvh) * kDH;
   const uint16_t* locV = Vl + (static_cast<int64_t>(l0) * H_kv + kvh) * kDH;
 
-  TileLoader<NW> loader;
+  TileLoader<NW, DH> loader;
   loader.init(wave, lane);
   // Every call enqueues the same number of loads per lane (a tile past the end re-reads the last
   // one into a stage nobody reads), so the vmcnt arithmetic of the loops is uniform.
@@ -337,7 +354,7 @@ __device__ __forceinline__ void attend_query_block(
   // memory would touch 32 rows per instruction), into the stages that tiles 1.. (NW = 4) or 2..
   // (NW = 8) use later.  Q^T fragments: lane (j, g) holds Q[my_i][16*ds + 8*g .. +8) for ds = 0..7.
   // Rows past the end of the sequence re-read its last row; nothing of them is stored.
-  constexpr int kLoadsPerTile = TileLoader<NW>::kPerWave * 2;
+  constexpr int kLoadsPerTile = TileLoader<NW, DH>::kPerWave * 2;
   constexpr int kQSlot0 = NW == 8 ? 4 : 2;  // first 16 KiB slot of the query rows
   bf16x8 qf[kDH / 16];
   if (n_tiles > 0) {
@@ -359,7 +376,7 @@ __device__ __forceinline__ void attend_query_block(
     const char* qbuf = lds + kQSlot0 * kTileBytes + (wave * 32 + j) * kRowBytes;
 #pragma unroll
     for (int ds = 0; ds < kDH / 16; ++ds)
-      qf[ds] = *reinterpret_cast<const bf16x8*>(qbuf + (((2 * ds + g) ^ (j & 15)) << 4));
+      qf[ds] = *reinterpret_cast<const bf16x8*>(qbuf + (((2 * ds + g) ^ (j & (kP - 1))) << 4));
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragments are in registers
     if (NW == 8) {
       __syncthreads();  // everyone has its fragments: the stages are free again
@@ -379,8 +396,8 @@ __device__ __forceinline__ void attend_query_block(
   float m_run = kNegInf, l_run = 0.f;
 
   // per-lane constants of the LDS read patterns
-  const int k_row_off = j * kRowBytes;  // K: row 32kb + j, piece (2ds + g) ^ (row & 15); (32kb + j) & 15 == j & 15
-  const int k_sw = j & 15;
+  const int k_row_off = j * kRowBytes;  // K: row 32kb + j, piece (2ds + g) ^ (row & (P-1)); (32kb + j) & (P-1) == j & (P-1)
+  const int k_sw = j & (kP - 1);
   // V^T via transposing read: lane supplies row 16t + 8e + 4g + (lane%16)/4, 8 bytes at channel 32cb + 16*half + 4*(lane%4)
   const int v_r = 4 * g + ((lane & 15) >> 2);
   const int v_in = 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
@@ -402,9 +419,9 @@ __device__ __forceinline__ void attend_query_block(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {
+    for (int s = 0; s < kSteps; ++s) {
       const bf16x8 cur = kf[s % kAhead];
-      if (s + kAhead < 16) kf[s % kAhead] = read_k(tile, s + kAhead);
+      if (s + kAhead < kSteps) kf[s % kAhead] = read_k(tile, s + kAhead);
       acc_s[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[s >> 1], acc_s[s & 1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -422,12 +439,12 @@ __device__ __forceinline__ void attend_query_block(
       bf16x8, j == 0 ? make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u) : make_uint4(0, 0, 0, 0));
   auto read_vt = [&](int tile, int s) -> bf16x8 {
     const char* vbuf = lds + (2 * (tile % kStages) + 1) * kTileBytes + v_in;
-    const int t = s >> 2, cb = s & 3;
+    const int t = s / kNCB, cb = s % kNCB;
     shortx4 a[2];
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       const int r = 16 * t + 8 * e + v_r;
-      const char* p = vbuf + r * kRowBytes + ((cb ^ (r & 3)) << 6);
+      const char* p = vbuf + r * kRowBytes + ((cb ^ (r & (kNCB - 1))) << 6);
       a[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
     }
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a[0], a[1], 0, 1, 2, 3, 4, 5, 6, 7));
@@ -437,10 +454,10 @@ __device__ __forceinline__ void attend_query_block(
 #pragma unroll
     for (int s = 0; s < kAhead; ++s) vf[s] = read_vt(tile, s);
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {
+    for (int s = 0; s < kSteps; ++s) {
       const bf16x8 cur = vf[s % kAhead];
-      if (s + kAhead < 16) vf[s % kAhead] = read_vt(tile, s + kAhead);
-      acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
+      if (s + kAhead < kSteps) vf[s % kAhead] = read_vt(tile, s + kAhead);
+      acc_o[s % kNCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s / kNCB], acc_o[s % kNCB], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -454,9 +471,9 @@ __device__ __forceinline__ void attend_query_block(
   };
   auto softmax = [&](const TileInfo& ti, floatx16 (&acc_s)[2], bf16x8 (&pf)[4]) {
     if (ti.need_mask) {
-      softmax_tile<true>(acc_s, ti.limit, g, scale_log2e, m_run, l_run, acc_o, pf);
+      softmax_tile<true, kNCB>(acc_s, ti.limit, g, scale_log2e, m_run, l_run, acc_o, pf);
     } else {
-      softmax_tile<false>(acc_s, kBN, g, scale_log2e, m_run, l_run, acc_o, pf);
+      softmax_tile<false, kNCB>(acc_s, kBN, g, scale_log2e, m_run, l_run, acc_o, pf);
     }
   };
 
@@ -497,16 +514,16 @@ __device__ __forceinline__ void attend_query_block(
     auto pv_steps = [&](int t, auto k_prefetch_tag) {  // PV(t-1); requests the first K fragments of tile t
       constexpr bool K_PREFETCH = decltype(k_prefetch_tag)::value;
 #pragma unroll
-      for (int s = 0; s < 16; ++s) {
+      for (int s = 0; s < kSteps; ++s) {
         const bf16x8 cur = ring[s % kAhead];
-        if (s + kAhead < 16) {
+        if (s + kAhead < kSteps) {
           ring[s % kAhead] = read_vt(t - 1, s + kAhead);
         } else if (K_PREFETCH) {
-          ring[s % kAhead] = read_k(t, s + kAhead - 16);
+          ring[s % kAhead] = read_k(t, s + kAhead - kSteps);
         }
-        acc_o[s & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s >> 2], acc_o[s & 3], 0, 0, 0);
-        if (kOnesBlock && (s & 3) == 3)
-          acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s >> 2], acc_l, 0, 0, 0);
+        acc_o[s % kNCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pf[s / kNCB], acc_o[s % kNCB], 0, 0, 0);
+        if (kOnesBlock && (s % kNCB) == kNCB - 1)
+          acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, pf[s / kNCB], acc_l, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
     };
@@ -516,9 +533,9 @@ __device__ __forceinline__ void attend_query_block(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_s[kb][v] = 0.f;
 #pragma unroll
-      for (int s = 0; s < 16; ++s) {
-        const bf16x8 cur = ring[(16 + s) % kAhead];
-        if (s + kAhead < 16) ring[(16 + s) % kAhead] = read_k(t, s + kAhead);
+      for (int s = 0; s < kSteps; ++s) {
+        const bf16x8 cur = ring[(kSteps + s) % kAhead];
+        if (s + kAhead < kSteps) ring[(kSteps + s) % kAhead] = read_k(t, s + kAhead);
         acc_s[s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qf[s >> 1], acc_s[s & 1], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -532,7 +549,7 @@ __device__ __forceinline__ void attend_query_block(
     // softmax: a request can take hundreds of cycles to issue when the memory pipeline is backed
     // up.  The wavefronts of group 1 bring K of tile t+2 (during phase 2t), those of group 0 its V
     // (during phase 2t+1), four requests per wavefront as in the prologue's split.
-    TileLoader<4> half_loader;
+    TileLoader<4, DH> half_loader;
     half_loader.init(wave & 3, lane);
     auto issue_half = [&](int tile, auto v_tag) {
       constexpr bool IS_V = decltype(v_tag)::value;
@@ -582,7 +599,7 @@ __device__ __forceinline__ void attend_query_block(
         __builtin_amdgcn_s_setprio(1);
         if (KIND == 0) {
 #pragma unroll
-          for (int s = 0; s < kAhead; ++s) ring[(16 + s) % kAhead] = read_k(t, s);
+          for (int s = 0; s < kAhead; ++s) ring[(kSteps + s) % kAhead] = read_k(t, s);
           s_steps(t);
         } else if (KIND == 1) {
           pv_steps(t, std::true_type{});
@@ -666,15 +683,15 @@ __device__ __forceinline__ void attend_query_block(
         uint2 out;
         out.x = pack2_bf16(acc_o[cb][4 * vq + 0] * inv, acc_o[cb][4 * vq + 1] * inv);
         out.y = pack2_bf16(acc_o[cb][4 * vq + 2] * inv, acc_o[cb][4 * vq + 3] * inv);
-        *reinterpret_cast<uint2*>(obuf + j * kRowBytes + ((piece ^ (j & 15)) << 4) + 8 * g) = out;
+        *reinterpret_cast<uint2*>(obuf + j * kRowBytes + ((piece ^ (j & (kP - 1))) << 4) + 8 * g) = out;
       }
     __builtin_amdgcn_wave_barrier();
     const int n_rows = min(32, q_b - w_i0);  // valid rows of this wavefront (may be <= 0)
     uint16_t* obase = O + (static_cast<int64_t>(q0 + w_i0) * H + h) * kDH;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = 4 * it + (lane >> 4), piece = lane & 15;
-      const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * kRowBytes + ((piece ^ (row & 15)) << 4));
+    for (int it = 0; it < kP / 2; ++it) {  // 64 / kP rows per iteration, 16 bytes per lane
+      const int row = (64 / kP) * it + (lane >> HD::kPiecesLog2), piece = lane & (kP - 1);
+      const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * kRowBytes + ((piece ^ (row & (kP - 1))) << 4));
       if (row < n_rows) *reinterpret_cast<uint4*>(obase + static_cast<int64_t>(row) * H * kDH + piece * 8) = val;
     }
   }
@@ -690,8 +707,8 @@ __device__ __forceinline__ void attend_query_block(
 // after the other: a block i from the end and a block i from the start, so that under the causal
 // mask all workgroups carry the same load (new workgroups are handed out in order, and a compute
 // unit that finishes early is not refilled before the ones ahead of it in that order).
-template <int NW, bool IDX>
-__global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) void block_attention_kernel(
+template <int NW, bool IDX, int DH>
+__global__ __launch_bounds__((BlockCfg<NW, DH>::kThreads), (BlockCfg<NW, DH>::kMinBlocks)) void block_attention_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
@@ -728,18 +745,18 @@ __global__ __launch_bounds__(BlockCfg<NW>::kThreads, BlockCfg<NW>::kMinBlocks) v
     bh1 = B * H - 1 - bh1;
     bh2 = B * H - 1 - bh2;
   }
-  attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh1, q1,
+  attend_query_block<NW, IDX, DH>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh1, q1,
                               nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
   if (q2 >= 0) {
     __syncthreads();  // the first block's use of LDS is over
-    attend_query_block<NW, IDX>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh2,
+    attend_query_block<NW, IDX, DH>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh2,
                                 q2, nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
   }
 }
 
-template <int NW, bool IDX>
+template <int NW, bool IDX, int DH>
 int launch_nw(const AttnParams& p) {
-  using Cfg = BlockCfg<NW>;
+  using Cfg = BlockCfg<NW, DH>;
   if (IDX && p.max_k > Cfg::kIdxCap) return DODO_ERR_UNSUPPORTED;
   constexpr int kLds = Cfg::kLdsBytes + (IDX ? Cfg::kIdxBytes : 0);
   const int n_qblocks = (p.max_q + Cfg::kBM - 1) / Cfg::kBM;
@@ -748,7 +765,7 @@ int launch_nw(const AttnParams& p) {
   const int pair = (n_qblocks >= 2 && bh8 * ((n_qblocks + 1) / 2) >= compute_units()) ? 1 : 0;
   const int64_t grid = bh8 * (pair ? (n_qblocks + 1) / 2 : n_qblocks);
   if (grid > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
-  auto kern = block_attention_kernel<NW, IDX>;
+  auto kern = block_attention_kernel<NW, IDX, DH>;
   if (kLds > 64 * 1024) {
     const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(kern), kLds);
     if (rc != DODO_OK) return rc;
@@ -762,21 +779,28 @@ int launch_nw(const AttnParams& p) {
   return launch_status();
 }
 
-}  // namespace
-
-int launch_block_attention(const AttnParams& p) {
-  if (p.dtype != DODO_DTYPE_BF16 || p.d_h != kDH) return DODO_ERR_UNSUPPORTED;
+template <int DH>
+int launch_dh(const AttnParams& p) {
   // the K/V row offsets inside one tile are kept in 32 bits
-  if (p.nug_tok_stride * 2 * kBN > 0x7fffffffLL || static_cast<int64_t>(p.H_kv) * kDH * 2 * kBN > 0x7fffffffLL ||
-      static_cast<int64_t>(p.H) * kDH * 2 * kBN > 0x7fffffffLL)
+  if (p.nug_tok_stride * 2 * kBN > 0x7fffffffLL || static_cast<int64_t>(p.H_kv) * DH * 2 * kBN > 0x7fffffffLL ||
+      static_cast<int64_t>(p.H) * DH * 2 * kBN > 0x7fffffffLL)
     return DODO_ERR_UNSUPPORTED;
   if (p.nug_idx != nullptr) {
     // a token's byte offset from its sequence's first row is kept in 32 bits as well
     if (static_cast<int64_t>(p.max_n) * p.nug_tok_stride * 2 > 0x7fffffffLL) return DODO_ERR_UNSUPPORTED;
-    return p.max_q > 128 ? launch_nw<8, true>(p) : launch_nw<4, true>(p);
+    return p.max_q > 128 ? launch_nw<8, true, DH>(p) : launch_nw<4, true, DH>(p);
   }
-  if (p.max_q > 128) return launch_nw<8, false>(p);
-  return launch_nw<4, false>(p);
+  if (p.max_q > 128) return launch_nw<8, false, DH>(p);
+  return launch_nw<4, false, DH>(p);
+}
+
+}  // namespace
+
+int launch_block_attention(const AttnParams& p) {
+  if (p.dtype != DODO_DTYPE_BF16) return DODO_ERR_UNSUPPORTED;
+  if (p.d_h == 128) return launch_dh<128>(p);
+  if (p.d_h == 64) return launch_dh<64>(p);
+  return DODO_ERR_UNSUPPORTED;
 }
 
 }  // namespace dodo

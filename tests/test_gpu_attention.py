@@ -108,6 +108,7 @@ def test_rows_that_see_nothing(D):
 ])
 def test_block_attention_bf16(D, q_lens, k_lens, m_lens, H, H_kv):
     _full_check(D, 410, q_lens, k_lens, m_lens, H, H_kv, 128, torch.bfloat16)
+    _full_check(D, 417, q_lens, k_lens, m_lens, H, H_kv, 64, torch.bfloat16)  # the same kernels with 64-wide heads
 
 
 def test_block_attention_scale_argument_and_head_major_cache(D):
@@ -143,6 +144,25 @@ def test_block_kernel_row_equals_decode_kernel_row(D):
         assert torch.max(torch.abs(O_dec[0].float() - O_blk[i].float())) <= 2e-2
 
 
+def test_block_attention_64_wide_heads_head_major_and_paired_launch(D):
+    # head-major cache with 64-wide heads, and a launch with two query blocks per workgroup (>= 256 (sequence, head)
+    # pairs of more than 256 rows), whole tensor against the oracle
+    q_lens, k_lens, m_lens = [130, 64], [90, 31], [200, 64]
+    host, devt = make_attention_case(424, q_lens, k_lens, m_lens, 4, 2, 64, torch.bfloat16, dev())
+    O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
+                                      host["cu_nuggets"], host["cu_local"], 0.11)
+    O, lse = _run(D, devt, q_lens, k_lens, m_lens, 0.11)
+    check_attention(O, O_ref, torch.bfloat16)
+    check_lse(lse, lse_ref, torch.bfloat16)
+    hm = dict(devt)
+    hm["Kn"], hm["Vn"] = devt["Kn"].permute(1, 0, 2).contiguous(), devt["Vn"].permute(1, 0, 2).contiguous()
+    O2, _ = _run(D, hm, q_lens, k_lens, m_lens, 0.11, layout=1)
+    assert torch.equal(O, O2)
+    q_lens = [512, 300, 257, 400, 511, 384, 290, 512, 450, 333, 260]
+    _full_check(D, 425, q_lens, [40, 0, 13, 64, 1, 65, 30, 70, 7, 50, 33], [q + t for q, t in zip(q_lens, [0, 5, 64, 0, 3, 0, 16, 1, 63, 20, 9])],
+                24, 8, 64, torch.bfloat16)
+
+
 def test_attention_is_deterministic(D):
     q_lens, k_lens, m_lens = [256], [410], [384]
     _, devt = make_attention_case(413, q_lens, k_lens, m_lens, 8, 8, 128, torch.bfloat16, dev())
@@ -166,3 +186,6 @@ def test_block_attention_exact_fallback_paths(D, scale):
     _full_check(D, 415, [300, 130], [200, 64], [364, 130], 2, 2, 128, torch.bfloat16, scale=scale)
     # 4-wavefront kernel (short query block) with the same scales
     _full_check(D, 416, [100], [70], [120], 2, 1, 128, torch.bfloat16, scale=scale)
+    # 64-wide heads, both kernels
+    _full_check(D, 418, [300, 130], [200, 64], [364, 130], 2, 2, 64, torch.bfloat16, scale=scale)
+    _full_check(D, 419, [100], [70], [120], 2, 1, 64, torch.bfloat16, scale=scale)

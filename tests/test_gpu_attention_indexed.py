@@ -73,6 +73,7 @@ def test_decode_split_k_and_padded_token_stride(D):
 ])
 def test_block_kernel_bf16(D, n_lens, k_lens, q_lens, m_lens, H, H_kv):
     _check(D, 502, n_lens, k_lens, q_lens, m_lens, H, H_kv, 128, torch.bfloat16)
+    _check(D, 505, n_lens, k_lens, q_lens, m_lens, H, H_kv, 64, torch.bfloat16)
 
 
 def test_block_kernel_padded_token_stride_and_long_index_list(D):

@@ -21,9 +21,9 @@ def test_attention_random_shapes(D):
     rng = np.random.default_rng(11)
     for it in range(40):
         B = int(rng.integers(1, 5))
-        block = rng.random() < 0.6  # query-block kernel (bf16, d_h = 128, >= 16 rows) or split-K kernel
+        block = rng.random() < 0.6  # query-block kernel (bf16, >= 16 rows) or split-K kernel
         dtype = torch.bfloat16 if block or rng.random() < 0.5 else torch.float32
-        d_h = 128 if block else int(rng.choice([64, 128]))
+        d_h = int(rng.choice([64, 128]))
         H_kv = int(rng.choice([1, 2, 4]))
         H = H_kv * int(rng.choice([1, 2]))
         qmax = int(rng.choice([16, 64, 130, 300, 520])) if block else int(rng.choice([1, 3, 9]))
