@@ -2,10 +2,11 @@
 // single-token decode and small query counts: every visible K and V row is
 // read once with 16-byte loads, a group of lanes per row.
 //
-// One workgroup handles one (query row, head, split) -- or, under grouped-query attention, GH query heads
-// that share a KV head: its lane groups are then split between those heads, every K/V row is requested by
-// the GH heads' groups in the same instructions, and the compute unit's L1 turns that into one read of the
-// row, so the row comes from HBM once per KV head rather than once per query head.  Its 256 threads form
+// One workgroup handles one (query row, head, split) -- or several query vectors that read the same K/V rows:
+// the GH query heads of one KV head (grouped-query attention) and / or QR consecutive query rows of a small
+// query block.  Its lane groups are then split between those query vectors, every K/V row is requested by
+// their groups in the same instructions, and the compute unit's L1 turns that into one read of the row, so
+// the row comes from HBM once per KV head and row group rather than once per query vector.  Its 256 threads form
 // G = 256 / lanes-per-row groups; with one head, group g walks rows g, g+G, ... of the split,
 // keeping an independent online-softmax state (running max, sum, d_h partial
 // outputs spread over its lanes) in base 2.  Groups are merged through LDS in
@@ -53,7 +54,8 @@ constexpr int kMaxPolls = 1 << 17;               // bound of the combiner's wait
 
 // INDEXED: Kn / Vn are the context's K / V ([N, H_kv, DH], nug_tok_stride between tokens) and nugget j of
 // sequence b is token cu_ctx[b] + nug_idx[cu_nuggets[b] + j] of it (no packed cache has been made).
-// GROUPED: the workgroup serves GH > 1 query heads of one KV head (else GH is 1 and everything about it folds away).
+// GROUPED: the workgroup serves GH query heads of one KV head times QR query rows, more than one query vector in all
+// (else both are 1 and everything about them folds away).
 template <int DTYPE, int DH, int kThreads, bool INDEXED, bool GROUPED>
 __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const void* __restrict__ Q, const void* __restrict__ Kn, const void* __restrict__ Vn,
@@ -61,9 +63,12 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
     const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
     const int32_t* __restrict__ cu_ctx,
-    int H, int H_kv, int GH_arg, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e,
-    void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws, uint32_t* __restrict__ flags) {
-  const int GH = GROUPED ? GH_arg : 1;
+    int H, int H_kv, int GH_arg, int QR_arg, int max_q, int nsplit, int64_t nug_tok_stride, int64_t nug_head_stride,
+    float scale_log2e, void* __restrict__ O, float* __restrict__ lse, float* __restrict__ ws,
+    uint32_t* __restrict__ flags) {
+  const int GH = GROUPED ? GH_arg : 1;  // query heads per workgroup
+  const int QR = GROUPED ? QR_arg : 1;  // query rows per workgroup
+  const int GV = GH * QR;               // query vectors per workgroup
   using VT = Vec16<DTYPE>;
   constexpr int kEPL = VT::kElems;          // elements per lane
   constexpr int kLPR = DH / kEPL;           // lanes per K/V row
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   const int HG = H / GH;
   int head0 = t % HG;
   t /= HG;
-  if (GH == 1) {
+  if (GV == 1) {
     const int G = H / H_kv;
     if (G > 1 && (H_kv & 7) == 0) {
       head0 = ((head0 / (8 * G)) * 8 + (head0 & 7)) * G + (head0 >> 3) % G;  // KV head from the position mod 8, then the head in its group
@@ -97,26 +102,33 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   } else {
     head0 *= GH;
   }
-  const int i = t % max_q;
-  const int b = t / max_q;
+  const int IG = (max_q + QR - 1) / QR;  // row groups per sequence
+  const int i0 = (t % IG) * QR;          // first query row of this workgroup
+  const int b = t / IG;
   const int q0 = cu_q[b];
   const int q_b = cu_q[b + 1] - q0;
-  if (i >= q_b) return;  // uniform over the workgroup
+  if (i0 >= q_b) return;  // uniform over the workgroup
   const int k0 = cu_nuggets[b], k_b = nug_len != nullptr ? nug_len[b] : cu_nuggets[b + 1] - k0;
   const int l0 = cu_local[b], m_b = loc_len != nullptr ? loc_len[b] : cu_local[b + 1] - l0;
-  const int n_local = max(0, min(m_b, m_b - q_b + i + 1));  // causal rule, bottom-right aligned
-  const int n_vis = k_b + n_local;
-  const int chunk = (n_vis + nsplit - 1) / nsplit;
-  const int r0 = split * chunk;
-  const int r1 = min(r0 + chunk, n_vis);
   const int g = threadIdx.x / kLPR;
   const int sub = threadIdx.x % kLPR;
-  const int gh = g % GH;      // this lane group's head among the workgroup's
-  const int rs = g / GH;      // ... and its row stream: rows rs, rs + R, ... of the split
-  const int R = kGroups / GH;
-  const int h = head0 + gh;
+  const int qv = g % GV;      // this lane group's query vector among the workgroup's: (row, head) = (qv / GH, qv % GH)
+  const int rs = g / GV;      // ... and its row stream: K/V rows rs, rs + R, ... of the split
+  const int R = kGroups / GV;
+  const int i = i0 + qv / GH;
+  const bool row_ok = i < q_b;  // (a row group may reach past the sequence's last query row)
+  const int h = head0 + qv % GH;
   const int kvh = h / (H / H_kv);  // the same for all heads of the workgroup
-  const int64_t row_id = static_cast<int64_t>(q0 + i) * H + h;
+  // causal rule, bottom-right aligned: row i sees the nuggets and local rows j <= m_b - q_b + i.  The split is cut
+  // from what the workgroup's last row sees (the most); every lane group stops at what its own row sees.
+  const int i_last = min(i0 + QR, q_b) - 1;
+  const int n_vis_wg = k_b + max(0, min(m_b, m_b - q_b + i_last + 1));
+  const int n_vis = row_ok ? k_b + max(0, min(m_b, m_b - q_b + i + 1)) : 0;
+  const int chunk = (n_vis_wg + nsplit - 1) / nsplit;
+  const int r0 = split * chunk;
+  const int r1_wg = min(r0 + chunk, n_vis_wg);  // rows [r0, r1_wg) are loaded by the workgroup ...
+  const int r1 = min(r0 + chunk, n_vis);        // ... of which this lane group's query vector sees [r0, r1)
+  const int64_t row_id = static_cast<int64_t>(q0 + min(i, q_b - 1)) * H + h;
 
   float q[kEPL];
   {
@@ -147,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
 #pragma unroll
       for (int u = 0; u < kRowsInFlight; ++u) {
         const int jr = j0 + u * R + rs;
-        const int j = jr < r1 ? jr : r1 - 1;
+        const int j = jr < r1_wg ? jr : r1_wg - 1;
         tok[u] = j < k_b ? nug_idx[k0 + j] : 0;
       }
     }
@@ -156,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
       // loads are unconditional (rows past the end re-read the last row of the range and are
       // discarded): a branch around them would serialise the loads behind a full wait
       const int jr = j0 + u * R + rs;
-      const int j = jr < r1 ? jr : r1 - 1;
+      const int j = jr < r1_wg ? jr : r1_wg - 1;
       const bool nug = j < k_b;
       const int64_t nug_row = INDEXED ? ctx0 + tok[u] : static_cast<int64_t>(k0 + j);
       const int64_t off = nug ? (nug_row * nug_tok_stride + nug_base) * kEs
@@ -200,14 +212,14 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   {
     const int kStep = R * kRowsInFlight;
     Batch ba, bb;
-    int j0 = r0;  // (uniform over the workgroup, like r1)
-    if (j0 < r1) load_batch(ba, j0);
-    while (j0 < r1) {
-      if (j0 + kStep < r1) load_batch(bb, j0 + kStep);
+    int j0 = r0;  // (uniform over the workgroup, like r1_wg)
+    if (j0 < r1_wg) load_batch(ba, j0);
+    while (j0 < r1_wg) {
+      if (j0 + kStep < r1_wg) load_batch(bb, j0 + kStep);
       use_batch(ba);
       j0 += kStep;
-      if (j0 >= r1) break;
-      if (j0 + kStep < r1) load_batch(ba, j0 + kStep);
+      if (j0 >= r1_wg) break;
+      if (j0 + kStep < r1_wg) load_batch(ba, j0 + kStep);
       use_batch(bb);
       j0 += kStep;
     }
@@ -222,16 +234,18 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   for (int e = 0; e < kEPL; ++e) part_o[g][sub * kEPL + e] = o[e];
   __syncthreads();
   __shared__ int all_there;
-  for (int hh = 0; hh < GH; ++hh) {  // one head of the workgroup after the other (uniform over the workgroup)
-    const int64_t out_row = static_cast<int64_t>(q0 + i) * H + head0 + hh;
+  for (int hh = 0; hh < GV; ++hh) {  // one query vector of the workgroup after the other (uniform over the workgroup)
+    const int i_out = i0 + hh / GH, h_out = head0 + hh % GH;
+    if (i_out >= q_b) continue;
+    const int64_t out_row = static_cast<int64_t>(q0 + i_out) * H + h_out;
     float Mg = kNegInf, Sg = 0.f, og = 0.f;  // this workgroup's merged partial of the head (threads < DH: channel threadIdx.x)
     if (threadIdx.x < DH) {
       const int c = threadIdx.x;
       float M = kNegInf;
-      for (int gg = hh; gg < kGroups; gg += GH) M = fmaxf(M, part_m[gg]);
+      for (int gg = hh; gg < kGroups; gg += GV) M = fmaxf(M, part_m[gg]);
       float S = 0.f, oc = 0.f;
       if (M != kNegInf) {
-        for (int gg = hh; gg < kGroups; gg += GH) {
+        for (int gg = hh; gg < kGroups; gg += GV) {
           const float wgt = exp2_guard(part_m[gg] - M);
           S = fmaf(part_s[gg], wgt, S);
           oc = fmaf(part_o[gg][c], wgt, oc);
@@ -253,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
     if (nsplit == 1) continue;
 
     // ---- several splits: the last one combines, in split order ----
-    const int64_t slot0 = ((static_cast<int64_t>(b) * max_q + i) * H + head0 + hh) * nsplit;
+    const int64_t slot0 = ((static_cast<int64_t>(b) * max_q + i_out) * H + h_out) * nsplit;
     if (split + 1 < nsplit) {
       // Records and flags are written and read with device-scope atomic accesses (plain stores and
       // loads that go to the level where all XCDs agree), so no cache has to be written back or
@@ -336,20 +350,28 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   }
 }
 
-// Query heads of one KV head that a workgroup serves together (a power of two that divides H / H_kv and the lane
-// groups of the smallest workgroup), as long as that still leaves two workgroups per compute unit.
-int heads_per_workgroup(const AttnParams& p, int nsplit) {
+// Query vectors that a workgroup serves together because they read the same K/V rows: gh query heads of one KV
+// head times qr consecutive query rows (powers of two, at most 8 vectors: the lane groups of the smallest
+// workgroup), as long as that still leaves two workgroups per compute unit.
+void vectors_per_workgroup(const AttnParams& p, int nsplit, int* gh_out, int* qr_out) {
   const int G = p.H / p.H_kv;
-  int gh = 1;
+  int gh = 1, qr = 1;
   while (gh < 8 && G % (2 * gh) == 0) gh *= 2;
-  while (gh > 1 && static_cast<int64_t>(p.B) * p.max_q * (p.H / gh) * nsplit < 2 * compute_units()) gh /= 2;
-  return gh;
+  while (gh * qr < 8 && qr < p.max_q) qr *= 2;
+  auto workgroups = [&](int gh_, int qr_) {
+    return static_cast<int64_t>(p.B) * ((p.max_q + qr_ - 1) / qr_) * (p.H / gh_) * nsplit;
+  };
+  while (qr > 1 && workgroups(gh, qr) < 2 * compute_units()) qr /= 2;
+  while (gh > 1 && workgroups(gh, qr) < 2 * compute_units()) gh /= 2;
+  *gh_out = gh;
+  *qr_out = qr;
 }
 
 template <int DTYPE, int DH, bool INDEXED>
 int launch_t(const AttnParams& p, int nsplit) {
-  const int gh = heads_per_workgroup(p, nsplit);
-  const int64_t rows = static_cast<int64_t>(p.B) * p.max_q * (p.H / gh);  // workgroups per split
+  int gh = 1, qr = 1;
+  vectors_per_workgroup(p, nsplit, &gh, &qr);
+  const int64_t rows = static_cast<int64_t>(p.B) * ((p.max_q + qr - 1) / qr) * (p.H / gh);  // workgroups per split
   // one flag word per record (one record per query row, head and split): right behind the records, unless the
   // caller keeps them elsewhere
   uint32_t* flags = p.ws_flags != nullptr
@@ -363,12 +385,12 @@ int launch_t(const AttnParams& p, int nsplit) {
 #define DODO_LAUNCH_SPLITK(THREADS, GROUPED)                                                                               \
   hipLaunchKernelGGL((splitk_attention_kernel<DTYPE, DH, THREADS, INDEXED, GROUPED>), grid, dim3(THREADS), 0, p.stream, p.Q,  \
                      p.Kn, p.Vn, p.Kl, p.Vl, p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.nug_idx, p.cu_ctx, p.H, \
-                     p.H_kv, gh, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,             \
+                     p.H_kv, gh, qr, p.max_q, nsplit, p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, p.O, p.lse,         \
                      static_cast<float*>(p.ws), flags)
   if (wide) {
-    if (gh > 1) DODO_LAUNCH_SPLITK(1024, true); else DODO_LAUNCH_SPLITK(1024, false);
+    if (gh * qr > 1) DODO_LAUNCH_SPLITK(1024, true); else DODO_LAUNCH_SPLITK(1024, false);
   } else {
-    if (gh > 1) DODO_LAUNCH_SPLITK(256, true); else DODO_LAUNCH_SPLITK(256, false);
+    if (gh * qr > 1) DODO_LAUNCH_SPLITK(256, true); else DODO_LAUNCH_SPLITK(256, false);
   }
 #undef DODO_LAUNCH_SPLITK
   return launch_status();

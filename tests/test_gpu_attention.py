@@ -60,6 +60,20 @@ def test_grouped_heads_served_by_one_workgroup(D):
     _full_check(D, 423, [1] * 80, [40] * 80, [9] * 80, 16, 4, 64, torch.bfloat16)
 
 
+def test_query_rows_served_by_one_workgroup(D):
+    # small query blocks with enough (sequence, row group, head) triples that a workgroup serves 8 (or 4 x 2 heads)
+    # query rows together: every row stops at its own causal limit, row groups reach past ragged ends
+    rng = np.random.default_rng(5)
+    q_lens = [int(v) for v in rng.integers(1, 16, 40)]
+    k_lens = [int(v) for v in rng.integers(0, 120, 40)]
+    m_lens = [int(v) for v in rng.integers(0, 40, 40)]
+    _full_check(D, 426, q_lens, k_lens, m_lens, 32, 32, 128, torch.bfloat16)
+    _full_check(D, 427, q_lens, k_lens, m_lens, 16, 8, 64, torch.bfloat16)
+    # fp32 query blocks of any length take this kernel: 33 rows = 4 full row groups and one row
+    _full_check(D, 428, [33, 32, 7, 1] * 6, [52, 0, 9, 100] * 6, [48, 32, 3, 5] * 6, 8, 8, 64, torch.float32)
+    _full_check(D, 429, [33, 32, 7, 1] * 8, [52, 0, 9, 100] * 8, [40, 40, 3, 5] * 8, 8, 2, 128, torch.float32)
+
+
 def test_decode_split_k_paths(D):
     # few (sequence, head) pairs and many rows: the split count goes above 1 and the last split combines
     assert D.dodo_nugget_attention_workspace_bytes(2, 2, 128, 1, 3277, 1089, D.BF16) > 0
