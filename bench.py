@@ -429,6 +429,7 @@ def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec
     # threshold rule of the autoregressive mode (Sec. 2.4)
     cap = max_k + 64
     lam = D.dodo_threshold_from_sample(g["scores"], wl.keep_num, wl.keep_den)
+    thr_ws = torch.empty(max(D.dodo_threshold_from_sample_workspace_bytes(wl.N), 16), dtype=torch.uint8, device=dev)
     Kc = torch.zeros((B, cap, wl.H_kv, wl.d_h), dtype=wl.dtype, device=dev)
     Vc = torch.zeros_like(Kc)
     Kc[:, :max_k] = g["Kn"].view(B, -1, wl.H_kv, wl.d_h)
@@ -439,7 +440,7 @@ def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec
     ws_c = torch.zeros(max(D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, cap, max(dec_local), D.BF16), 16),
                        dtype=torch.uint8, device=dev)
     ar = {
-        "threshold_from_sample": t(lambda: D.dodo_threshold_from_sample(g["scores"], wl.keep_num, wl.keep_den, out=lam)),
+        "threshold_from_sample": t(lambda: D.dodo_threshold_from_sample(g["scores"], wl.keep_num, wl.keep_den, out=lam, ws=thr_ws)),
         "select_threshold": t(lambda: D.dodo_select_threshold(g["scores"], g["cu_seqlens"], lam)),
         "stream_append": t(lambda: (counts.fill_(max_k), D.dodo_stream_append(leave_s, lam, leave_K, leave_V, counts, Kc, Vc))),
         "attn_decode_cached": t(lambda: D.dodo_nugget_attention_cached(

@@ -342,9 +342,13 @@ int dodo_ste_score_grad(const void* Q, const void* Kn, const void* Vn, const voi
  * of the n sampled scores (device, fp32), so that exactly k of them exceed it when there are no
  * ties; NaN ranks lowest, -0 counts as +0.  If k >= n, or that score is NaN, the threshold is
  * -inf (keep everything).  Integer comparisons on the score bits only: bit-exact.  n >= 1.
+ * ws is optional (dodo_threshold_from_sample_workspace_bytes(n) bytes, contents irrelevant; 0 for small samples):
+ * with it a large sample is histogrammed by many workgroups, one launch per radix pass; without it (NULL or too
+ * small) one workgroup does the same work, more slowly.  The result does not depend on it.
  */
-int dodo_threshold_from_sample(const float* sample, int64_t n, int64_t num, int64_t den, float* lambda_out,
-                               void* stream);
+size_t dodo_threshold_from_sample_workspace_bytes(int64_t n);
+int dodo_threshold_from_sample(const float* sample, int64_t n, int64_t num, int64_t den, float* lambda_out, void* ws,
+                               size_t ws_bytes, void* stream);
 
 /*
  * Threshold selection (Eq. 8): token i of a sequence is kept iff scores[i] > *lambda (device fp32;

@@ -12,6 +12,6 @@ from .binding import (  # noqa: F401
     dodo_nugget_attention_cached, dodo_nugget_attention_indexed, dodo_nugget_attention_noalloc, dodo_nugget_attention_segments, dodo_segment_plan,
     dodo_ste_score_grad, dodo_ste_score_grad_workspace_bytes,
     dodo_score, dodo_score_layers, dodo_score_mlp, dodo_score_mlp_workspace_bytes, dodo_select_threshold, dodo_select_topk,
-    dodo_select_topk_workspace_bytes, dodo_status_string, dodo_stream_append, dodo_threshold_from_sample, dodo_version,
+    dodo_select_topk_workspace_bytes, dodo_status_string, dodo_stream_append, dodo_threshold_from_sample, dodo_threshold_from_sample_workspace_bytes, dodo_version,
     cu_nuggets_from_lengths, lib,
 )

@@ -86,7 +86,9 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.dodo_nugget_attention_cached.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                                i64, f32, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
     L.dodo_threshold_from_sample.restype = ctypes.c_int
-    L.dodo_threshold_from_sample.argtypes = [vp, i64, i64, i64, vp, vp]
+    L.dodo_threshold_from_sample.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
+    L.dodo_threshold_from_sample_workspace_bytes.restype = sz
+    L.dodo_threshold_from_sample_workspace_bytes.argtypes = [i64]
     L.dodo_select_threshold.restype = ctypes.c_int
     L.dodo_select_threshold.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
     L.dodo_stream_append.restype = ctypes.c_int
@@ -442,15 +444,22 @@ def dodo_nugget_attention_cached(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Te
     return O, lse
 
 
-def dodo_threshold_from_sample(sample: torch.Tensor, num: int, den: int,
-                               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+def dodo_threshold_from_sample_workspace_bytes(n: int) -> int:
+    return int(lib.dodo_threshold_from_sample_workspace_bytes(n))
+
+
+def dodo_threshold_from_sample(sample: torch.Tensor, num: int, den: int, out: Optional[torch.Tensor] = None,
+                               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Threshold Lambda (device tensor with one fp32) from sampled scores: the (k+1)-th highest, k = nugget count."""
-    _dev(sample, out)
+    _dev(sample, out, ws)
     assert sample.dtype == torch.float32 and sample.is_contiguous()
     if out is None:
         out = torch.empty(1, dtype=torch.float32, device=sample.device)
-    _check(lib.dodo_threshold_from_sample(_ptr(sample), sample.numel(), num, den, _ptr(out), _stream()),
-           "dodo_threshold_from_sample")
+    need = dodo_threshold_from_sample_workspace_bytes(sample.numel())
+    if need and ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=sample.device)
+    _check(lib.dodo_threshold_from_sample(_ptr(sample), sample.numel(), num, den, _ptr(out), _ptr(ws),
+                                          0 if ws is None else ws.numel(), _stream()), "dodo_threshold_from_sample")
     return out
 
 

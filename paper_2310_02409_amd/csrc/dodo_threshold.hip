@@ -27,7 +27,8 @@ __device__ __forceinline__ float key_to_score(uint32_t key) {
 }
 
 // Key of the `rank`-th highest of n scores (1 <= rank <= n) by a 4-pass, 8-bit MSB radix select;
-// one workgroup, the scores are re-read from global memory in every pass (they sit in L2).
+// one workgroup, the scores are re-read from global memory in every pass (they sit in L2).  For small samples,
+// and for callers without a workspace; larger ones take the multi-workgroup form below.
 __global__ __launch_bounds__(kSampleThreads) void kth_highest_kernel(const float* __restrict__ sample, int64_t n,
                                                                      int64_t rank, float* __restrict__ lambda_out) {
   __shared__ uint32_t hist[256];
@@ -88,6 +89,133 @@ __global__ __launch_bounds__(kSampleThreads) void kth_highest_kernel(const float
     mask |= 255u << shift;
   }
   if (tid == 0) *lambda_out = key_to_score(prefix);
+}
+
+// The same selection with many workgroups, one launch per radix pass: every workgroup reads the histograms of the
+// passes before (global, complete: they were made by earlier launches), derives the prefix and the remaining rank
+// from them -- all workgroups the same -- and adds the histogram of its own part of the sample to the pass's
+// global bins.  hist: 4 x 256 counters, cleared by the first launch's predecessor.
+constexpr int kPassSampleThreads = 1024;
+constexpr int kPassKeysPerBlock = 16384;
+
+// Called by one whole wavefront: lane l owns bins 4l .. 4l+3 of every pass; the digit of a pass is where the
+// count from the top reaches the remaining rank.  All lanes return the same values.
+__device__ __forceinline__ void prefix_from_histograms(const uint32_t* hist_lds, int n_pass, unsigned long long rank,
+                                                       uint32_t* prefix_out, uint32_t* mask_out,
+                                                       unsigned long long* remaining_out) {
+  const int lane = lane_id();
+  uint32_t prefix = 0, mask = 0;
+  unsigned long long remaining = rank;
+  for (int p = 0; p < n_pass; ++p) {
+    const int shift = 24 - 8 * p;
+    const uint32_t b0 = hist_lds[256 * p + 4 * lane], b1 = hist_lds[256 * p + 4 * lane + 1],
+                   b2 = hist_lds[256 * p + 4 * lane + 2], b3 = hist_lds[256 * p + 4 * lane + 3];
+    unsigned long long suf = static_cast<unsigned long long>(b0) + b1 + b2 + b3;  // inclusive suffix sum over lanes
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const unsigned long long t = __shfl_down(suf, off, kWave);
+      if (lane + off < kWave) suf += t;
+    }
+    const uint64_t ge = __ballot(suf >= remaining);
+    // ge is empty only if the rank exceeds the sample size (excluded by the caller): then the lowest bin is taken
+    const int L = ge != 0 ? 63 - __clzll(static_cast<long long>(ge)) : 0;
+    unsigned long long above = suf - (static_cast<unsigned long long>(b0) + b1 + b2 + b3);  // counts in bins above this lane's
+    int dsel = 0;
+    if (above + b3 >= remaining) {
+      dsel = 3;
+    } else if (above + b3 + b2 >= remaining) {
+      dsel = 2;
+      above += b3;
+    } else if (above + b3 + b2 + b1 >= remaining) {
+      dsel = 1;
+      above += static_cast<unsigned long long>(b3) + b2;
+    } else {
+      above += static_cast<unsigned long long>(b3) + b2 + b1;
+    }
+    const int digit = __shfl(4 * lane + dsel, L, kWave);
+    const unsigned long long above_sel = __shfl(above, L, kWave);
+    prefix |= static_cast<uint32_t>(digit) << shift;
+    mask |= 255u << shift;
+    remaining -= above_sel;
+  }
+  *prefix_out = prefix;
+  *mask_out = mask;
+  *remaining_out = remaining;
+}
+
+__global__ void clear_hist_kernel(uint32_t* hist) { hist[threadIdx.x] = 0; }
+
+__global__ __launch_bounds__(kPassSampleThreads) void kth_pass_kernel(const float* __restrict__ sample, int64_t n,
+                                                                      int64_t rank, int pass,
+                                                                      uint32_t* __restrict__ hist_global) {
+  __shared__ uint32_t prev[3 * 256];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t s_prefix, s_mask;
+  const int tid = threadIdx.x, lane = lane_id();
+  for (int i = tid; i < 256 * pass; i += kPassSampleThreads) prev[i] = hist_global[i];
+  for (int i = tid; i < 256; i += kPassSampleThreads) hist[i] = 0;
+  __syncthreads();
+  if (tid < kWave) {
+    uint32_t prefix, mask;
+    unsigned long long remaining;
+    prefix_from_histograms(prev, pass, static_cast<unsigned long long>(rank), &prefix, &mask, &remaining);
+    if (tid == 0) {
+      s_prefix = prefix;
+      s_mask = mask;
+    }
+  }
+  __syncthreads();
+  const uint32_t prefix = s_prefix, mask = s_mask;
+  const int shift = 24 - 8 * pass;
+  const int64_t lo = static_cast<int64_t>(blockIdx.x) * kPassKeysPerBlock;
+  const int64_t hi = min(lo + kPassKeysPerBlock, n);
+  constexpr int kBatch = 4;
+  for (int64_t i0 = lo + tid; i0 < hi; i0 += kPassSampleThreads * kBatch) {
+    float v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int64_t i = i0 + u * kPassSampleThreads;
+      v[u] = sample[i < hi ? i : hi - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int64_t i = i0 + u * kPassSampleThreads;
+      const uint32_t key = order_key(v[u]);
+      bool part = (i < hi) && ((key & mask) == prefix);
+      const uint32_t digit = (key >> shift) & 255u;
+#pragma unroll
+      for (int round = 0; round < 2; ++round) {  // wavefront aggregation of the hot bins, as in the one-workgroup kernel
+        const uint64_t act = __ballot(part);
+        if (act != 0) {
+          const int leader = __ffsll(static_cast<long long>(act)) - 1;
+          const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
+          const bool same = part && digit == d0;
+          const uint64_t mm = __ballot(same);
+          if (lane == leader) atomicAdd(&hist[d0], static_cast<uint32_t>(__popcll(mm)));
+          part = part && !same;
+        }
+      }
+      if (part) atomicAdd(&hist[digit], 1u);
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < 256; i += kPassSampleThreads) {
+    const uint32_t c = hist[i];
+    if (c != 0) atomicAdd(&hist_global[256 * pass + i], c);
+  }
+}
+
+__global__ __launch_bounds__(256) void kth_final_kernel(const uint32_t* __restrict__ hist_global, int64_t rank,
+                                                        float* __restrict__ lambda_out) {
+  __shared__ uint32_t prev[4 * 256];
+  for (int i = threadIdx.x; i < 4 * 256; i += 256) prev[i] = hist_global[i];
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    uint32_t prefix, mask;
+    unsigned long long remaining;
+    prefix_from_histograms(prev, 4, static_cast<unsigned long long>(rank), &prefix, &mask, &remaining);
+    if (threadIdx.x == 0) *lambda_out = key_to_score(prefix);
+  }
 }
 
 __global__ void fill_float_kernel(float* p, float v) { *p = v; }
@@ -191,15 +319,29 @@ __global__ __launch_bounds__(kAppendThreads) void stream_append_kernel(
 }  // namespace
 }  // namespace dodo
 
+extern "C" size_t dodo_threshold_from_sample_workspace_bytes(int64_t n) {
+  return n > dodo::kPassKeysPerBlock ? 4 * 256 * sizeof(uint32_t) : 0;
+}
+
 extern "C" int dodo_threshold_from_sample(const float* sample, int64_t n, int64_t num, int64_t den, float* lambda_out,
-                                          void* stream) {
+                                          void* ws, size_t ws_bytes, void* stream) {
   using namespace dodo;
   if (n <= 0 || num <= 0 || den <= 0) return DODO_ERR_INVALID_ARG;
   if (!sample || !lambda_out) return DODO_ERR_INVALID_ARG;
   const int64_t k = dodo_nugget_count(n, num, den);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t need = dodo_threshold_from_sample_workspace_bytes(n);
   if (k >= n) {
     hipLaunchKernelGGL(fill_float_kernel, dim3(1), dim3(1), 0, s, lambda_out, -__builtin_inff());
+  } else if (need > 0 && ws != nullptr && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 3u) == 0 &&
+             (n + kPassKeysPerBlock - 1) / kPassKeysPerBlock <= 0x7fffffffLL) {
+    // large samples, given the workspace: one launch per radix pass over many workgroups
+    uint32_t* hist = static_cast<uint32_t*>(ws);
+    const unsigned blocks = static_cast<unsigned>((n + kPassKeysPerBlock - 1) / kPassKeysPerBlock);
+    hipLaunchKernelGGL(clear_hist_kernel, dim3(1), dim3(4 * 256), 0, s, hist);
+    for (int pass = 0; pass < 4; ++pass)
+      hipLaunchKernelGGL(kth_pass_kernel, dim3(blocks), dim3(kPassSampleThreads), 0, s, sample, n, k + 1, pass, hist);
+    hipLaunchKernelGGL(kth_final_kernel, dim3(1), dim3(256), 0, s, hist, k + 1, lambda_out);
   } else {
     hipLaunchKernelGGL(kth_highest_kernel, dim3(1), dim3(kSampleThreads), 0, s, sample, n, k + 1, lambda_out);
   }

@@ -72,7 +72,7 @@ int main() {
   EXPECT(dodo_ste_score_grad(P, P, P, P, P, nullptr, PI, PI, 2, 8, 8, 128, 16, 10, 32, 20, 0.1f, 0.1f, 0, DODO_DTYPE_BF16, 0, PF,
                              nullptr, 0, nullptr),
          DODO_ERR_INVALID_ARG);
-  EXPECT(dodo_threshold_from_sample(PF, 0, 1, 10, PF, nullptr), DODO_ERR_INVALID_ARG);
+  EXPECT(dodo_threshold_from_sample(PF, 0, 1, 10, PF, nullptr, 0, nullptr), DODO_ERR_INVALID_ARG);
   EXPECT(dodo_select_threshold(PF, PI, -1, PF, PO, PO, PO, nullptr), DODO_ERR_INVALID_ARG);
   EXPECT(dodo_stream_append(PF, PF, P, P, DODO_DTYPE_BF16, 2, 4, 64, 8, 16, PO, nullptr, P, P, nullptr), DODO_ERR_INVALID_ARG);
   EXPECT(dodo_probe_read(P, 24, reinterpret_cast<uint32_t*>(buf), nullptr), DODO_ERR_UNSUPPORTED);

@@ -139,9 +139,12 @@ def test_attention_argument_validation(lib):
 def test_threshold_path_argument_validation(lib):
     P = ctypes.c_void_p(16)  # never dereferenced: validation fails first
     i64 = ctypes.c_int64
-    assert lib.dodo_threshold_from_sample(P, i64(0), i64(1), i64(10), P, None) == -1
-    assert lib.dodo_threshold_from_sample(P, i64(10), i64(0), i64(10), P, None) == -1
-    assert lib.dodo_threshold_from_sample(None, i64(10), i64(1), i64(10), P, None) == -1
+    assert lib.dodo_threshold_from_sample(P, i64(0), i64(1), i64(10), P, None, ctypes.c_size_t(0), None) == -1
+    assert lib.dodo_threshold_from_sample(P, i64(10), i64(0), i64(10), P, None, ctypes.c_size_t(0), None) == -1
+    assert lib.dodo_threshold_from_sample(None, i64(10), i64(1), i64(10), P, None, ctypes.c_size_t(0), None) == -1
+    lib.dodo_threshold_from_sample_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.dodo_threshold_from_sample_workspace_bytes(i64(1000)) == 0
+    assert lib.dodo_threshold_from_sample_workspace_bytes(i64(400000)) == 4096
     assert lib.dodo_select_threshold(P, P, -1, P, P, P, P, None) == -1
     assert lib.dodo_select_threshold(P, P, 0, P, P, P, P, None) == 0
     assert lib.dodo_select_threshold(P, P, 2, None, P, P, P, None) == -1

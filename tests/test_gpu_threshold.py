@@ -39,6 +39,29 @@ def test_threshold_from_sample_is_bit_exact(D, n, num, den, kind):
     assert got.tobytes() == want.tobytes(), (got, want)
 
 
+@pytest.mark.parametrize("n,num,den,kind", [(40000, 1, 10, "gauss"), (410000, 1, 20, "gauss"), (65536, 1, 10, "quant"),
+                                            (100001, 1, 10, "specials"), (33000, 9, 10, "specials")])
+def test_threshold_from_large_samples_over_many_workgroups(D, n, num, den, kind):
+    # beyond 16384 scores, given the workspace, one launch per radix pass over many workgroups: the same bits as
+    # the oracle, and as the one-workgroup form (no workspace)
+    assert D.dodo_threshold_from_sample_workspace_bytes(n) > 0
+    s = W.normal(600 + n, 0, (n,), 1.0, torch.float32)
+    if kind == "quant":
+        s = W.quantise16(s)
+    if kind == "specials":
+        s[::7] = float("nan")
+        s[1::11] = -0.0
+        s[2::13] = float("inf")
+        s[3::17] = float("-inf")
+    want = np.float32(oracle.threshold_from_sample(s.numpy(), num, den))
+    sd = s.to(dev())
+    ws = torch.full((D.dodo_threshold_from_sample_workspace_bytes(n),), 0xAB, dtype=torch.uint8, device=dev())
+    got = D.dodo_threshold_from_sample(sd, num, den, ws=ws).cpu().numpy()[0]
+    assert got.tobytes() == want.tobytes(), (got, want)
+    one = D.dodo_threshold_from_sample(sd, num, den, ws=torch.zeros(16, dtype=torch.uint8, device=dev())).cpu().numpy()[0]
+    assert one.tobytes() == want.tobytes()
+
+
 def test_threshold_from_sample_when_the_rank_falls_on_nan(D):
     s = torch.tensor([float("nan"), 5.0, float("nan"), 1.0, -0.0, 7.0], dtype=torch.float32)
     for num, den in [(1, 3), (1, 2), (4, 6)]:
