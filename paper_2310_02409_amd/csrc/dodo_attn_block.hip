@@ -48,6 +48,9 @@ struct HeadDims {
   static constexpr int kTileBytes = kBN * kRowBytes;  // 16 KiB (DH = 128) or 8 KiB (DH = 64) per K or V tile
   static constexpr int kPieces = kRowBytes / 16;      // 16-byte pieces of a row
   static constexpr int kPiecesLog2 = DH == 128 ? 4 : 3;
+  // Rows of 128 bytes cover half of the LDS banks, so two consecutive rows sit side by side and the swizzles take
+  // the row's index from bit 1 on; rows of 256 bytes cover all banks and use the index as it is.
+  static constexpr int kRowShift = DH == 128 ? 0 : 1;
   static constexpr int kChannelBlocks = DH / 32;      // 32-channel blocks of O^T = 64-byte granules of a V row
   static constexpr int kSteps = DH / 8;               // MFMAs per tile of S^T = K Q^T (2 key blocks x DH/16), and of
                                                       // O^T += V^T P^T (4 key steps x DH/32 channel blocks)
@@ -68,23 +71,25 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
 // Per-lane part of the tile loads.  A 64 x DH tile is 64 * P pieces of 16 bytes (P = 16 or 8 per row); wavefront
 // w of NW fills LDS rows (64/NW)*w ..., 64/P rows (1 KiB) per instruction.  The lane at LDS position
 // (row, pos) fetches the piece that the swizzle stores there:
-//   K: piece = pos ^ (row & (P-1))                      (16-byte granules, for the 16-byte row reads)
-//   V: piece = ((pos/4) ^ (row & (P/4-1)))*4 + pos%4    (64-byte granules, for the transposing reads)
+//   K: piece = pos ^ (r & (P-1))                      (16-byte granules, for the 16-byte row reads)
+//   V: piece = ((pos/4) ^ (r & (P/4-1)))*4 + pos%4    (64-byte granules, for the transposing reads)
+// with r = row >> kRowShift.
 template <int NW, int DH>
 struct TileLoader {
   static constexpr int kP = HeadDims<DH>::kPieces;
   static constexpr int kRowsPerInstr = 64 / kP;
   static constexpr int kGranMask = HeadDims<DH>::kChannelBlocks - 1;
+  static constexpr int kRowShift = HeadDims<DH>::kRowShift;
   static constexpr int kPerWave = (kBN / kRowsPerInstr) / NW;  // load instructions per wavefront per tile and tensor
   int row0;                // LDS row of this lane in the wavefront's first instruction
   uint32_t pos;            // 16-byte position inside the row
-  uint32_t v_piece_bytes;  // (row & kGranMask) is the same for all of the wavefront's instructions
+  uint32_t v_piece_bytes;  // the V swizzle term is the same for all of the wavefront's instructions
   uint32_t lds_chunk0;     // byte offset of the wavefront's first 1 KiB chunk inside a tile
 
   __device__ __forceinline__ void init(int wave, int lane) {
     row0 = wave * kPerWave * kRowsPerInstr + (lane >> HeadDims<DH>::kPiecesLog2);
     pos = lane & (kP - 1);
-    v_piece_bytes = ((((pos >> 2) ^ (row0 & kGranMask)) << 2) | (pos & 3)) * 16u;
+    v_piece_bytes = ((((pos >> 2) ^ ((row0 >> kRowShift) & kGranMask)) << 2) | (pos & 3)) * 16u;
     lds_chunk0 = wave * kPerWave * 1024;
   }
   // Rows past the end of the region re-read its last row (finite data, masked later).
@@ -94,7 +99,7 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) {
       const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
-      const uint32_t k_piece_bytes = (pos ^ (row & (kP - 1))) * 16u;
+      const uint32_t k_piece_bytes = (pos ^ ((row >> kRowShift) & (kP - 1))) * 16u;
       dma16_uniform(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
       dma16_uniform(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
@@ -113,7 +118,7 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) {
       const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
-      dma16_uniform(base, roff + (pos ^ (row & (kP - 1))) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + (pos ^ ((row >> kRowShift) & (kP - 1))) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
   // The same three with the rows taken through an index list: row r of the tile is token idx[r] of `base`
@@ -124,7 +129,7 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) {
       const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
-      const uint32_t k_piece_bytes = (pos ^ (row & (kP - 1))) * 16u;
+      const uint32_t k_piece_bytes = (pos ^ ((row >> kRowShift) & (kP - 1))) * 16u;
       dma16_uniform(kbase, roff + k_piece_bytes, __builtin_amdgcn_readfirstlane(lds_k + lds_chunk0 + u * 1024));
       dma16_uniform(vbase, roff + v_piece_bytes, __builtin_amdgcn_readfirstlane(lds_v + lds_chunk0 + u * 1024));
     }
@@ -143,7 +148,7 @@ struct TileLoader {
     for (int u = 0; u < kPerWave; ++u) {
       const int row = row0 + kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(idx[min(row, cnt - 1)]) * stride_bytes;
-      dma16_uniform(base, roff + (pos ^ (row & (kP - 1))) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
+      dma16_uniform(base, roff + (pos ^ ((row >> kRowShift) & (kP - 1))) * 16u, __builtin_amdgcn_readfirstlane(lds_dst + lds_chunk0 + u * 1024));
     }
   }
 };
@@ -266,6 +271,7 @@ __device__ __forceinline__ void attend_query_block(
   using HD = HeadDims<DH>;
   constexpr int kDH = DH, kRowBytes = HD::kRowBytes, kTileBytes = HD::kTileBytes;
   constexpr int kP = HD::kPieces;           // 16-byte pieces of a row
+  constexpr int kRowShift = HD::kRowShift;  // swizzles use row >> kRowShift
   constexpr int kNCB = HD::kChannelBlocks;  // 32-channel blocks of the output
   constexpr int kSteps = HD::kSteps;        // MFMAs of S^T per tile, and of O^T += V^T P^T
   constexpr int kBM = Cfg::kBM;
@@ -376,7 +382,7 @@ __device__ __forceinline__ void attend_query_block(
     const char* qbuf = lds + kQSlot0 * kTileBytes + (wave * 32 + j) * kRowBytes;
 #pragma unroll
     for (int ds = 0; ds < kDH / 16; ++ds)
-      qf[ds] = *reinterpret_cast<const bf16x8*>(qbuf + (((2 * ds + g) ^ (j & (kP - 1))) << 4));
+      qf[ds] = *reinterpret_cast<const bf16x8*>(qbuf + (((2 * ds + g) ^ ((j >> kRowShift) & (kP - 1))) << 4));
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragments are in registers
     if (NW == 8) {
       __syncthreads();  // everyone has its fragments: the stages are free again
@@ -396,8 +402,8 @@ __device__ __forceinline__ void attend_query_block(
   float m_run = kNegInf, l_run = 0.f;
 
   // per-lane constants of the LDS read patterns
-  const int k_row_off = j * kRowBytes;  // K: row 32kb + j, piece (2ds + g) ^ (row & (P-1)); (32kb + j) & (P-1) == j & (P-1)
-  const int k_sw = j & (kP - 1);
+  const int k_row_off = j * kRowBytes;  // K: row 32kb + j, piece (2ds + g) ^ swizzle(row); swizzle(32kb + j) == swizzle(j)
+  const int k_sw = (j >> kRowShift) & (kP - 1);
   // V^T via transposing read: lane supplies row 16t + 8e + 4g + (lane%16)/4, 8 bytes at channel 32cb + 16*half + 4*(lane%4)
   const int v_r = 4 * g + ((lane & 15) >> 2);
   const int v_in = 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
@@ -444,7 +450,7 @@ __device__ __forceinline__ void attend_query_block(
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       const int r = 16 * t + 8 * e + v_r;
-      const char* p = vbuf + r * kRowBytes + ((cb ^ (r & (kNCB - 1))) << 6);
+      const char* p = vbuf + r * kRowBytes + ((cb ^ ((r >> kRowShift) & (kNCB - 1))) << 6);
       a[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
     }
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a[0], a[1], 0, 1, 2, 3, 4, 5, 6, 7));
@@ -683,7 +689,7 @@ __device__ __forceinline__ void attend_query_block(
         uint2 out;
         out.x = pack2_bf16(acc_o[cb][4 * vq + 0] * inv, acc_o[cb][4 * vq + 1] * inv);
         out.y = pack2_bf16(acc_o[cb][4 * vq + 2] * inv, acc_o[cb][4 * vq + 3] * inv);
-        *reinterpret_cast<uint2*>(obuf + j * kRowBytes + ((piece ^ (j & (kP - 1))) << 4) + 8 * g) = out;
+        *reinterpret_cast<uint2*>(obuf + j * kRowBytes + ((piece ^ ((j >> kRowShift) & (kP - 1))) << 4) + 8 * g) = out;
       }
     __builtin_amdgcn_wave_barrier();
     const int n_rows = min(32, q_b - w_i0);  // valid rows of this wavefront (may be <= 0)
@@ -691,7 +697,7 @@ __device__ __forceinline__ void attend_query_block(
 #pragma unroll
     for (int it = 0; it < kP / 2; ++it) {  // 64 / kP rows per iteration, 16 bytes per lane
       const int row = (64 / kP) * it + (lane >> HD::kPiecesLog2), piece = lane & (kP - 1);
-      const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * kRowBytes + ((piece ^ (row & (kP - 1))) << 4));
+      const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * kRowBytes + ((piece ^ ((row >> kRowShift) & (kP - 1))) << 4));
       if (row < n_rows) *reinterpret_cast<uint4*>(obase + static_cast<int64_t>(row) * H * kDH + piece * 8) = val;
     }
   }
