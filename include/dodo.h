@@ -201,6 +201,8 @@ size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, 
  * bound split-K kernel, whose last split combines the partials in split order.  Both are deterministic.
  * Supported: d_h in {64, 128}, fp32 or bf16.  Under grouped-query heads the split-K kernel serves the query heads of
  * a KV head from one workgroup when there are enough (sequence, row, KV head) triples to fill the GPU that way.
+ * The split-K kernel takes at most 65535 (sequence, query-row group) pairs per call (B * max_q at most, fewer when
+ * it groups query rows), and K/V token strides below 2^32 bytes; beyond that DODO_ERR_UNSUPPORTED.
  */
 int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const void* Kl, const void* Vl,
                           const int32_t* cu_q, const int32_t* cu_nuggets, const int32_t* cu_local, int32_t B,

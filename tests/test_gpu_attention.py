@@ -60,6 +60,19 @@ def test_grouped_heads_served_by_one_workgroup(D):
     _full_check(D, 423, [1] * 80, [40] * 80, [9] * 80, 16, 4, 64, torch.bfloat16)
 
 
+def test_neighbouring_heads_served_by_one_workgroup(D):
+    # multi-head attention (every query head its own KV head) with thousands of (sequence, head) pairs: two
+    # neighbouring heads share a workgroup for the sake of contiguous reads; each keeps its own rows and state
+    rng = np.random.default_rng(6)
+    B = 72
+    k_lens = [int(v) for v in rng.integers(0, 90, B)]
+    m_lens = [int(v) for v in rng.integers(1, 40, B)]
+    _full_check(D, 431, [1] * B, k_lens, m_lens, 32, 32, 64, torch.bfloat16)
+    _full_check(D, 432, [1] * (B - 1) + [0], k_lens, m_lens, 32, 32, 128, torch.float32)
+    # ... and with two query rows as well (2 heads x 2 rows per workgroup)
+    _full_check(D, 433, [2] * B, k_lens, m_lens, 32, 32, 64, torch.bfloat16)
+
+
 def test_query_rows_served_by_one_workgroup(D):
     # small query blocks with enough (sequence, row group, head) triples that a workgroup serves 8 (or 4 x 2 heads)
     # query rows together: every row stops at its own causal limit, row groups reach past ragged ends

@@ -45,6 +45,38 @@ def test_attention_random_shapes(D):
             raise AssertionError(f"{case}: {e}") from e
 
 
+def test_attention_random_shapes_shared_kv_rows(D):
+    # many (sequence, head, row) triples, several query heads per KV head and / or a few query rows: the split-K
+    # kernel serves up to 8 query vectors that read the same K/V rows from one workgroup (heads x rows in all
+    # combinations the launch rule picks), each row with its own causal limit
+    rng = np.random.default_rng(15)
+    for it in range(14):
+        B = int(rng.integers(6, 40))
+        dtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+        d_h = int(rng.choice([64, 128]))
+        H_kv = int(rng.choice([1, 2, 4]))
+        H = H_kv * int(rng.choice([1, 2, 4, 8]))
+        qmax = int(rng.choice([1, 2, 3, 5, 8, 13]))
+        q_lens = [int(rng.integers(0, qmax + 1)) for _ in range(B)]
+        q_lens[0] = qmax
+        k_lens = [int(rng.integers(0, 300)) for _ in range(B)]
+        m_lens = [int(rng.integers(0, 200)) for _ in range(B)]
+        if it % 5 == 4:  # long rows as well: several splits per row group, merged by the last one
+            k_lens[1], m_lens[1] = 2500, 900
+        host, d = make_attention_case(5000 + it, q_lens, k_lens, m_lens, H, H_kv, d_h, dtype, dev())
+        scale = d_h ** -0.5
+        O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
+                                          host["cu_nuggets"], host["cu_local"], scale)
+        O, lse = D.dodo_nugget_attention(d["Q"], d["Kn"], d["Vn"], d["Kl"], d["Vl"], d["cu_q"], d["cu_nuggets"],
+                                         d["cu_local"], max(q_lens), max(k_lens), max(m_lens), scale, want_lse=True)
+        case = f"case {it}: {dtype} d_h={d_h} H={H}/{H_kv} q={q_lens} k={k_lens} m={m_lens}"
+        try:
+            check_attention(O, O_ref, dtype)
+            check_lse(lse, lse_ref, dtype)
+        except AssertionError as e:
+            raise AssertionError(f"{case}: {e}") from e
+
+
 def test_select_random_shapes(D):
     rng = np.random.default_rng(12)
     for it in range(16):
