@@ -255,16 +255,46 @@ struct BlockCfg {
   static constexpr int kIdxBytes = kIdxCap * 4;
 };
 
+// What a query block needs to know of its sequence: first rows and lengths of its queries, nuggets and local rows
+// (and, gather-free form, the first token of its context).  Read with scalar loads by load_seq_geom, for both query
+// blocks of a workgroup at the kernel's start, so that no block begins with a chain of dependent loads.
+struct SeqGeom {
+  int b, h, kvh;
+  int q0, q_b, k0, k_b, l0, m_b;
+  int64_t ctx0;
+};
+template <bool IDX>
+__device__ __forceinline__ SeqGeom load_seq_geom(int bh, FastDiv div_H, int H, FastDiv div_G,
+                                                 const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_nuggets,
+                                                 const int32_t* __restrict__ nug_len, const int32_t* __restrict__ cu_local,
+                                                 const int32_t* __restrict__ loc_len, const int32_t* __restrict__ cu_ctx) {
+  SeqGeom g;
+  g.b = static_cast<int>(fast_div(static_cast<uint32_t>(bh), div_H));
+  g.h = bh - g.b * H;
+  g.kvh = static_cast<int>(fast_div(static_cast<uint32_t>(g.h), div_G));
+  const int32_t* k_end_p = nug_len != nullptr ? nug_len + g.b : cu_nuggets + g.b + 1;
+  const int32_t* l_end_p = loc_len != nullptr ? loc_len + g.b : cu_local + g.b + 1;
+  g.q0 = cu_q[g.b];
+  const int q_end = cu_q[g.b + 1];
+  g.k0 = cu_nuggets[g.b];
+  const int k_end = *k_end_p;
+  g.l0 = cu_local[g.b];
+  const int l_end = *l_end_p;
+  g.ctx0 = IDX ? cu_ctx[g.b] : 0;
+  asm volatile("" ::"s"(g.q0), "s"(q_end), "s"(g.k0), "s"(k_end), "s"(g.l0), "s"(l_end), "s"(g.ctx0));  // one round of loads
+  g.q_b = q_end - g.q0;
+  g.k_b = nug_len != nullptr ? k_end : k_end - g.k0;
+  g.m_b = loc_len != nullptr ? l_end : l_end - g.l0;
+  return g;
+}
+
 // One query block (kBM rows) of one (sequence, head); called by the whole workgroup.
 // IDX: Kn / Vn are the context's K / V and nugget j of sequence b is its token cu_ctx[b] + nug_idx[cu_nuggets[b] + j].
 template <int NW, bool IDX, int DH>
 __device__ __forceinline__ void attend_query_block(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
-    const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
-    const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
-    const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
-    const int32_t* __restrict__ cu_ctx,
-    int H, int H_kv, int bh, int qblk,
+    const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ nug_idx,
+    int H, int H_kv, const SeqGeom& geom, int qblk,
     int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse) {
   using Cfg = BlockCfg<NW, DH>;
@@ -279,13 +309,10 @@ __device__ __forceinline__ void attend_query_block(
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // stage s: K at 2s, V at 2s+1 (tiles of 16 KiB)
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void*)lds));
 
-  const int b = bh / H, h = bh % H;
-  const int q0 = cu_q[b], q_b = cu_q[b + 1] - q0;
+  const int h = geom.h, kvh = geom.kvh;
+  const int q0 = geom.q0, q_b = geom.q_b, k0 = geom.k0, k_b = geom.k_b, l0 = geom.l0, m_b = geom.m_b;
   const int i0 = qblk * kBM;
   if (i0 >= q_b) return;  // uniform over the workgroup
-  const int k0 = cu_nuggets[b], k_b = nug_len != nullptr ? nug_len[b] : cu_nuggets[b + 1] - k0;
-  const int l0 = cu_local[b], m_b = loc_len != nullptr ? loc_len[b] : cu_local[b + 1] - l0;
-  const int kvh = h / (H / H_kv);
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -305,7 +332,7 @@ __device__ __forceinline__ void attend_query_block(
   const int n_loc_tiles = (wg_vis + kBN - 1) / kBN;
   const int n_tiles = n_nug_tiles + n_loc_tiles;
 
-  const int64_t nug_row0 = IDX ? cu_ctx[b] : k0;  // IDX: the index list holds tokens of the sequence that starts here
+  const int64_t nug_row0 = IDX ? geom.ctx0 : k0;  // IDX: the index list holds tokens of the sequence that starts here
   const uint16_t* nugK = Kn + nug_row0 * nug_tok_stride + static_cast<int64_t>(kvh) * nug_head_stride;
   const uint16_t* nugV = Vn + nug_row0 * nug_tok_stride + static_cast<int64_t>(kvh) * nug_head_stride;
   const int32_t* idx_l = reinterpret_cast<const int32_t*>(lds + Cfg::kLdsBytes);
@@ -720,13 +747,20 @@ __global__ __launch_bounds__((BlockCfg<NW, DH>::kThreads), (BlockCfg<NW, DH>::kM
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len,
     const int32_t* __restrict__ cu_local, const int32_t* __restrict__ loc_len, const int32_t* __restrict__ nug_idx,
     const int32_t* __restrict__ cu_ctx,
-    int B, int H, int H_kv, int n_qblocks, int pair, int heavy_last, int64_t nug_tok_stride, int64_t nug_head_stride,
-    float scale_log2e, uint16_t* __restrict__ O, float* __restrict__ lse) {
-  const int n_groups = pair ? (n_qblocks + 1) / 2 : n_qblocks;
+    int B, int H, int H_kv, int n_qblocks, int pair, int heavy_last, FastDiv div_groups, FastDiv div_H, FastDiv div_G,
+    int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
+    float* __restrict__ lse) {
+  // all arguments in one round of scalar loads (the compiler would fetch them a few at a time, before each first use)
+  asm volatile("" ::"s"(Q), "s"(Kn), "s"(Vn), "s"(Kl), "s"(Vl), "s"(cu_q), "s"(cu_nuggets), "s"(nug_len), "s"(cu_local),
+               "s"(loc_len), "s"(nug_idx), "s"(cu_ctx), "s"(B), "s"(H), "s"(H_kv), "s"(n_qblocks), "s"(pair),
+               "s"(heavy_last), "s"(div_groups.mul), "s"(div_groups.shift), "s"(div_H.mul), "s"(div_H.shift),
+               "s"(div_G.mul), "s"(div_G.shift), "s"(nug_tok_stride), "s"(nug_head_stride), "s"(scale_log2e), "s"(O),
+               "s"(lse));
+  const int n_groups = pair ? (n_qblocks + 1) >> 1 : n_qblocks;  // (div_groups divides by this)
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int j = slot / n_groups;
+  const int j = static_cast<int>(fast_div(static_cast<uint32_t>(slot), div_groups));
   const int bh = j * 8 + xcd;
-  const int heavy = n_qblocks - 1 - slot % n_groups, light = n_qblocks - 1 - heavy;
+  const int heavy = n_qblocks - 1 - (slot - j * n_groups), light = n_qblocks - 1 - heavy;
   if (bh >= B * H) return;
   // Two neighbouring workgroups of an XCD (j even and odd) share two (sequence, head) pairs
   // crosswise: one takes the heavy block of the first pair and then the light block of the second,
@@ -751,12 +785,15 @@ __global__ __launch_bounds__((BlockCfg<NW, DH>::kThreads), (BlockCfg<NW, DH>::kM
     bh1 = B * H - 1 - bh1;
     bh2 = B * H - 1 - bh2;
   }
-  attend_query_block<NW, IDX, DH>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh1, q1,
-                              nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
+  // both blocks' sequence data are requested here, before the first block's work
+  const SeqGeom g1 = load_seq_geom<IDX>(bh1, div_H, H, div_G, cu_q, cu_nuggets, nug_len, cu_local, loc_len, cu_ctx);
+  const SeqGeom g2 = load_seq_geom<IDX>(q2 >= 0 ? bh2 : bh1, div_H, H, div_G, cu_q, cu_nuggets, nug_len, cu_local, loc_len, cu_ctx);
+  attend_query_block<NW, IDX, DH>(Q, Kn, Vn, Kl, Vl, nug_idx, H, H_kv, g1, q1, nug_tok_stride, nug_head_stride, scale_log2e, O,
+                                  lse);
   if (q2 >= 0) {
     __syncthreads();  // the first block's use of LDS is over
-    attend_query_block<NW, IDX, DH>(Q, Kn, Vn, Kl, Vl, cu_q, cu_nuggets, nug_len, cu_local, loc_len, nug_idx, cu_ctx, H, H_kv, bh2,
-                                q2, nug_tok_stride, nug_head_stride, scale_log2e, O, lse);
+    attend_query_block<NW, IDX, DH>(Q, Kn, Vn, Kl, Vl, nug_idx, H, H_kv, g2, q2, nug_tok_stride, nug_head_stride, scale_log2e, O,
+                                    lse);
   }
 }
 
@@ -780,7 +817,8 @@ int launch_nw(const AttnParams& p) {
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
                      static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.nug_idx, p.cu_ctx, p.B, p.H, p.H_kv,
-                     n_qblocks, pair, p.heavy_last,
+                     n_qblocks, pair, p.heavy_last, make_fast_div(static_cast<uint32_t>(pair ? (n_qblocks + 1) / 2 : n_qblocks)),
+                     make_fast_div(static_cast<uint32_t>(p.H)), make_fast_div(static_cast<uint32_t>(p.H / p.H_kv)),
                      p.nug_tok_stride, p.nug_head_stride, p.scale_log2e, static_cast<uint16_t*>(p.O), p.lse);
   return launch_status();
 }

@@ -17,8 +17,6 @@
 // running or done; the wait is bounded anyway), merges the partials in split
 // order, writes the row and clears the flags.  No float atomics anywhere, so
 // results are run-to-run deterministic.
-#include <type_traits>
-
 #include "dodo_attn.h"
 
 namespace dodo {
@@ -60,19 +58,10 @@ struct Vec16<DODO_DTYPE_F32> {
   }
 };
 
-// Sum over the kLPR lanes that share a K/V row (kLPR = 8, 16 or 32 consecutive lanes), every lane getting the
-// total: data-parallel-primitive adds inside a row of 16 lanes (pairs, quads, mirrored halves, mirrored rows:
-// each step adds the partner group's sum, which is the same in all of its lanes), one lane exchange beyond.
+// Sum over the kLPR lanes that share a K/V row (kLPR = 8, 16 or 32 consecutive lanes), every lane getting the total.
 template <int kLPR>
 __device__ __forceinline__ float sum_over_row_lanes(float d) {
-  auto dpp_add = [](float x, auto ctrl_tag) {
-    constexpr int CTRL = decltype(ctrl_tag)::value;
-    return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
-  };
-  d = dpp_add(d, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
-  d = dpp_add(d, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
-  d = dpp_add(d, std::integral_constant<int, 0x141>{});  // row_half_mirror: lane i <-> 7 - i of each 8
-  if (kLPR >= 16) d = dpp_add(d, std::integral_constant<int, 0x140>{});  // row_mirror: lane i <-> 15 - i
+  d = lanes_sum<(kLPR >= 16 ? 16 : 8)>(d);
   if (kLPR >= 32) d += __shfl_xor(d, 16, kWave);
   return d;
 }

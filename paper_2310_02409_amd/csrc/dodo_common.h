@@ -92,6 +92,50 @@ __device__ __forceinline__ void dma16_uniform(const void* base, uint32_t voff, u
                : "memory", "m0");
 }
 
+// Sum over groups of NL consecutive lanes (NL = 8 or 16: inside one row of 16 lanes), every lane getting its
+// group's total: data-parallel-primitive adds with the partner lane of a pair, the partner pair of a quad, the
+// mirrored half and the mirrored row.  At every step the partner holds its own group's sum in all of its lanes and
+// both sides add the same two numbers, so all lanes of a group end with the same bits.  No LDS traffic.
+template <int NL>
+__device__ __forceinline__ float lanes_sum(float x) {
+  static_assert(NL == 8 || NL == 16, "groups of 8 or 16 lanes");
+#define DODO_DPP_ADD(CTRL) \
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false))
+  DODO_DPP_ADD(0xB1);                // quad_perm [1,0,3,2]
+  DODO_DPP_ADD(0x4E);                // quad_perm [2,3,0,1]
+  DODO_DPP_ADD(0x141);               // row_half_mirror: lane i <-> 7 - i of each 8
+  if (NL == 16) DODO_DPP_ADD(0x140);  // row_mirror: lane i <-> 15 - i
+#undef DODO_DPP_ADD
+  return x;
+}
+// Sum over the 64 lanes of a wavefront, the same bits in every lane: the four rows' sums, read as scalars.
+__device__ __forceinline__ float wave_sum64(float x) {
+  const int r = __builtin_bit_cast(int, lanes_sum<16>(x));
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(r, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(r, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(r, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(r, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+// Division of a number below 2^31 by a divisor fixed on the host: one 32 x 32 -> 64 bit multiplication and a
+// shift, which stay on the scalar unit for a wavefront-uniform dividend (a division by a run-time value would be
+// some thirty vector instructions).  mul = ceil(2^shift / d), shift = 31 + ceil(log2 d): exact for all x < 2^31.
+struct FastDiv {
+  uint32_t mul, shift;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  FastDiv f;
+  f.shift = 31 + l;
+  f.mul = static_cast<uint32_t>(((1ull << f.shift) + d - 1) / d);
+  return f;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t x, FastDiv f) {
+  return static_cast<uint32_t>((static_cast<uint64_t>(x) * f.mul) >> f.shift);
+}
+
 // number of set bits of `mask` strictly below this lane
 __device__ __forceinline__ int popc_below_lane(uint64_t mask) {
   return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),

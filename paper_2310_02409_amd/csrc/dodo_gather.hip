@@ -74,6 +74,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const int bound = cu_nuggets[min(lane + 1, B)];  // upper boundary of sequence `lane`
     const int start = cu_seqlens[min(lane, B)];      // first token of sequence `lane`
     const int idx = nugget_idx[dst_tok];
+    asm volatile("" ::"v"(bound), "v"(start), "s"(idx));  // all three requested before the first branch, one wait
     const uint64_t above = __ballot(lane < B && bound > dst_tok);  // sequences that end after dst_tok
     if (above == 0) return;  // dst_tok >= cu_nuggets[B]: Kt may be an upper bound of the nugget count
     b = __ffsll(static_cast<long long>(above)) - 1;

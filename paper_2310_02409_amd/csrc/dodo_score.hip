@@ -59,10 +59,40 @@ struct Elems<DODO_DTYPE_F32> {
   }
 };
 
-__device__ __forceinline__ float wave_sum(float v) {
+__device__ __forceinline__ float wave_sum(float v) { return wave_sum64(v); }
+
+// The weight vector as fp32 in LDS, staged by the whole workgroup.  16-byte loads, all of a thread's loads issued
+// before the first is used (the kernel's first loads: one round trip instead of one per element); a weight
+// vector that is not 16-byte aligned is fetched element by element.
+template <int DTYPE>
+__device__ __forceinline__ void stage_weights(const void* __restrict__ w, int d, float* __restrict__ w_lds) {
+  using E = Elems<DTYPE>;
+  constexpr int kEPL = E::kPerLoad;
+  constexpr int kVecPerThread = 4;
+  if ((reinterpret_cast<uintptr_t>(w) & 15u) == 0) {
+    const int nvec = d / kEPL;  // d is a multiple of 8
+    for (int v0 = threadIdx.x; v0 < nvec; v0 += kScoreThreads * kVecPerThread) {
+      uint4 wv[kVecPerThread];
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+      for (int u = 0; u < kVecPerThread; ++u)
+        wv[u] = static_cast<const uint4*>(w)[min(v0 + u * kScoreThreads, nvec - 1)];
+#pragma unroll
+      for (int u = 0; u < kVecPerThread; ++u) {
+        const int v = v0 + u * kScoreThreads;
+        if (v < nvec) {
+          float* dst = w_lds + static_cast<size_t>(v) * kEPL;
+          if (DTYPE == DODO_DTYPE_F32) {
+            *reinterpret_cast<uint4*>(dst) = wv[u];
+          } else {
+            *reinterpret_cast<float4*>(dst) = make_float4(bf16_lo(wv[u].x), bf16_hi(wv[u].x), bf16_lo(wv[u].y), bf16_hi(wv[u].y));
+            *reinterpret_cast<float4*>(dst + 4) = make_float4(bf16_lo(wv[u].z), bf16_hi(wv[u].z), bf16_lo(wv[u].w), bf16_hi(wv[u].w));
+          }
+        }
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < d; c += kScoreThreads) w_lds[c] = E::load_one(w, c);
+  }
 }
 
 template <int DTYPE>
@@ -71,6 +101,9 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
                                                               int d, int64_t row_stride,
                                                               float* __restrict__ scores_all, LayerDim ld) {
   using E = Elems<DTYPE>;
+  // all arguments in one round of scalar loads (the compiler would fetch them a few at a time, before each first use)
+  asm volatile("" ::"s"(hidden_all), "s"(w_all), "s"(bias), "s"(N), "s"(d), "s"(row_stride), "s"(scores_all),
+               "s"(ld.hidden_ls), "s"(ld.w_ls), "s"(ld.scores_ls), "s"(ld.biases));
   const int64_t layer = blockIdx.y;
   const size_t esz_l = DTYPE == DODO_DTYPE_F32 ? 4 : 2;
   const void* hidden = static_cast<const char*>(hidden_all) + layer * ld.hidden_ls * esz_l;
@@ -80,7 +113,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
   constexpr int kEPL = E::kPerLoad;     // elements per 16-byte load
   constexpr int kChunk = kWave * kEPL;  // elements one wave-wide load covers
   extern __shared__ __attribute__((aligned(16))) float w_lds[];
-  for (int c = threadIdx.x; c < d; c += kScoreThreads) w_lds[c] = E::load_one(w, c);
+  stage_weights<DTYPE>(w, d, w_lds);
   __syncthreads();
 
   const int lane = lane_id();
@@ -130,6 +163,9 @@ __global__ __launch_bounds__(kScoreThreads) void score_pipelined_kernel(const vo
                                                                         float* __restrict__ scores_all, LayerDim ld) {
   const int nb = SINGLE ? 1 : nb_arg;
   using E = Elems<DTYPE>;
+  // all arguments in one round of scalar loads (the compiler would fetch them a few at a time, before each first use)
+  asm volatile("" ::"s"(hidden_all), "s"(w_all), "s"(bias), "s"(N), "s"(d), "s"(row_stride), "s"(scores_all),
+               "s"(ld.hidden_ls), "s"(ld.w_ls), "s"(ld.scores_ls), "s"(ld.biases));
   const int64_t layer = blockIdx.y;
   const size_t esz_l = DTYPE == DODO_DTYPE_F32 ? 4 : 2;
   const void* hidden = static_cast<const char*>(hidden_all) + layer * ld.hidden_ls * esz_l;
@@ -139,7 +175,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_pipelined_kernel(const vo
   constexpr int kEPL = E::kPerLoad;
   constexpr int kChunk = kWave * kEPL;
   extern __shared__ __attribute__((aligned(16))) float w_lds[];
-  for (int c = threadIdx.x; c < d; c += kScoreThreads) w_lds[c] = E::load_one(w, c);
+  stage_weights<DTYPE>(w, d, w_lds);
   __syncthreads();
 
   const int lane = lane_id();
