@@ -15,7 +15,7 @@
 namespace dodo {
 namespace {
 
-constexpr int kGatherThreads = 256;
+constexpr int kGatherThreads = 512;  // upper bound: the launch picks a size that gives every thread the same number of pieces
 constexpr int kMaxVec = 4;  // 16-byte vectors per thread per tensor held in registers at once
 
 // Copies row src_tok of K or of V (of the layer given by blockIdx.y) to row dst_tok of the nugget cache.
@@ -28,16 +28,17 @@ __device__ __forceinline__ void copy_row(const uint4* __restrict__ src, int64_t 
   const uint4* from = src + layer * src_layer_stride_vec + src_tok * token_stride_vec;
   uint4* to = dst_base + layer * dst_layer_stride_vec;
 
-  for (int c0 = threadIdx.x; c0 < vec_per_row; c0 += kGatherThreads * kMaxVec) {
+  const int threads = blockDim.x;
+  for (int c0 = threadIdx.x; c0 < vec_per_row; c0 += threads * kMaxVec) {
     uint4 v[kMaxVec];
 #pragma unroll
     for (int u = 0; u < kMaxVec; ++u) {
-      const int c = c0 + u * kGatherThreads;
+      const int c = c0 + u * threads;
       if (c < vec_per_row) v[u] = load16_stream(from + c);
     }
 #pragma unroll
     for (int u = 0; u < kMaxVec; ++u) {
-      const int c = c0 + u * kGatherThreads;
+      const int c = c0 + u * threads;
       if (c < vec_per_row) {
         int64_t dst;
         if (HEAD_MAJOR) {
@@ -117,7 +118,12 @@ int gather_entry(const void* K, const void* V, int dtype, const int32_t* nugget_
   const int64_t stride_vec = token_stride * es / 16;
   const int64_t src_l = src_layer_stride * es / 16, dst_l = dst_layer_stride * es / 16;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const dim3 grid(static_cast<unsigned>(2 * Kt), static_cast<unsigned>(L)), block(kGatherThreads);
+  // workgroup size: the row's 16-byte pieces divided evenly over the threads (a 10 KiB row is two pieces each for
+  // 320 threads rather than three for some of 256 and two for the rest), between one and eight wavefronts
+  const int passes = vec_per_row >= 512 ? vec_per_row / 256 : 1;
+  int threads = ((vec_per_row + passes - 1) / passes + kWave - 1) / kWave * kWave;
+  if (threads > kGatherThreads) threads = kGatherThreads;
+  const dim3 grid(static_cast<unsigned>(2 * Kt), static_cast<unsigned>(L)), block(static_cast<unsigned>(threads));
   if (layout == DODO_LAYOUT_HEAD_MAJOR) {
     hipLaunchKernelGGL(gather_kernel<true>, grid, block, 0, s, static_cast<const uint4*>(K),
                        static_cast<const uint4*>(V), nugget_idx, cu_seqlens, cu_nuggets, B, Kt, vec_per_head,
