@@ -2,21 +2,20 @@
 // single-token decode and small query counts: every visible K and V row is
 // read once with 16-byte loads, a group of lanes per row.
 //
-// One workgroup handles one (query row, head, split) -- or several query vectors that read the same K/V rows:
-// the GH query heads of one KV head (grouped-query attention) and / or QR consecutive query rows of a small
-// query block.  Its lane groups are then split between those query vectors, every K/V row is requested by
-// their groups in the same instructions, and the compute unit's L1 turns that into one read of the row, so
-// the row comes from HBM once per KV head and row group rather than once per query vector.  Its 256 threads form
-// G = 256 / lanes-per-row groups; with one head, group g walks rows g, g+G, ... of the split,
-// keeping an independent online-softmax state (running max, sum, d_h partial
-// outputs spread over its lanes) in base 2.  Groups are merged through LDS in
-// group order.  With several splits every workgroup but the last of a row
-// writes its partial (m, s, o) to the workspace and raises a flag; the
-// workgroup of the last split waits for those flags (workgroups start in index
-// order and the last split has the highest indices, so what it waits for is
-// running or done; the wait is bounded anyway), merges the partials in split
-// order, writes the row and clears the flags.  No float atomics anywhere, so
-// results are run-to-run deterministic.
+// One workgroup handles one (query row, head, split) -- or several query vectors: the GH query heads of one KV head
+// (grouped-query attention) and / or QR consecutive query rows of a small query block, which read the same K/V rows,
+// or two neighbouring heads of plain multi-head attention, whose rows lie side by side in memory.  Its lane groups
+// are then split between those query vectors; where they read the same row, the row is requested by their groups
+// in the same instructions and the compute unit's L1 turns that into one read, so it comes from HBM once per KV
+// head and row group rather than once per query vector.  The workgroup's threads form threads / lanes-per-row
+// lane groups; with one query vector, group g walks rows g, g+G, ... of the split, four rows per batch, two
+// batches in flight, keeping an independent online-softmax state (running max, sum, d_h partial outputs spread
+// over its lanes) in base 2.  Lane groups are merged across the lanes of a wavefront, then through LDS, in a
+// fixed order.  With several splits every workgroup but the last of a row writes its partial (m, s, o) to the
+// workspace and raises a flag; the workgroup of the last split waits for those flags (workgroups start in index
+// order and the last split has the highest indices, so what it waits for is running or done; the wait is bounded
+// anyway), merges the partials in split order, writes the row and clears the flags.  No float atomics anywhere,
+// so results are run-to-run deterministic.
 #include "dodo_attn.h"
 
 namespace dodo {
@@ -120,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void splitk_attention_kernel(
   // (GH == 1: few workgroups in all), they are placed a multiple of 8 workgroups apart, so that they run on one XCD
   // at about the same time and share the rows in its L2 as far as that holds them.  (Query rows of one head are H
   // workgroups apart, which does the same when H is a multiple of 8.)
-  // GH > 1: this workgroup serves heads head0 .. head0 + GH - 1 (one KV head); else the one head head0
+  // GH > 1: this workgroup serves heads head0 .. head0 + GH - 1; else the one head head0
   int head0 = blockIdx.x;
   if (GV == 1) {
     if (G > 1 && (H_kv & 7) == 0) {

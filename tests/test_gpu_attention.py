@@ -113,6 +113,19 @@ def test_split_k_workspace_is_reusable_and_needs_no_initialisation(D):
         check_lse(lse, lse_ref, torch.bfloat16)
 
 
+def test_split_k_grid_limit_is_reported(D):
+    # more (sequence, query-row group) pairs than the second grid dimension takes: refused before any launch
+    B = 66000
+    host, d = make_attention_case(440, [1] * B, [1] * B, [1] * B, 1, 1, 64, torch.float32, dev())
+    with pytest.raises(D.DodoError) as e:
+        D.dodo_nugget_attention(d["Q"], d["Kn"], d["Vn"], d["Kl"], d["Vl"], d["cu_q"], d["cu_nuggets"], d["cu_local"],
+                                1, 1, 1, 0.125)
+    assert e.value.status == -2
+    # ... and one below the limit runs and is right
+    B = 65535
+    _full_check(D, 441, [1] * B, [1] * B, [1] * B, 1, 1, 64, torch.float32)
+
+
 def test_tiny_fp32_config_block_through_split_k_kernel(D):
     # workload 1: 32 causal query rows, 16 earlier local rows, 52 nuggets, 4 heads x 64, fp32
     _full_check(D, 403, [32], [52], [48], 4, 4, 64, torch.float32)
