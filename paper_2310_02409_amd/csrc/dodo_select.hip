@@ -49,13 +49,17 @@ __global__ __launch_bounds__(THREADS) void select_topk_kernel(const float* __res
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
   __shared__ int s_ok, s_out_base, s_eq_base;
 
+  // (a latency-bound kernel: all arguments in one round of scalar loads, the sequence's four boundaries in a second)
+  asm volatile("" ::"s"(scores), "s"(cu_seqlens), "s"(cu_nuggets), "s"(flags), "s"(max_n), "s"(lds_keys), "s"(G), "s"(ws),
+               "s"(nugget_idx));
   const int b = MULTI ? blockIdx.x / G : blockIdx.x;
   const int chunk = MULTI ? blockIdx.x % G : 0;
   const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
-  const int seq0 = cu_seqlens[b];
-  const int n = cu_seqlens[b + 1] - seq0;
-  const int nug0 = cu_nuggets[b];
-  int k = cu_nuggets[b + 1] - nug0;
+  const int seq0 = cu_seqlens[b], seq1 = cu_seqlens[b + 1];
+  const int nug0 = cu_nuggets[b], nug1 = cu_nuggets[b + 1];
+  asm volatile("" ::"s"(seq0), "s"(seq1), "s"(nug0), "s"(nug1));
+  const int n = seq1 - seq0;
+  int k = nug1 - nug0;
   if (k <= 0 || n <= 0 || n > max_n) return;  // uniform over the workgroup
   if (k > n) k = n;
   const bool force = (flags & DODO_TOPK_FORCE_LAST) != 0;
