@@ -126,6 +126,18 @@ def _dev(*ts: Optional[torch.Tensor]) -> None:
             raise ValueError("dodo tensors must be contiguous device tensors")
 
 
+def _dev_rows(*ts: torch.Tensor) -> None:
+    """Device tensors whose rows (all dimensions but the first) are contiguous; the first dimension may be strided."""
+    for t in ts:
+        inner = 1
+        for size, stride in zip(reversed(t.shape[1:]), reversed(t.stride()[1:])):
+            if size != 1 and stride != inner:
+                raise ValueError("dodo tensors must have contiguous rows")
+            inner *= size
+        if not t.is_cuda or (t.shape[0] > 1 and t.stride(0) < inner):
+            raise ValueError("dodo tensors must be device tensors with a row stride of at least a row")
+
+
 def dodo_version() -> int:
     return int(lib.dodo_version())
 
@@ -150,7 +162,8 @@ def cu_nuggets_from_lengths(seq_lens: Sequence[int], num: int, den: int, device)
 def dodo_score(hidden: torch.Tensor, w: torch.Tensor, bias: float = 0.0,
                scores: Optional[torch.Tensor] = None) -> torch.Tensor:
     """scores[t] = hidden[t] . w + bias (fp32 [N]) for packed hidden [N, d]."""
-    _dev(hidden, w, scores)
+    _dev(w, scores)
+    _dev_rows(hidden)
     N, d = hidden.shape
     assert w.shape == (d,) and w.dtype == hidden.dtype
     if scores is None:
@@ -208,9 +221,10 @@ def dodo_gather_nuggets(K: torch.Tensor, V: torch.Tensor, nugget_idx: torch.Tens
                         cu_nuggets: torch.Tensor, total_nuggets: int, layout: int = TOKEN_MAJOR,
                         Kn: Optional[torch.Tensor] = None, Vn: Optional[torch.Tensor] = None):
     """Packs the chosen rows of K, V [N, H_kv, d_h] into the nugget cache."""
-    _dev(K, V, nugget_idx, cu_seqlens, cu_nuggets, Kn, Vn)
+    _dev(nugget_idx, cu_seqlens, cu_nuggets, Kn, Vn)
+    _dev_rows(K, V)
     _, H_kv, d_h = K.shape
-    assert V.shape == K.shape and V.dtype == K.dtype
+    assert V.shape == K.shape and V.dtype == K.dtype and V.stride() == K.stride()
     B = cu_seqlens.numel() - 1
     shape = (total_nuggets, H_kv, d_h) if layout == TOKEN_MAJOR else (H_kv, total_nuggets, d_h)
     if Kn is None:

@@ -55,6 +55,22 @@ def test_score_is_deterministic_and_respects_row_stride(D):
         assert torch.equal(scores, first)
 
 
+@pytest.mark.parametrize("dtype,d,pad,unaligned", [
+    (torch.bfloat16, 4096, 64, False), (torch.bfloat16, 5120, 0, True), (torch.float32, 1536, 8, True),
+    (torch.bfloat16, 520, 8, True), (torch.float32, 4096, 0, False),
+])
+def test_score_strided_rows_and_unaligned_weights_through_the_binding(D, dtype, d, pad, unaligned):
+    # rows further apart than d elements; a weight vector that does not start on a 16-byte boundary is staged
+    # element by element instead of with 16-byte loads
+    N = 257
+    hid = W.normal(102, 0, (N, d + pad), 1.0, dtype)
+    wfull = W.normal(102, 1, (d + 8,), d ** -0.5, dtype)
+    lo = 1 if unaligned else 0
+    ref = oracle.score(W.to_numpy(hid[:, :d].contiguous()), W.to_numpy(wfull[lo:lo + d].contiguous()), 0.25)
+    got = D.dodo_score(hid.to(dev())[:, :d], wfull.to(dev())[lo:lo + d], 0.25).cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 1e-5 * (1 + np.abs(ref))), np.max(np.abs(got - ref))
+
+
 @pytest.mark.parametrize("dtype,L,N,d", [(torch.bfloat16, 5, 700, 4096), (torch.float32, 3, 129, 256), (torch.bfloat16, 2, 64, 1000)])
 def test_score_layers_matches_oracle_and_the_single_layer_call(D, dtype, L, N, d):
     x = W.normal(130, 0, (L, N, d), 1.0, dtype)
@@ -226,6 +242,28 @@ def test_gather_bit_exact(D, dtype, H_kv, d_h, layout):
     Kn, Vn = D.dodo_gather_nuggets(K.to(dev()), V.to(dev()), torch.from_numpy(idx).to(dev()),
                                    torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()),
                                    int(cu_k[-1]), layout)
+    assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)
+
+
+@pytest.mark.parametrize("dtype,H_kv,d_h,layout", [
+    (torch.bfloat16, 40, 128, 0), (torch.bfloat16, 1, 64, 1), (torch.float32, 5, 64, 0), (torch.float32, 40, 128, 1),
+    (torch.bfloat16, 3, 128, 0),
+])
+def test_gather_row_widths_and_token_stride(D, dtype, H_kv, d_h, layout):
+    # rows from 128 bytes to 20 KiB (the workgroup size follows the row width), tokens one head further apart than
+    # the heads that are gathered
+    n_lens = [90, 0, 41, 300, 7]
+    N = sum(n_lens)
+    K = W.normal(301, 0, (N, H_kv + 1, d_h), 1.0, dtype)
+    V = W.normal(301, 1, (N, H_kv + 1, d_h), 1.0, dtype)
+    k_lens, cu_k = oracle_counts(n_lens, 1, 3)
+    cu_s = oracle.cu_from_lengths(n_lens)
+    idx = oracle.select_topk(W.normal(301, 2, (N,), 1.0, torch.float32).numpy(), cu_s, cu_k)
+    Kn_ref, Vn_ref = oracle.gather(W.to_numpy(K[:, :H_kv].contiguous()), W.to_numpy(V[:, :H_kv].contiguous()), idx, cu_s,
+                                   cu_k, layout)
+    Kn, Vn = D.dodo_gather_nuggets(K.to(dev())[:, :H_kv], V.to(dev())[:, :H_kv], torch.from_numpy(idx).to(dev()),
+                                   torch.from_numpy(cu_s).to(dev()), torch.from_numpy(cu_k).to(dev()), int(cu_k[-1]),
+                                   layout)
     assert np.array_equal(W.to_numpy(Kn), Kn_ref) and np.array_equal(W.to_numpy(Vn), Vn_ref)
 
 
