@@ -3,9 +3,9 @@
 // K and V rows of a chunk are averaged into one row, giving a cache of the same
 // shape as the nugget cache (same downstream attention calls).
 //
-// HBM-bound: every K and V row is read once.  One workgroup per output row; a
-// thread owns 16-byte pieces of the row and walks the chunk's tokens in order,
-// four tokens' loads in flight.  Sums and the division are done in double and
+// HBM-bound: every K and V row is read once.  One workgroup per output row and
+// tensor; a thread owns a 16-byte piece of the row and walks the chunk's tokens in
+// order, eight tokens' loads in flight.  Sums and the division are done in double and
 // rounded once to the storage type, in the same order as the plain definition,
 // so the result is bit-exact.
 #include "dodo_common.h"
@@ -13,8 +13,8 @@
 namespace dodo {
 namespace {
 
-constexpr int kPoolThreads = 256;
-constexpr int kTokensInFlight = 4;
+constexpr int kPoolThreads = 512;  // upper bound: the launch gives every thread one 16-byte piece of the row if it can
+constexpr int kTokensInFlight = 8;
 
 // double -> bf16 bits with one rounding (to nearest, ties to even); finite inputs and NaN
 __device__ __forceinline__ uint16_t f64_to_bf16_bits(double v) {
@@ -71,41 +71,70 @@ __global__ __launch_bounds__(kPoolThreads) void meanpool_kernel(
     const int32_t* __restrict__ cu_nuggets, int B, int64_t Kt, int vec_per_head, int vec_per_row,
     int64_t token_stride_vec, uint4* __restrict__ Kn, uint4* __restrict__ Vn) {
   using P = Piece<DTYPE>;
-  const int64_t dst_tok = blockIdx.x;
-  if (dst_tok >= cu_nuggets[B]) return;
-  int lo = 0, hi = B;  // sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (cu_nuggets[mid] <= dst_tok) lo = mid; else hi = mid;
+  // two workgroups per output row, one for its K and one for its V (as in the gather kernel)
+  const int64_t dst_tok = blockIdx.x >> 1;
+  const uint4* __restrict__ src = (blockIdx.x & 1) ? V : K;
+  uint4* __restrict__ dst_base = (blockIdx.x & 1) ? Vn : Kn;
+  // Sequence b with cu_nuggets[b] <= dst_tok < cu_nuggets[b+1], its first token and its lengths.  For up to 64
+  // sequences every lane fetches the boundaries of one sequence, all in one round of loads before the first
+  // branch; a ballot finds b and lane reads hand its values over.  More sequences: a binary search.
+  int seq0, nug0;
+  int64_t n, k;
+  if (B <= kWave) {
+    const int lane = lane_id();
+    const int lo_i = min(lane, B), hi_i = min(lane + 1, B);
+    const int nug_lo = cu_nuggets[lo_i], nug_hi = cu_nuggets[hi_i];
+    const int seq_lo = cu_seqlens[lo_i], seq_hi = cu_seqlens[hi_i];
+    asm volatile("" ::"v"(nug_lo), "v"(nug_hi), "v"(seq_lo), "v"(seq_hi));  // one wait for all four
+    const uint64_t above = __ballot(lane < B && nug_hi > dst_tok);  // sequences that end after dst_tok
+    if (above == 0) return;  // dst_tok >= cu_nuggets[B]: Kt may be an upper bound of the row count
+    const int b = __ffsll(static_cast<long long>(above)) - 1;
+    nug0 = __shfl(nug_lo, b, kWave);
+    seq0 = __shfl(seq_lo, b, kWave);
+    k = __shfl(nug_hi, b, kWave) - nug0;
+    n = __shfl(seq_hi, b, kWave) - seq0;
+  } else {
+    if (dst_tok >= cu_nuggets[B]) return;
+    int lo = 0, hi = B;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (cu_nuggets[mid] <= dst_tok) lo = mid; else hi = mid;
+    }
+    nug0 = cu_nuggets[lo];
+    seq0 = cu_seqlens[lo];
+    k = cu_nuggets[lo + 1] - nug0;
+    n = cu_seqlens[lo + 1] - seq0;
   }
-  const int b = lo;
-  const int64_t n = cu_seqlens[b + 1] - cu_seqlens[b];
-  const int64_t k = cu_nuggets[b + 1] - cu_nuggets[b];
-  const int64_t j = dst_tok - cu_nuggets[b];
-  const int64_t t0 = j * n / k, t1 = (j + 1) * n / k;
+  const int64_t j = dst_tok - nug0;
+  // chunk boundaries floor(j n / k) and floor((j + 1) n / k): in 32 bits when the products fit (a 64-bit division by
+  // a run-time value is some hundred vector instructions)
+  int64_t t0, t1;
+  if ((j + 1) * n <= 0xffffffffLL) {
+    t0 = static_cast<uint32_t>(j * n) / static_cast<uint32_t>(k);
+    t1 = static_cast<uint32_t>((j + 1) * n) / static_cast<uint32_t>(k);
+  } else {
+    t0 = j * n / k;
+    t1 = (j + 1) * n / k;
+  }
   const double inv = t1 > t0 ? 1.0 / static_cast<double>(t1 - t0) : 0.0;
-  const uint4* ksrc = K + (cu_seqlens[b] + t0) * token_stride_vec;
-  const uint4* vsrc = V + (cu_seqlens[b] + t0) * token_stride_vec;
+  const uint4* rows = src + (seq0 + t0) * token_stride_vec;
   const int len = static_cast<int>(t1 - t0);
 
-  for (int c = threadIdx.x; c < vec_per_row; c += kPoolThreads) {
-    double ak[P::kElems], av[P::kElems];
+  const int threads = blockDim.x;
+  for (int c = threadIdx.x; c < vec_per_row; c += threads) {
+    double acc[P::kElems];
 #pragma unroll
-    for (int e = 0; e < P::kElems; ++e) ak[e] = av[e] = 0.0;
+    for (int e = 0; e < P::kElems; ++e) acc[e] = 0.0;
     for (int t = 0; t < len; t += kTokensInFlight) {
-      uint4 kk[kTokensInFlight], vv[kTokensInFlight];
+      uint4 vv[kTokensInFlight];
 #pragma unroll
       for (int u = 0; u < kTokensInFlight; ++u) {
         const int64_t tt = min(t + u, len - 1);  // unconditional loads; the surplus is not added
-        kk[u] = load16_stream(ksrc + tt * token_stride_vec + c);
-        vv[u] = load16_stream(vsrc + tt * token_stride_vec + c);
+        vv[u] = load16_stream(rows + tt * token_stride_vec + c);
       }
 #pragma unroll
       for (int u = 0; u < kTokensInFlight; ++u)
-        if (t + u < len) {
-          P::add(kk[u], ak);
-          P::add(vv[u], av);
-        }
+        if (t + u < len) P::add(vv[u], acc);
     }
     int64_t dst;
     if (HEAD_MAJOR) {
@@ -114,8 +143,7 @@ __global__ __launch_bounds__(kPoolThreads) void meanpool_kernel(
     } else {
       dst = dst_tok * vec_per_row + c;
     }
-    store16_stream(Kn + dst, P::round(ak, inv));
-    store16_stream(Vn + dst, P::round(av, inv));
+    store16_stream(dst_base + dst, P::round(acc, inv));
   }
 }
 
@@ -140,7 +168,10 @@ extern "C" int dodo_meanpool_nuggets(const void* K, const void* V, int dtype, co
   const int vec_per_row = vec_per_head * H_kv;
   const int64_t stride_vec = token_stride * es / 16;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const dim3 grid(static_cast<unsigned>(Kt)), block(kPoolThreads);
+  if (Kt > 0x3fffffffLL) return DODO_ERR_UNSUPPORTED;
+  int threads = (vec_per_row + kWave - 1) / kWave * kWave;
+  if (threads > kPoolThreads) threads = kPoolThreads;
+  const dim3 grid(static_cast<unsigned>(2 * Kt)), block(static_cast<unsigned>(threads));
   auto go = [&](auto kern) {
     hipLaunchKernelGGL(kern, grid, block, 0, s, static_cast<const uint4*>(K), static_cast<const uint4*>(V), cu_seqlens,
                        cu_nuggets, B, Kt, vec_per_head, vec_per_row, stride_vec, static_cast<uint4*>(Kn),
