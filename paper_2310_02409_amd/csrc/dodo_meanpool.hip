@@ -5,7 +5,7 @@
 //
 // HBM-bound: every K and V row is read once.  One workgroup per output row and
 // tensor; a thread owns a 16-byte piece of the row and walks the chunk's tokens in
-// order, eight tokens' loads in flight.  Sums and the division are done in double and
+// order, twelve tokens' loads in flight.  Sums and the division are done in double and
 // rounded once to the storage type, in the same order as the plain definition,
 // so the result is bit-exact.
 #include "dodo_common.h"
@@ -14,7 +14,7 @@ namespace dodo {
 namespace {
 
 constexpr int kPoolThreads = 512;  // upper bound: the launch gives every thread one 16-byte piece of the row if it can
-constexpr int kTokensInFlight = 8;
+constexpr int kTokensInFlight = 12;  // (chunks of 10 tokens at 10x: one batch; a load under a condition costs more than a surplus one)
 
 // double -> bf16 bits with one rounding (to nearest, ties to even); finite inputs and NaN
 __device__ __forceinline__ uint16_t f64_to_bf16_bits(double v) {
