@@ -510,7 +510,8 @@ def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec
              frac_of_bf16_peak=round(flop / r["avg_us"] * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
              plan=t(lambda: D.dodo_segment_plan(g["idx"], g["cu_seqlens"], cu_k, seg_len, tau, n_seg)))
     out["segment_form_8x4096_seg512_tau128"] = r
-    # grouped-query decode (8 query heads per KV head): the heads of a group run on one XCD and share the rows in its L2
+    # grouped-query decode (8 query heads per KV head): one workgroup per (sequence, KV head) reads every row once
+    # for the 8 heads and multiplies on the matrix cores
     Bg, Hg, Hkvg, kg, mg = 64, 64, 8, 410, 257
     gsets = []
     for s_ in range(4):

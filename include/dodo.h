@@ -178,11 +178,21 @@ int dodo_gather_nuggets_layers(const void* K, const void* V, int dtype, const in
 /* Bytes of device workspace dodo_nugget_attention needs for these bounds (may be 0).  The workspace holds
  * the partial results of the split-K kernel and one flag word per partial.  Its contents need not be
  * initialised, with one exception: no flag word may hold the library's "ready" value 0x600DD0D0 on
- * entry -- the call clears the flags it used, so memory that was never a workspace of this library and
- * memory that was one in a completed call both qualify; fill it with zeros after a call that was aborted.
+ * entry -- the call clears the flags it used, so zero-filled memory and memory that was a workspace in a
+ * completed call with the same arguments both qualify; fill it with zeros after a call that was aborted or
+ * before a call with other sizes.
  * A workspace must not be shared by calls that may overlap in time. */
 size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, int32_t max_k,
                                              int32_t max_local, int dtype);
+
+/* The same with the number of KV heads known: at least the size above, and more where the kernel for grouped
+ * heads and small query blocks (see dodo_nugget_attention) would like to split the keys of a (sequence, KV head)
+ * pair over more workgroups than that size has partial records for -- a small batch with few KV heads.  That
+ * kernel takes whatever workspace it is given and splits as far as the records fit (not at all without one, or
+ * with one that is not 8-byte aligned), so the smaller size is always sufficient and this one is the faster.
+ * Same rules for the contents. */
+size_t dodo_nugget_attention_workspace_bytes_grouped(int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q,
+                                                     int32_t max_k, int32_t max_local, int dtype);
 
 /*
  * Nugget attention (Eq. 13 compressor mode; Eq. 9 mixed resolution).  For
@@ -199,8 +209,12 @@ size_t dodo_nugget_attention_workspace_bytes(int32_t B, int32_t H, int32_t d_h, 
  * multiplied on the matrix cores with fp32 accumulation when max_q >= 16
  * (query-block kernel); smaller max_q and all fp32 inputs use the bandwidth-
  * bound split-K kernel, whose last split combines the partials in split order.  Both are deterministic.
- * Supported: d_h in {64, 128}, fp32 or bf16.  Under grouped-query heads the split-K kernel serves the query heads of
- * a KV head from one workgroup when there are enough (sequence, row, KV head) triples to fill the GPU that way.
+ * Supported: d_h in {64, 128}, fp32 or bf16.  When 4 to 32 query vectors read the same K/V rows -- (H / H_kv) *
+ * max_q of them: grouped-query heads, a small query block, or both -- and the inputs are bf16 with d_h = 128, a
+ * third kernel reads every K/V row once for all of them and multiplies on the matrix cores (fp32 accumulation,
+ * partial results merged in a fixed order: deterministic for a given workspace size).  Otherwise the split-K kernel
+ * serves the query heads of a KV head from one workgroup when there are enough (sequence, row, KV head) triples to
+ * fill the GPU that way.
  * The split-K kernel takes at most 65535 (sequence, query-row group) pairs per call (B * max_q at most, fewer when
  * it groups query rows), and K/V token strides below 2^32 bytes; beyond that DODO_ERR_UNSUPPORTED.
  */
@@ -219,7 +233,8 @@ int dodo_nugget_attention(const void* Q, const void* Kn, const void* Vn, const v
  * DODO_NOALLOC_MAX_PARTIALS partial results, i.e. (sequence, query row, head, split) combinations of a
  * call that splits (dodo_nugget_attention_workspace_bytes / ((d_h + 3) * 4) gives the number for given
  * bounds; 0 means the call needs no buffer at all and always fits); beyond that the call returns
- * DODO_ERR_SCRATCH_LIMIT and launches nothing.  All calls on one GPU share that GPU's buffer: calls that
+ * DODO_ERR_SCRATCH_LIMIT and launches nothing (the kernel for grouped heads and small query blocks never
+ * does: it splits as far as the buffer has room).  All calls on one GPU share that GPU's buffer: calls that
  * may overlap in time on one GPU (different streams, different threads) race and must not be made; calls
  * on one stream are ordered and safe.  Each call leaves the buffer's flags cleared for the next.
  */

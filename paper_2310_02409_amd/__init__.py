@@ -8,7 +8,7 @@ library has not been built, importing this package raises.
 """
 from .binding import (  # noqa: F401
     BF16, F32, FORCE_LAST, GELU, HEAD_MAJOR, RELU, TANH, TOKEN_MAJOR, DodoError, LIB_PATH,
-    dodo_gather_nuggets, dodo_gather_nuggets_layers, dodo_meanpool_nuggets, dodo_nugget_attention, dodo_nugget_attention_workspace_bytes, dodo_nugget_count, dodo_probe_copy, dodo_probe_read,
+    dodo_gather_nuggets, dodo_gather_nuggets_layers, dodo_meanpool_nuggets, dodo_nugget_attention, dodo_nugget_attention_workspace_bytes, dodo_nugget_attention_workspace_bytes_grouped, dodo_nugget_count, dodo_probe_copy, dodo_probe_read,
     dodo_nugget_attention_cached, dodo_nugget_attention_indexed, dodo_nugget_attention_noalloc, dodo_nugget_attention_segments, dodo_segment_plan,
     dodo_ste_score_grad, dodo_ste_score_grad_workspace_bytes,
     dodo_score, dodo_score_layers, dodo_score_mlp, dodo_score_mlp_workspace_bytes, dodo_select_threshold, dodo_select_topk,

@@ -66,6 +66,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
                                       vp]
     L.dodo_nugget_attention_workspace_bytes.restype = sz
     L.dodo_nugget_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, ctypes.c_int]
+    L.dodo_nugget_attention_workspace_bytes_grouped.restype = sz
+    L.dodo_nugget_attention_workspace_bytes_grouped.argtypes = [i32, i32, i32, i32, i32, i32, i32, ctypes.c_int]
     L.dodo_nugget_attention.restype = ctypes.c_int
     L.dodo_nugget_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i64, f32,
                                         ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, vp]
@@ -268,6 +270,11 @@ def dodo_nugget_attention_workspace_bytes(B: int, H: int, d_h: int, max_q: int, 
     return int(lib.dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, dtype))
 
 
+def dodo_nugget_attention_workspace_bytes_grouped(B: int, H: int, H_kv: int, d_h: int, max_q: int, max_k: int,
+                                                  max_local: int, dtype: int) -> int:
+    return int(lib.dodo_nugget_attention_workspace_bytes_grouped(B, H, H_kv, d_h, max_q, max_k, max_local, dtype))
+
+
 def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, Kl: torch.Tensor, Vl: torch.Tensor,
                           cu_q: torch.Tensor, cu_nuggets: torch.Tensor, cu_local: torch.Tensor, max_q: int,
                           max_k: int, max_local: int, softmax_scale: Optional[float] = None,
@@ -287,7 +294,7 @@ def dodo_nugget_attention(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Tensor, K
     if lse is None and want_lse:
         lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
     code = _dtype_code(Q)
-    need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, code)
+    need = dodo_nugget_attention_workspace_bytes_grouped(B, H, H_kv, d_h, max_q, max_k, max_local, code)
     if need and ws is None:
         # zero-filled: the split-K flags must not hold the library's "ready" value on entry
         ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
@@ -415,7 +422,7 @@ def dodo_nugget_attention_segments(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.
     if lse is None and want_lse:
         lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
     code = _dtype_code(Q)
-    need = dodo_nugget_attention_workspace_bytes(n_seg, H, d_h, max_q, max_k, max_local, code)
+    need = dodo_nugget_attention_workspace_bytes_grouped(n_seg, H, H_kv, d_h, max_q, max_k, max_local, code)
     if need and ws is None:
         ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
     _check(lib.dodo_nugget_attention_segments(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(K), _ptr(V), _ptr(seg_cu_q),
@@ -447,7 +454,7 @@ def dodo_nugget_attention_cached(Q: torch.Tensor, Kn: torch.Tensor, Vn: torch.Te
     if lse is None and want_lse:
         lse = torch.empty((Sq, H), dtype=torch.float32, device=Q.device)
     code = _dtype_code(Q)
-    need = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, code)
+    need = dodo_nugget_attention_workspace_bytes_grouped(B, H, H_kv, d_h, max_q, max_k, max_local, code)
     if need and ws is None:
         ws = torch.zeros(need, dtype=torch.uint8, device=Q.device)
     _check(lib.dodo_nugget_attention_cached(_ptr(Q), _ptr(Kn), _ptr(Vn), _ptr(Kl), _ptr(Vl), _ptr(cu_q),

@@ -20,18 +20,34 @@ struct AttnParams {
   int dtype;
   void* O;
   float* lse;
-  void* ws;        // split-K kernel: partial records, followed by one flag word per record ...
-  void* ws_flags;  // ... unless this is set: then the flag words live here
+  void* ws;         // bandwidth-bound kernels: partial records, followed by one flag word per record ...
+  size_t ws_bytes;  //   (bytes at ws)
+  void* ws_flags;   // ... unless this is set: then the flag words live here, and both regions hold ws_slots entries
+  int64_t ws_slots;
   hipStream_t stream;
 };
 
-// Split count of the bandwidth-bound kernel for these bounds (>= 1), shared by
-// the launch and the workspace query.
+// Workspace format of the bandwidth-bound kernels: one partial record [m, s, o[0..DH)] of floats per (sequence,
+// query row, head, split); after all records (or where ws_flags points), one 32-bit flag per record.
+template <int DH>
+__host__ __device__ constexpr int partial_floats() { return DH + 2; }
+constexpr uint32_t kPartialReady = 0x600DD0D0u;  // flag value of a record that has been written
+constexpr int kMaxPolls = 1 << 17;               // bound of the combiner's wait (~0.1 s, never reached in a healthy run)
+
+// Split count of the bandwidth-bound kernels for these bounds (>= 1), shared by
+// the launches and the workspace query.
 int splitk_count(int32_t B, int32_t H, int32_t max_q, int32_t max_k, int32_t max_local);
 size_t splitk_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, int nsplit);
 
 // fp32 or bf16, d_h in {64,128}, any max_q: one workgroup per (query row, head, split).
 int launch_splitk_attention(const AttnParams& p);
+// bf16, d_h = 128, 4 to 32 query vectors per KV head and sequence ((H / H_kv) * max_q): MFMA kernel that reads
+// every K/V row once for all of them.  group_attention_applies says whether it takes the call.
+// It splits the keys of a (sequence, KV head) pair as far as the caller's workspace has room for records;
+// group_workspace_bytes is the size that lets it split as far as it would like to (0: no split wanted).
+bool group_attention_applies(const AttnParams& p);
+size_t group_workspace_bytes(int32_t B, int32_t H, int32_t H_kv, int32_t max_q, int32_t max_k, int32_t max_local);
+int launch_group_attention(const AttnParams& p);
 // bf16, d_h in {64,128}: MFMA kernel over 128- or 256-row query blocks.
 int launch_block_attention(const AttnParams& p);
 

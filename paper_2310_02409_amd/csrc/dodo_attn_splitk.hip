@@ -67,13 +67,6 @@ __device__ __forceinline__ float sum_over_row_lanes(float d) {
 
 __device__ __forceinline__ float exp2_guard(float x) { return __builtin_amdgcn_exp2f(x); }  // exp2(-inf) = 0
 
-// partial record of one split in the workspace: [m, s, o[0..DH)] floats; after all records, one
-// 32-bit flag per record
-template <int DH>
-__host__ __device__ constexpr int partial_floats() { return DH + 2; }
-constexpr uint32_t kPartialReady = 0x600DD0D0u;  // flag value of a record that has been written
-constexpr int kMaxPolls = 1 << 17;               // bound of the combiner's wait (~0.1 s, never reached in a healthy run)
-
 // INDEXED: Kn / Vn are the context's K / V ([N, H_kv, DH], nug_tok_stride between tokens) and nugget j of
 // sequence b is token cu_ctx[b] + nug_idx[cu_nuggets[b] + j] of it (no packed cache has been made).
 // GROUPED: the workgroup serves GH query heads of one KV head times QR query rows, more than one query vector in all
