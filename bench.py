@@ -527,6 +527,30 @@ def next_rows_c2(torch, D, W, clock, dev, wl, g, cu_k, ks, ws, cu_qd, cu_ld, dec
     r.update(min_us=round(m_, 2), note=f"batch {Bg}, {Hg} query heads over {Hkvg} KV heads, {kg} nuggets + {mg} local rows; "
                                        "algorithmic bytes count every K/V row once")
     out["gqa_decode_64_heads_8_kv_heads"] = r
+
+    def shared_rows(Bs, Hs, Hkvs, qs, ks_, ms_, tid0):
+        """Several query vectors per K/V row at another shape: 4 rotating sets, the workspace the grouped kernel asks for."""
+        sets = []
+        for s_ in range(4):
+            mk = lambda tid, n, h: W.normal(wl.seed, tid0 + 8 * s_ + tid, (n, h, wl.d_h), 1.0, wl.dtype, dev)
+            sets.append(dict(Q=mk(0, Bs * qs, Hs), Kn=mk(1, Bs * ks_, Hkvs), Vn=mk(2, Bs * ks_, Hkvs), Kl=mk(3, Bs * ms_, Hkvs),
+                             Vl=mk(4, Bs * ms_, Hkvs)))
+        cq, ck, cl = W.cumulative([qs] * Bs, dev), W.cumulative([ks_] * Bs, dev), W.cumulative([ms_] * Bs, dev)
+        Os = torch.empty_like(sets[0]["Q"])
+        need = D.dodo_nugget_attention_workspace_bytes_grouped(Bs, Hs, Hkvs, wl.d_h, qs, ks_, ms_, D.BF16)
+        wsb = torch.zeros(max(need, 16), dtype=torch.uint8, device=dev)
+        a_, m2 = clock.batched([lambda t_=t_: D.dodo_nugget_attention(t_["Q"], t_["Kn"], t_["Vn"], t_["Kl"], t_["Vl"], cq, ck, cl,
+                                                                      qs, ks_, ms_, scale, D.TOKEN_MAJOR, Os, ws=wsb)
+                                for t_ in sets])
+        row = hbm_row(a_, work_attention([qs] * Bs, [ks_] * Bs, [ms_] * Bs, Hs, Hkvs, wl.d_h))
+        row.update(min_us=round(m2, 2))
+        return row
+    r = shared_rows(2, 64, 8, 1, 3277, 1089, 3200)
+    r["note"] = "batch 2, 64 query heads over 8 KV heads, 3277 nuggets + 1089 local rows: the keys of a (sequence, KV head) pair are split over 16 workgroups; latency-bound (36 MB)"
+    out["gqa_decode_long_context_batch_2"] = r
+    r = shared_rows(64, 32, 32, 4, kg, mg, 3300)
+    r["note"] = "batch 64, multi-head attention, query blocks of 4 rows (each row of a head reads the same K/V rows)"
+    out["query_block_of_4_rows"] = r
     # query-block attention with 64-wide heads (64 heads x 64: the same flop count as the 32 x 128 workload)
     mk = lambda tid, n, h: W.normal(wl.seed, 3100 + tid, (n, h, 64), 1.0, wl.dtype, dev)
     Q6, Kn6, Vn6 = mk(0, sum(wl.q_lens), 64), mk(1, Kt, 64), mk(2, Kt, 64)
