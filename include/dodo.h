@@ -210,7 +210,7 @@ size_t dodo_nugget_attention_workspace_bytes_grouped(int32_t B, int32_t H, int32
  * (query-block kernel); smaller max_q and all fp32 inputs use the bandwidth-
  * bound split-K kernel, whose last split combines the partials in split order.  Both are deterministic.
  * Supported: d_h in {64, 128}, fp32 or bf16.  When 4 to 32 query vectors read the same K/V rows -- (H / H_kv) *
- * max_q of them: grouped-query heads, a small query block, or both -- and the inputs are bf16 with d_h = 128, a
+ * max_q of them: grouped-query heads, a small query block, or both -- and the inputs are bf16, a
  * third kernel reads every K/V row once for all of them and multiplies on the matrix cores (fp32 accumulation,
  * partial results merged in a fixed order: deterministic for a given workspace size).  Otherwise the split-K kernel
  * serves the query heads of a KV head from one workgroup when there are enough (sequence, row, KV head) triples to

@@ -1,6 +1,7 @@
 // Nugget attention for a few query vectors that read the same K/V rows, on the matrix cores (Eq. 13 / Eq. 9 of
 // the Dodo paper with q_b small): the G query heads of one KV head (grouped-query attention) times the rows of a
-// small query block -- at most 32 vectors, the width of one MFMA tile.  bf16, d_h = 128.
+// small query block -- at most 32 vectors, the width of one MFMA tile.  bf16, d_h = 128 or 64 (a template
+// parameter: tile sizes, LDS layout and fragment counts follow from it).
 //
 // The work is bandwidth-bound (every K and V row is read once, and serves all the vectors), so the layout is built
 // around keeping loads in flight: a workgroup owns one (sequence, KV head, split); each of its wavefronts streams
@@ -25,17 +26,33 @@ typedef __attribute__((ext_vector_type(8))) float floatx8;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int kDH = 128;
-constexpr int kRowBytes = kDH * 2;
-constexpr int kKeys = 32;                          // keys per tile
-constexpr int kTensorBytes = kKeys * kRowBytes;    // K or V part of a stage: 8 KiB
-constexpr int kStageBytes = 2 * kTensorBytes;      // 16 KiB
-constexpr int kWaveLds = 2 * kStageBytes;          // two stages per wavefront: 32 KiB
-constexpr int kLoadsPerTile = 2 * (kKeys / 4);     // 1 KiB (4 rows) per instruction, K and V
-constexpr int kMaxVectors = 32;
-constexpr int kPartStride = kDH + 4;               // floats per vector of a partial in LDS (528 B: spreads the banks)
-constexpr int kPartBytes = (kMaxVectors * kPartStride + 2 * kMaxVectors) * 4;  // a wavefront's partial: O, then m and l
-static_assert(kPartBytes + (kMaxVectors * 63 + 3 * kMaxVectors) * 4 <= kWaveLds, "the merge's staging fits behind the partials");
+constexpr int kKeys = 32;        // keys per tile
+constexpr int kMaxVectors = 32;  // query vectors per workgroup: the N side of one MFMA tile
+// What follows from the head size DH (128 or 64)
+template <int DH>
+struct GroupDims {
+  static constexpr int kRowBytes = DH * 2;
+  static constexpr int kP = kRowBytes / 16;           // 16-byte pieces of a row
+  static constexpr int kPLog2 = DH == 128 ? 4 : 3;
+  // rows of 128 bytes cover half of the LDS banks: two consecutive rows sit side by side and the swizzles take the
+  // row's index from bit 1 on; rows of 256 bytes use the index as it is
+  static constexpr int kRowShift = DH == 128 ? 0 : 1;
+  static constexpr int kNCB = DH / 32;                // 32-channel blocks of O^T = 64-byte granules of a V row
+  static constexpr int kKSteps = DH / 16;             // MFMAs of S^T per tile
+  static constexpr int kRowsPerInstr = 64 / kP;       // a load instruction brings 1 KiB: 4 or 8 rows
+  static constexpr int kInstrPerTensor = kKeys / kRowsPerInstr;
+  static constexpr int kTensorBytes = kKeys * kRowBytes;  // K or V part of a stage: 8 or 4 KiB
+  static constexpr int kStageBytes = 2 * kTensorBytes;
+  static constexpr int kWaveLds = 2 * kStageBytes;        // two stages per wavefront: 32 or 16 KiB
+  static constexpr int kLoadsPerTile = 2 * kInstrPerTensor;
+  static constexpr int kPartStride = DH + 4;              // floats per vector of a partial in LDS (spreads the banks)
+  static constexpr int kPartBytes = (kMaxVectors * kPartStride + 2 * kMaxVectors) * 4;  // a partial: O, then m and l
+  // splits of the keys of a (sequence, KV head) pair over workgroups: the last split's staging (one float per
+  // vector and other split in each of the first two wavefronts' regions, behind the partials) bounds their number
+  static constexpr int kMaxSplits = DH == 128 ? 64 : 32;
+  static_assert(kPartBytes + (kMaxVectors * (kMaxSplits - 1) + 3 * kMaxVectors) * 4 <= kWaveLds,
+                "the merge's staging fits behind the partials");
+};
 constexpr float kNegInf = -__builtin_inff();
 
 __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }  // exp2(-inf) = 0
@@ -46,12 +63,12 @@ constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); } 
 // operands (k-step t covers keys 16t .. 16t+15).
 // The exponent offset m_run of a vector is moved (and its sum and output accumulators rescaled) only when the tile's
 // maximum exceeds it by more than kSlack: the result does not depend on the offset, the weights stay below
-// 2^kSlack, and after the first tiles of a vector the 64 accumulators are hardly ever touched again (the rescale is
+// 2^kSlack, and after the first tiles of a vector the output accumulators are hardly ever touched again (the rescale is
 // a wavefront-uniform branch: taken if any vector of the wavefront moves).
 constexpr float kSlack = 8.f;
-template <bool MASK>
+template <bool MASK, int NCB>
 __device__ __forceinline__ void softmax_tile32(floatx16& acc, int limit, int g, float scale_log2e, float& m_run,
-                                               float& l_run, floatx16 (&acc_o)[4], bf16x8 (&pf)[2]) {
+                                               float& l_run, floatx16 (&acc_o)[NCB], bf16x8 (&pf)[2]) {
   float tmax = kNegInf;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
@@ -70,7 +87,7 @@ __device__ __forceinline__ void softmax_tile32(floatx16& acc, int limit, int g, 
     const float alpha = exp2_hw(m_run - ((m_new == kNegInf) ? 0.f : m_new));  // 1 where nothing moves, 0 from -inf
     l_run *= alpha;
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
+    for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc_o[cb][v] *= alpha;
     m_run = m_new;
@@ -91,7 +108,7 @@ __device__ __forceinline__ void softmax_tile32(floatx16& acc, int limit, int g, 
 }
 
 // NWV wavefronts per workgroup.  Grid: (KV head, sequence, split).
-template <int NWV>
+template <int DH, int NWV>
 __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
@@ -99,6 +116,10 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     const int32_t* __restrict__ loc_len, int H, int H_kv, int G, FastDiv div_G, int max_q, int nsplit,
     int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse, float* __restrict__ ws, uint32_t* __restrict__ flags) {
+  using GD = GroupDims<DH>;
+  constexpr int kDH = DH, kRowBytes = GD::kRowBytes, kP = GD::kP, kRowShift = GD::kRowShift, kNCB = GD::kNCB;
+  constexpr int kTensorBytes = GD::kTensorBytes, kStageBytes = GD::kStageBytes, kWaveLds = GD::kWaveLds;
+  constexpr int kPartStride = GD::kPartStride, kPartBytes = GD::kPartBytes, kMaxSplits = GD::kMaxSplits;
   constexpr int kThreads = NWV * kWave;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int kvh = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
@@ -150,20 +171,25 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
   const uint16_t* locK = Kl + (static_cast<int64_t>(l0) * H_kv + kvh) * kDH;
   const uint16_t* locV = Vl + (static_cast<int64_t>(l0) * H_kv + kvh) * kDH;
 
-  // Tile loads: instruction u brings rows 4u .. 4u+3 (1 KiB) of K and of V; the lane at LDS position (row, pos)
-  // fetches the 16-byte piece that the swizzle stores there (K: pos ^ (row & 15); V: 64-byte granule
-  // (pos / 4) ^ (row & 3)).  Rows past the end of the region re-read its last row (finite data, masked later).
+  // Tile loads: an instruction brings 1 KiB (4 or 8 rows) of K or of V; the lane at LDS position (row, pos) fetches
+  // the 16-byte piece that the swizzle stores there (K: pos ^ r; V: 64-byte granule (pos / 4) ^ r; r = row >>
+  // kRowShift, taken modulo the number of pieces or granules).  Rows past the end of the region re-read its last row
+  // (finite data, masked later).
   char* const lds_w = lds + wave * kWaveLds;
   const uint32_t lds_w_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void*)lds_w));
-  const int ld_row0 = lane >> 4;
-  const uint32_t ld_pos = lane & 15;
-  // Whole tiles (the usual case): the row term of instruction u, 4u * stride, goes into the scalar base, so the
-  // lanes' offsets are loop constants (the K piece depends on u % 4 only, the V piece not at all).
+  const int ld_row0 = lane >> GD::kPLog2;
+  const uint32_t ld_pos = lane & (kP - 1);
+  auto k_piece_of = [&](int row) -> uint32_t { return (ld_pos ^ ((row >> kRowShift) & (kP - 1))) * 16u; };
+  auto v_piece_of = [&](int row) -> uint32_t {
+    return ((((ld_pos >> 2) ^ ((row >> kRowShift) & (kNCB - 1))) << 2) | (ld_pos & 3)) * 16u;
+  };
+  // Whole tiles (the usual case): the row term of instruction u goes into the scalar base, so the lanes' offsets
+  // are loop constants (the V piece is the same for all of a lane's rows).
   const uint32_t nug_sb = static_cast<uint32_t>(nug_tok_stride) * 2u, loc_sb = static_cast<uint32_t>(loc_stride) * 2u;
-  const uint32_t v_piece0 = ((((ld_pos >> 2) ^ (ld_row0 & 3)) << 2) | (ld_pos & 3)) * 16u;
-  uint32_t k_piece0[4];
+  const uint32_t v_piece0 = v_piece_of(ld_row0);
+  uint32_t k_piece0[GD::kInstrPerTensor];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) k_piece0[u] = (ld_pos ^ ((ld_row0 + 4 * u) & 15)) * 16u;
+  for (int u = 0; u < GD::kInstrPerTensor; ++u) k_piece0[u] = k_piece_of(ld_row0 + GD::kRowsPerInstr * u);
   auto issue_tile = [&](int tile, int stage) {
     const bool nug = tile < n_nug_tiles;
     const int base = nug ? tile * kKeys : (tile - n_nug_tiles) * kKeys;
@@ -176,27 +202,26 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     if (cnt == kKeys) {
       const uint32_t row_term = static_cast<uint32_t>(ld_row0) * stride_bytes;
 #pragma unroll
-      for (int u = 0; u < kKeys / 4; ++u) {
-        dma16_uniform(kbase + 4 * u * stride, row_term + k_piece0[u & 3], __builtin_amdgcn_readfirstlane(dst + u * 1024));
-        dma16_uniform(vbase + 4 * u * stride, row_term + v_piece0,
+      for (int u = 0; u < GD::kInstrPerTensor; ++u) {
+        dma16_uniform(kbase + GD::kRowsPerInstr * u * stride, row_term + k_piece0[u],
+                      __builtin_amdgcn_readfirstlane(dst + u * 1024));
+        dma16_uniform(vbase + GD::kRowsPerInstr * u * stride, row_term + v_piece0,
                       __builtin_amdgcn_readfirstlane(dst + kTensorBytes + u * 1024));
       }
       return;
     }
 #pragma unroll
-    for (int u = 0; u < kKeys / 4; ++u) {
-      const int row = ld_row0 + 4 * u;
+    for (int u = 0; u < GD::kInstrPerTensor; ++u) {
+      const int row = ld_row0 + GD::kRowsPerInstr * u;
       const uint32_t roff = static_cast<uint32_t>(min(row, cnt - 1)) * stride_bytes;
-      const uint32_t k_piece = (ld_pos ^ (row & 15)) * 16u;
-      const uint32_t v_piece = ((((ld_pos >> 2) ^ (row & 3)) << 2) | (ld_pos & 3)) * 16u;
-      dma16_uniform(kbase, roff + k_piece, __builtin_amdgcn_readfirstlane(dst + u * 1024));
-      dma16_uniform(vbase, roff + v_piece, __builtin_amdgcn_readfirstlane(dst + kTensorBytes + u * 1024));
+      dma16_uniform(kbase, roff + k_piece_of(row), __builtin_amdgcn_readfirstlane(dst + u * 1024));
+      dma16_uniform(vbase, roff + v_piece_of(row), __builtin_amdgcn_readfirstlane(dst + kTensorBytes + u * 1024));
     }
   };
 
-  floatx16 acc_o[4];
+  floatx16 acc_o[kNCB];
 #pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
+  for (int cb = 0; cb < kNCB; ++cb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc_o[cb][v] = 0.f;
   float m_run = kNegInf, l_run = 0.f;
@@ -217,23 +242,23 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     for (int ds = 0; ds < kDH / 16; ++ds) asm volatile("" ::"v"(qf[ds]));
     for (int n = 0; n < n_mine; ++n) {
       const int tile = first + n * NWV, stage = n & 1;
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerTile));  // this tile has landed, the next one is in flight
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(GD::kLoadsPerTile));  // this tile has landed, the next one is in flight
       const char* kbuf = lds_w + stage * kStageBytes;
       const char* vbuf = kbuf + kTensorBytes;
       // all fragment reads of the tile are requested up front
-      bf16x8 kf[kDH / 16], vt[2][4];
+      bf16x8 kf[kDH / 16], vt[2][kNCB];
 #pragma unroll
       for (int ds = 0; ds < kDH / 16; ++ds)
-        kf[ds] = *reinterpret_cast<const bf16x8*>(kbuf + j * kRowBytes + (((2 * ds + g) ^ (j & 15)) << 4));
+        kf[ds] = *reinterpret_cast<const bf16x8*>(kbuf + j * kRowBytes + (((2 * ds + g) ^ ((j >> kRowShift) & (kP - 1))) << 4));
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
+        for (int cb = 0; cb < kNCB; ++cb) {
           shortx4 a[2];
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
             const int r = 16 * t + 8 * e + v_r;
-            const char* p = vbuf + r * kRowBytes + ((cb ^ (r & 3)) << 6) + v_in;
+            const char* p = vbuf + r * kRowBytes + ((cb ^ ((r >> kRowShift) & (kNCB - 1))) << 6) + v_in;
             a[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
           }
           vt[t][cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a[0], a[1], 0, 1, 2, 3, 4, 5, 6, 7));
@@ -254,14 +279,14 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
       const int limit = nug ? k_b - base : my_vis - base;  // keys [0, limit) of the tile are visible to this lane's vector
       bf16x8 pf[2];
       if (__all(limit >= kKeys)) {
-        softmax_tile32<false>(acc_s, limit, g, scale_log2e, m_run, l_run, acc_o, pf);
+        softmax_tile32<false, kNCB>(acc_s, limit, g, scale_log2e, m_run, l_run, acc_o, pf);
       } else {
-        softmax_tile32<true>(acc_s, limit, g, scale_log2e, m_run, l_run, acc_o, pf);
+        softmax_tile32<true, kNCB>(acc_s, limit, g, scale_log2e, m_run, l_run, acc_o, pf);
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
+        for (int cb = 0; cb < kNCB; ++cb)
           acc_o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[t][cb], pf[t], acc_o[cb], 0, 0, 0);
     }
   }
@@ -273,7 +298,7 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     float* part = reinterpret_cast<float*>(lds_w);
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
+    for (int cb = 0; cb < kNCB; ++cb)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd)
         *reinterpret_cast<float4*>(part + j * kPartStride + 32 * cb + 8 * qd + 4 * g) =
@@ -323,7 +348,7 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     return;
   }
 
-  // ---- several splits: partial records [m, s, o[0..128)] per (sequence, row, head, split); the last split
+  // ---- several splits: partial records [m, s, o[0..DH)] per (sequence, row, head, split); the last split
   // waits for the others' flags and merges in split order (device-scope accesses, as in the split-K kernel) ----
   const int64_t b_row0 = static_cast<int64_t>(b) * max_q;
   if (split + 1 < nsplit) {
@@ -353,10 +378,10 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
   // ---- the last split ----
   // (1) All flags are polled at once (one per thread and round: a device-scope load is a round trip past the
   // XCD's L2); the thread that sees the flag of (vector, split) fetches that record's m and s right away.  They go
-  // to LDS behind the wavefronts' partials (room for 32 vectors x 63 splits in each of the first two regions).
+  // to LDS behind the wavefronts' partials (room for 32 vectors x kMaxSplits - 1 splits in each of the first two regions).
   float* const st_m = reinterpret_cast<float*>(lds + kPartBytes);
   float* const st_s = reinterpret_cast<float*>(lds + kWaveLds + kPartBytes);
-  float* const tot_s = st_m + kMaxVectors * 63;  // per vector: the total sum and the weight of the own partial
+  float* const tot_s = st_m + kMaxVectors * (kMaxSplits - 1);  // per vector: the total sum and the weight of the own partial
   float* const own_w = tot_s + kMaxVectors;
   float* const tot_m = own_w + kMaxVectors;
   const int ns1 = nsplit - 1;
@@ -466,15 +491,15 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
   }
 }
 
-template <int NWV>
+template <int DH, int NWV>
 int launch_nwv(const AttnParams& p, int nsplit, uint32_t* flags) {
-  constexpr int kLds = NWV * kWaveLds;
-  const void* kernel = reinterpret_cast<const void*>(&group_attention_kernel<NWV>);
+  constexpr int kLds = NWV * GroupDims<DH>::kWaveLds;
+  const void* kernel = reinterpret_cast<const void*>(&group_attention_kernel<DH, NWV>);
   const int rc = allow_dynamic_lds(kernel, kLds);
   if (rc != DODO_OK) return rc;
   const int G = p.H / p.H_kv;
   const dim3 grid(static_cast<unsigned>(p.H_kv), static_cast<unsigned>(p.B), static_cast<unsigned>(nsplit));
-  hipLaunchKernelGGL((group_attention_kernel<NWV>), grid, dim3(NWV * kWave), kLds, p.stream,
+  hipLaunchKernelGGL((group_attention_kernel<DH, NWV>), grid, dim3(NWV * kWave), kLds, p.stream,
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
                      static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.H,
@@ -486,47 +511,49 @@ int launch_nwv(const AttnParams& p, int nsplit, uint32_t* flags) {
 
 constexpr int kWantedWorkgroups = 512;  // two per compute unit of the 256
 
-// Splits for these bounds: enough workgroups for two per compute unit, at least eight tiles per split, and no
-// more than the caller's workspace has records for (none if it is not 8-byte aligned: records are read in 8-byte words).
+// Splits for these bounds: enough workgroups for two per compute unit (one of four wavefronts where that takes
+// splitting), at least eight tiles per split, and no more than the caller's workspace has records for (none if it
+// is not 8-byte aligned: records are read in 8-byte words).
 int group_split_count(const AttnParams& p) {
   const int64_t pairs = static_cast<int64_t>(p.B) * p.H_kv;
   const int64_t rows = static_cast<int64_t>(p.max_k) + p.max_local;
-  // (fewer than a workgroup per compute unit without splitting: one of four wavefronts per unit is the aim)
   int64_t n = pairs >= kWantedWorkgroups / 2 ? (kWantedWorkgroups + pairs - 1) / pairs
                                              : (kWantedWorkgroups / 2 + pairs - 1) / pairs;
   const int64_t room = rows / (8 * kKeys);
   if (n > room) n = room;
-  if (n > 64) n = 64;
-  const int64_t per_split = static_cast<int64_t>(p.B) * p.max_q * p.H * (partial_floats<kDH>() + 1) * sizeof(float);
-  const bool usable = p.ws != nullptr && (reinterpret_cast<uintptr_t>(p.ws) & 7) == 0;
-  const int64_t fit = usable ? static_cast<int64_t>(p.ws_bytes / per_split) : 0;
-  if (p.ws_flags != nullptr) {
-    // records and flags in separate regions of ws_slots entries each
-    if (n > p.ws_slots / (static_cast<int64_t>(p.B) * p.max_q * p.H)) n = p.ws_slots / (static_cast<int64_t>(p.B) * p.max_q * p.H);
-  } else if (n > fit) {
-    n = fit;
+  const int64_t most = p.d_h == 128 ? GroupDims<128>::kMaxSplits : GroupDims<64>::kMaxSplits;
+  if (n > most) n = most;
+  const int64_t records_per_split = static_cast<int64_t>(p.B) * p.max_q * p.H;
+  int64_t fit;
+  if (p.ws_flags != nullptr) {  // records and flags in separate regions of ws_slots entries each
+    fit = p.ws_slots / records_per_split;
+  } else {  // one region: records of d_h + 2 floats, then a flag each
+    const bool usable = p.ws != nullptr && (reinterpret_cast<uintptr_t>(p.ws) & 7) == 0;
+    fit = usable ? static_cast<int64_t>(p.ws_bytes / (records_per_split * (p.d_h + 3) * sizeof(float))) : 0;
   }
+  if (n > fit) n = fit;
   return n < 1 ? 1 : static_cast<int>(n);
 }
 
 }  // namespace
 
-size_t group_workspace_bytes(int32_t B, int32_t H, int32_t H_kv, int32_t max_q, int32_t max_k, int32_t max_local) {
+size_t group_workspace_bytes(int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
+                             int32_t max_local) {
   AttnParams p{};
-  p.B = B; p.H = H; p.H_kv = H_kv; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
+  p.B = B; p.H = H; p.H_kv = H_kv; p.d_h = d_h; p.max_q = max_q; p.max_k = max_k; p.max_local = max_local;
   p.ws = &p;  // any non-null address: the count is not limited by a workspace here
   p.ws_bytes = ~static_cast<size_t>(0);
   const int n = group_split_count(p);
-  return n <= 1 ? 0 : static_cast<size_t>(B) * max_q * H * n * (partial_floats<kDH>() + 1) * sizeof(float);
+  return n <= 1 ? 0 : static_cast<size_t>(B) * max_q * H * n * (d_h + 3) * sizeof(float);
 }
 
 bool group_attention_applies(const AttnParams& p) {
-  if (p.dtype != DODO_DTYPE_BF16 || p.d_h != kDH || p.nug_idx != nullptr) return false;
+  if (p.dtype != DODO_DTYPE_BF16 || (p.d_h != 128 && p.d_h != 64) || p.nug_idx != nullptr) return false;
   const int64_t vectors = static_cast<int64_t>(p.H / p.H_kv) * p.max_q;
   if (vectors < 4 || vectors > kMaxVectors) return false;
   if (p.B > 65535) return false;  // second grid dimension
   // a row number times a stride in bytes is kept in 32 bits
-  if (p.nug_tok_stride * 2 * kKeys > 0xffffffffLL || static_cast<int64_t>(p.H_kv) * kDH * 2 * kKeys > 0xffffffffLL)
+  if (p.nug_tok_stride * 2 * kKeys > 0xffffffffLL || static_cast<int64_t>(p.H_kv) * p.d_h * 2 * kKeys > 0xffffffffLL)
     return false;
   // at least a workgroup for every other compute unit: with fewer (a small batch and a workspace too small to
   // split further), the split-K kernel's wider workgroups keep more loads in flight
@@ -538,10 +565,11 @@ int launch_group_attention(const AttnParams& p) {
   uint32_t* flags = p.ws_flags != nullptr
                         ? static_cast<uint32_t*>(p.ws_flags)
                         : reinterpret_cast<uint32_t*>(static_cast<float*>(p.ws) +
-                                                      static_cast<int64_t>(p.B) * p.max_q * p.H * nsplit * partial_floats<kDH>());
+                                                      static_cast<int64_t>(p.B) * p.max_q * p.H * nsplit * (p.d_h + 2));
   // two workgroups of two wavefronts per compute unit when there are that many; else one of four
-  if (static_cast<int64_t>(p.B) * p.H_kv * nsplit >= 2 * compute_units()) return launch_nwv<2>(p, nsplit, flags);
-  return launch_nwv<4>(p, nsplit, flags);
+  const bool two = static_cast<int64_t>(p.B) * p.H_kv * nsplit >= 2 * compute_units();
+  if (p.d_h == 128) return two ? launch_nwv<128, 2>(p, nsplit, flags) : launch_nwv<128, 4>(p, nsplit, flags);
+  return two ? launch_nwv<64, 2>(p, nsplit, flags) : launch_nwv<64, 4>(p, nsplit, flags);
 }
 
 }  // namespace dodo

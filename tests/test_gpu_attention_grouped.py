@@ -1,5 +1,5 @@
 """GPU parity: the matrix-core kernel for a few query vectors per K/V row (grouped-query heads and small query
-blocks, bf16, d_h = 128) against the oracle, through dodo_nugget_attention and its variants."""
+blocks, bf16, d_h = 128 or 64) against the oracle, through dodo_nugget_attention and its variants."""
 import numpy as np
 import pytest
 import torch
@@ -18,9 +18,9 @@ def D():
     return D
 
 
-def _check(D, seed, q_lens, k_lens, m_lens, H, H_kv, layout=0, ws="wanted", scale=None):
-    host, t = make_attention_case(seed, q_lens, k_lens, m_lens, H, H_kv, 128, BF, dev())
-    scale = default_scale(128) if scale is None else scale
+def _check(D, seed, q_lens, k_lens, m_lens, H, H_kv, layout=0, ws="wanted", scale=None, d_h=128):
+    host, t = make_attention_case(seed, q_lens, k_lens, m_lens, H, H_kv, d_h, BF, dev())
+    scale = default_scale(d_h) if scale is None else scale
     B, mq, mk, mm = len(q_lens), max(q_lens), max(k_lens), max(m_lens)
     O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
                                       host["cu_nuggets"], host["cu_local"], scale)
@@ -29,9 +29,9 @@ def _check(D, seed, q_lens, k_lens, m_lens, H, H_kv, layout=0, ws="wanted", scal
         Kn, Vn = Kn.transpose(0, 1).contiguous(), Vn.transpose(0, 1).contiguous()
     O, lse = nan_outputs(t["Q"], H)
     if ws == "wanted":  # as much as the kernel would like to have
-        need = D.dodo_nugget_attention_workspace_bytes_grouped(B, H, H_kv, 128, mq, mk, mm, D.BF16)
+        need = D.dodo_nugget_attention_workspace_bytes_grouped(B, H, H_kv, d_h, mq, mk, mm, D.BF16)
     elif ws == "plain":  # what the query without H_kv asks for: fewer splits, same result to the tolerance
-        need = D.dodo_nugget_attention_workspace_bytes(B, H, 128, mq, mk, mm, D.BF16)
+        need = D.dodo_nugget_attention_workspace_bytes(B, H, d_h, mq, mk, mm, D.BF16)
     else:
         need = int(ws)
     buf = torch.zeros(max(need, 16), dtype=torch.uint8, device=dev()) if need else None
@@ -85,6 +85,25 @@ def test_small_query_blocks_share_their_keys(D):
     _check(D, 722, q8, k_lens, m_lens, 32, 32)       # multi-head attention: 8 rows of one head
     _check(D, 723, q8, k_lens, [0] * B, 16, 4)       # nuggets only
     _check(D, 724, q8, [0] * B, [max(m, 1) for m in m_lens], 16, 4)  # local rows only
+
+
+def test_heads_of_64_channels(D):
+    # the same kernel with half the channels: other tile sizes, LDS swizzles and fragment counts
+    rng = np.random.default_rng(12)
+    B = 70
+    k_lens = [int(v) for v in rng.integers(0, 150, B)]
+    m_lens = [int(v) for v in rng.integers(1, 70, B)]
+    k_lens[3], m_lens[3] = 0, 1
+    k_lens[4], m_lens[4] = 31, 33
+    _check(D, 770, [1] * B, k_lens, m_lens, 32, 8, d_h=64)
+    _check(D, 771, [1] * B, k_lens, m_lens, 40, 8, d_h=64, layout=1)
+    q_lens = [int(v) for v in rng.integers(0, 5, B)]
+    _check(D, 772, q_lens, k_lens, m_lens, 32, 4, d_h=64)
+    _check(D, 773, [int(v) for v in rng.integers(1, 9, B)], k_lens, m_lens, 16, 16, d_h=64)
+    # split over workgroups (two and four wavefronts each)
+    _check(D, 774, [1, 1], [3277, 1500], [1089, 1025], 64, 8, d_h=64)
+    _check(D, 775, [1] * 5, [205, 410, 333, 1, 0], [257, 257, 40, 3, 5], 64, 8, d_h=64)
+    _check(D, 776, [2] * 3, [2000, 37, 900], [300, 700, 31], 40, 8, d_h=64)
 
 
 def test_softmax_scale_and_large_logits(D):
