@@ -1,5 +1,5 @@
-"""The whole step (score, select, gather, block attention, decode token with the split-K workspace) is captured into
-a HIP graph and replayed: every replay, with eager work and synchronisations in between, must reproduce the eager
+"""The whole step (score, select, gather, block attention, decode token with the split-K workspace, a small query
+block through the entry point that allocates nothing) is captured into a HIP graph and replayed: every replay, with eager work and synchronisations in between, must reproduce the eager
 results bit for bit (the library records kernel launches only: no memset nodes, no allocation, no host read-back)."""
 import pytest
 import torch
@@ -33,6 +33,11 @@ def test_step_replays_from_a_graph():
     need = D.dodo_nugget_attention_workspace_bytes(B, wl.H, wl.d_h, 1, max_k, m_dec, D.BF16)
     assert need > 0
     ws = torch.zeros(need, dtype=torch.uint8, device=dev())
+    # four query rows per sequence over the same rows: the matrix-core kernel for several vectors per K/V row, split
+    # over workgroups, with its partial records and flags in the library's own buffer
+    Q4 = W.normal(wl.seed, 53, (B * 4, wl.H, wl.d_h), 1.0, wl.dtype, dev())
+    cu_q4 = W.cumulative([4] * B, dev())
+    O4 = torch.empty_like(Q4)
 
     def step():
         D.dodo_score(g["hidden"], g["w"], 0.0, scores)
@@ -41,10 +46,11 @@ def test_step_replays_from_a_graph():
         D.dodo_nugget_attention(g["Q"], Kn, Vn, g["Kl"], g["Vl"], g["cu_q"], cu_k, g["cu_local"], max(wl.q_lens), max_k,
                                 max(wl.local_lens), scale, D.TOKEN_MAJOR, O)
         D.dodo_nugget_attention(Qd, Kn, Vn, Kld, Vld, cu_qd, cu_k, cu_ld, 1, max_k, m_dec, scale, D.TOKEN_MAJOR, Od, ws=ws)
+        D.dodo_nugget_attention_noalloc(Q4, Kn, Vn, Kld, Vld, cu_q4, cu_k, cu_ld, 4, max_k, m_dec, scale, D.TOKEN_MAJOR, O4)
 
     step()
     torch.cuda.synchronize()
-    want = [t.clone() for t in (scores, idx, Kn, Vn, O, Od)]
+    want = [t.clone() for t in (scores, idx, Kn, Vn, O, Od, O4)]
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -54,12 +60,12 @@ def test_step_replays_from_a_graph():
     with torch.cuda.graph(graph):
         step()
     for rep in range(4):
-        for t in (scores, idx, Kn, Vn, O, Od):
+        for t in (scores, idx, Kn, Vn, O, Od, O4):
             t.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((scores, idx, Kn, Vn, O, Od), want):
+        for got, ref in zip((scores, idx, Kn, Vn, O, Od, O4), want):
             assert torch.equal(got, ref), f"replay {rep} differs from the eager result"
         step()  # eager work between the replays
         torch.cuda.synchronize()
