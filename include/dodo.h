@@ -209,10 +209,11 @@ size_t dodo_nugget_attention_workspace_bytes_grouped(int32_t B, int32_t H, int32
  * multiplied on the matrix cores with fp32 accumulation when max_q >= 16
  * (query-block kernel); smaller max_q and all fp32 inputs use the bandwidth-
  * bound split-K kernel, whose last split combines the partials in split order.  Both are deterministic.
- * Supported: d_h in {64, 128}, fp32 or bf16.  When 4 to 32 query vectors read the same K/V rows -- (H / H_kv) *
+ * Supported: d_h in {64, 128}, fp32 or bf16.  When 4 or more query vectors read the same K/V rows -- (H / H_kv) *
  * max_q of them: grouped-query heads, a small query block, or both -- and the inputs are bf16, a
- * third kernel reads every K/V row once for all of them and multiplies on the matrix cores (fp32 accumulation,
- * partial results merged in a fixed order: deterministic for a given workspace size).  Otherwise the split-K kernel
+ * third kernel reads every K/V row once for up to 32 of them and multiplies on the matrix cores (fp32 accumulation,
+ * partial results merged in a fixed order: deterministic for a given workspace size); more vectors take up to four
+ * passes over the keys, each for as many query rows as fill 32 vectors.  Otherwise the split-K kernel
  * serves the query heads of a KV head from one workgroup when there are enough (sequence, row, KV head) triples to
  * fill the GPU that way.
  * The split-K kernel takes at most 65535 (sequence, query-row group) pairs per call (B * max_q at most, fewer when

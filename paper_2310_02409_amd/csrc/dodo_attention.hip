@@ -32,8 +32,7 @@ extern "C" size_t dodo_nugget_attention_workspace_bytes_grouped(int32_t B, int32
   const size_t plain = dodo_nugget_attention_workspace_bytes(B, H, d_h, max_q, max_k, max_local, dtype);
   if (B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv != 0 || max_q <= 0 || max_k < 0 || max_local < 0) return plain;
   if (use_block_kernel(dtype, d_h, max_q) || dtype != DODO_DTYPE_BF16 || (d_h != 128 && d_h != 64)) return plain;
-  const int64_t vectors = static_cast<int64_t>(H / H_kv) * max_q;  // query vectors that share their K/V rows
-  if (vectors < 4 || vectors > 32) return plain;
+  if (group_launches(H, H_kv, max_q) == 0) return plain;  // too few query vectors share their K/V rows, or too many
   const size_t grouped = group_workspace_bytes(B, H, H_kv, d_h, max_q, max_k, max_local);
   return grouped > plain ? grouped : plain;
 }

@@ -41,11 +41,12 @@ size_t splitk_workspace_bytes(int32_t B, int32_t H, int32_t d_h, int32_t max_q, 
 
 // fp32 or bf16, d_h in {64,128}, any max_q: one workgroup per (query row, head, split).
 int launch_splitk_attention(const AttnParams& p);
-// bf16, d_h in {64,128}, 4 to 32 query vectors per KV head and sequence ((H / H_kv) * max_q): MFMA kernel that reads
-// every K/V row once for all of them.  group_attention_applies says whether it takes the call.
+// bf16, d_h in {64,128}, at least 4 query vectors per KV head and sequence ((H / H_kv) * max_q): MFMA kernel that reads
+// every K/V row once for up to 32 of them (more: up to four passes).  group_attention_applies says whether it takes the call.
 // It splits the keys of a (sequence, KV head) pair as far as the caller's workspace has room for records;
 // group_workspace_bytes is the size that lets it split as far as it would like to (0: no split wanted).
 bool group_attention_applies(const AttnParams& p);
+int group_launches(int32_t H, int32_t H_kv, int32_t max_q);  // 0: not for these head counts and this max_q
 size_t group_workspace_bytes(int32_t B, int32_t H, int32_t H_kv, int32_t d_h, int32_t max_q, int32_t max_k,
                              int32_t max_local);
 int launch_group_attention(const AttnParams& p);

@@ -113,7 +113,8 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kn, const uint16_t* __restrict__ Vn,
     const uint16_t* __restrict__ Kl, const uint16_t* __restrict__ Vl, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_nuggets, const int32_t* __restrict__ nug_len, const int32_t* __restrict__ cu_local,
-    const int32_t* __restrict__ loc_len, int H, int H_kv, int G, FastDiv div_G, int max_q, int nsplit,
+    const int32_t* __restrict__ loc_len, int H, int H_kv, int G, FastDiv div_G, int max_q, int row0, int rows_per,
+    int nsplit,
     int64_t nug_tok_stride, int64_t nug_head_stride, float scale_log2e, uint16_t* __restrict__ O,
     float* __restrict__ lse, float* __restrict__ ws, uint32_t* __restrict__ flags) {
   using GD = GroupDims<DH>;
@@ -130,25 +131,29 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
   const int k0 = cu_nuggets[b], k_end = *k_end_p;
   const int l0 = cu_local[b], l_end = *l_end_p;
   asm volatile("" ::"s"(q0), "s"(q_end), "s"(k0), "s"(k_end), "s"(l0), "s"(l_end));  // one round of loads
-  const int q_b = min(q_end - q0, max_q);
+  const int q_b = min(q_end - q0, max_q);  // query rows of the sequence; this launch takes rows row0 .. row0 + rows_per
   const int k_b = nug_len != nullptr ? k_end : k_end - k0;
   const int m_b = loc_len != nullptr ? l_end : l_end - l0;
-  if (q_b <= 0) return;  // uniform over the workgroup and over the splits: nothing to write, nothing to wait for
+  if (q_b <= row0) return;  // uniform over the workgroup and over the splits: nothing to write, nothing to wait for
+  const int q_cnt = min(rows_per, q_b - row0);
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int lane = tid % kWave;
   const int j = lane & 31, g = lane >> 5;
-  const int nv = q_b * G;  // query vectors of this workgroup: vector v = (row v / G, head kvh * G + v % G)
+  const int nv = q_cnt * G;  // query vectors of this workgroup: vector v = (row row0 + v / G, head kvh * G + v % G)
   const bool valid = j < nv;
   const int jv = valid ? j : 0;  // spare lanes repeat vector 0; nothing of them is stored
-  const int my_i = static_cast<int>(fast_div(static_cast<uint32_t>(jv), div_G));
-  const int my_h = kvh * G + (jv - my_i * G);
-  // causal rule, bottom-right aligned: query row i sees local rows j <= m_b - q_b + i; the last row sees all
+  const int my_il = static_cast<int>(fast_div(static_cast<uint32_t>(jv), div_G));
+  const int my_i = row0 + my_il;
+  const int my_h = kvh * G + (jv - my_il * G);
+  // causal rule, bottom-right aligned: query row i sees local rows j <= m_b - q_b + i (the sequence's last row sees
+  // all); the launch's last row bounds the local tiles
+  const int wg_vis = max(0, min(m_b, m_b - q_b + row0 + q_cnt));
   const int my_vis = valid ? max(0, min(m_b, m_b - q_b + my_i + 1)) : 0;
 
   const int n_nug_tiles = (k_b + kKeys - 1) / kKeys;
-  const int n_loc_tiles = (m_b + kKeys - 1) / kKeys;
+  const int n_loc_tiles = (wg_vis + kKeys - 1) / kKeys;
   const int n_tiles = n_nug_tiles + n_loc_tiles;
   const int per_split = (n_tiles + nsplit - 1) / nsplit;
   const int t0 = min(n_tiles, split * per_split), t1 = min(n_tiles, t0 + per_split);
@@ -329,8 +334,9 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
     }
   };
   auto out_row_of = [&](int v, int& i_out, int& h_out) -> int64_t {
-    i_out = static_cast<int>(fast_div(static_cast<uint32_t>(v), div_G));
-    h_out = kvh * G + (v - i_out * G);
+    const int il = static_cast<int>(fast_div(static_cast<uint32_t>(v), div_G));
+    i_out = row0 + il;
+    h_out = kvh * G + (v - il * G);
     return static_cast<int64_t>(q0 + i_out) * H + h_out;
   };
   const int n_out = nv * kDH;
@@ -492,7 +498,7 @@ __global__ __launch_bounds__(NWV * kWave) void group_attention_kernel(
 }
 
 template <int DH, int NWV>
-int launch_nwv(const AttnParams& p, int nsplit, uint32_t* flags) {
+int launch_nwv(const AttnParams& p, int row0, int rows_per, int nsplit, uint32_t* flags) {
   constexpr int kLds = NWV * GroupDims<DH>::kWaveLds;
   const void* kernel = reinterpret_cast<const void*>(&group_attention_kernel<DH, NWV>);
   const int rc = allow_dynamic_lds(kernel, kLds);
@@ -503,7 +509,7 @@ int launch_nwv(const AttnParams& p, int nsplit, uint32_t* flags) {
                      static_cast<const uint16_t*>(p.Q), static_cast<const uint16_t*>(p.Kn),
                      static_cast<const uint16_t*>(p.Vn), static_cast<const uint16_t*>(p.Kl),
                      static_cast<const uint16_t*>(p.Vl), p.cu_q, p.cu_nuggets, p.nug_len, p.cu_local, p.loc_len, p.H,
-                     p.H_kv, G, make_fast_div(static_cast<uint32_t>(G)), p.max_q, nsplit, p.nug_tok_stride,
+                     p.H_kv, G, make_fast_div(static_cast<uint32_t>(G)), p.max_q, row0, rows_per, nsplit, p.nug_tok_stride,
                      p.nug_head_stride, p.scale_log2e, static_cast<uint16_t*>(p.O), p.lse, static_cast<float*>(p.ws),
                      flags);
   return launch_status();
@@ -547,10 +553,20 @@ size_t group_workspace_bytes(int32_t B, int32_t H, int32_t H_kv, int32_t d_h, in
   return n <= 1 ? 0 : static_cast<size_t>(B) * max_q * H * n * (d_h + 3) * sizeof(float);
 }
 
+// Launches that cover the query rows of a call: each takes as many rows as fit the 32 vectors of a tile with G
+// heads per row.  0: the kernel does not take such a call (fewer than 4 vectors share a row, more than 32 heads
+// per KV head, or more than four passes over the keys, where the K/V rows would be read too often).
+int group_launches(int32_t H, int32_t H_kv, int32_t max_q) {
+  const int64_t G = H / H_kv;
+  if (G > kMaxVectors || G * max_q < 4) return 0;
+  const int rows_per = static_cast<int>(kMaxVectors / G);
+  const int launches = (max_q + rows_per - 1) / rows_per;
+  return launches <= 4 ? launches : 0;
+}
+
 bool group_attention_applies(const AttnParams& p) {
   if (p.dtype != DODO_DTYPE_BF16 || (p.d_h != 128 && p.d_h != 64) || p.nug_idx != nullptr) return false;
-  const int64_t vectors = static_cast<int64_t>(p.H / p.H_kv) * p.max_q;
-  if (vectors < 4 || vectors > kMaxVectors) return false;
+  if (group_launches(p.H, p.H_kv, p.max_q) == 0) return false;
   if (p.B > 65535) return false;  // second grid dimension
   // a row number times a stride in bytes is kept in 32 bits
   if (p.nug_tok_stride * 2 * kKeys > 0xffffffffLL || static_cast<int64_t>(p.H_kv) * p.d_h * 2 * kKeys > 0xffffffffLL)
@@ -568,8 +584,17 @@ int launch_group_attention(const AttnParams& p) {
                                                       static_cast<int64_t>(p.B) * p.max_q * p.H * nsplit * (p.d_h + 2));
   // two workgroups of two wavefronts per compute unit when there are that many; else one of four
   const bool two = static_cast<int64_t>(p.B) * p.H_kv * nsplit >= 2 * compute_units();
-  if (p.d_h == 128) return two ? launch_nwv<128, 2>(p, nsplit, flags) : launch_nwv<128, 4>(p, nsplit, flags);
-  return two ? launch_nwv<64, 2>(p, nsplit, flags) : launch_nwv<64, 4>(p, nsplit, flags);
+  const int rows_per = kMaxVectors / (p.H / p.H_kv);
+  for (int row0 = 0; row0 < p.max_q; row0 += rows_per) {  // (records and flags of different rows are apart)
+    int rc;
+    if (p.d_h == 128) {
+      rc = two ? launch_nwv<128, 2>(p, row0, rows_per, nsplit, flags) : launch_nwv<128, 4>(p, row0, rows_per, nsplit, flags);
+    } else {
+      rc = two ? launch_nwv<64, 2>(p, row0, rows_per, nsplit, flags) : launch_nwv<64, 4>(p, row0, rows_per, nsplit, flags);
+    }
+    if (rc != DODO_OK) return rc;
+  }
+  return DODO_OK;
 }
 
 }  // namespace dodo

@@ -134,7 +134,7 @@ def test_attention_argument_validation(lib):
     assert call(B=2, H=2, H_kv=2, max_q=1, max_k=3277, max_local=1089, ws=0, ws_bytes=0) == -3
     assert call(B=2, H=2, H_kv=2, max_q=1, max_k=3277, max_local=1089, ws=P, ws_bytes=need - 1) == -3
     assert lib.dodo_nugget_attention_workspace_bytes(8, 32, 128, 512, 410, 640, 1) == 0
-    # with the number of KV heads known: never less; more for a small batch of grouped heads (bf16, 4 to 32
+    # with the number of KV heads known: never less; more for a small batch of grouped heads (bf16, at least 4
     # query vectors per K/V row); the same where that kernel does not apply
     lib.dodo_nugget_attention_workspace_bytes_grouped.restype = ctypes.c_size_t
     G = lib.dodo_nugget_attention_workspace_bytes_grouped
@@ -147,6 +147,8 @@ def test_attention_argument_validation(lib):
     assert G(2, 64, 8, 128, 1, 3277, 1089, 0) == lib.dodo_nugget_attention_workspace_bytes(2, 64, 128, 1, 3277, 1089, 0)
     assert G(64, 64, 8, 128, 1, 410, 257, 1) == 0          # enough (sequence, KV head) pairs: no split wanted
     assert G(2, 64, 8, 128, 512, 3277, 1089, 1) == 0       # query blocks go to the other matrix-core kernel
+    assert G(2, 64, 8, 128, 15, 3277, 1089, 1) > lib.dodo_nugget_attention_workspace_bytes(2, 64, 128, 15, 3277, 1089, 1)  # four passes
+    assert G(2, 128, 2, 128, 1, 3277, 1089, 1) == lib.dodo_nugget_attention_workspace_bytes(2, 128, 128, 1, 3277, 1089, 1)  # 64 heads per KV head
     assert G(2, 64, 5, 128, 1, 3277, 1089, 1) == plain     # H_kv does not divide H: the plain size (the call refuses)
 
 

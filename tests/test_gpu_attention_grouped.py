@@ -87,6 +87,24 @@ def test_small_query_blocks_share_their_keys(D):
     _check(D, 724, q8, [0] * B, [max(m, 1) for m in m_lens], 16, 4)  # local rows only
 
 
+def test_more_than_32_vectors_take_several_passes(D):
+    # rows x heads beyond one tile: the rows are dealt out to up to four launches, each with its own causal limits
+    rng = np.random.default_rng(13)
+    B = 40
+    q_lens = [int(v) for v in rng.integers(0, 16, B)]
+    q_lens[0], q_lens[1], q_lens[2] = 15, 0, 4        # all passes, none, exactly the first
+    k_lens = [int(v) for v in rng.integers(0, 120, B)]
+    m_lens = [int(v) for v in rng.integers(0, 40, B)]
+    m_lens[0] = 7                                       # fewer local rows than query rows: early rows see none
+    _check(D, 780, q_lens, k_lens, m_lens, 64, 8)      # 8 heads x 15 rows: four passes of 4 rows
+    _check(D, 781, q_lens, k_lens, m_lens, 16, 4)      # 4 heads x 15 rows: two passes of 8 rows
+    _check(D, 782, [min(q, 8) for q in q_lens], k_lens, m_lens, 32, 2, d_h=64)   # 16 heads x 8 rows: four passes of 2
+    _check(D, 783, [min(q, 6) for q in q_lens], k_lens, m_lens, 20, 4)           # 5 heads x 6 rows: one pass of 6
+    # few sequences and long caches: every pass splits the keys over workgroups, all on one workspace
+    _check(D, 784, [15, 9], [3277, 1500], [1089, 1025], 64, 8)
+    _check(D, 785, [7, 7, 2], [2000, 37, 900], [300, 700, 31], 40, 8, layout=1)
+
+
 def test_heads_of_64_channels(D):
     # the same kernel with half the channels: other tile sizes, LDS swizzles and fragment counts
     rng = np.random.default_rng(12)
