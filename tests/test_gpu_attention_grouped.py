@@ -144,6 +144,22 @@ def test_run_to_run_deterministic(D):
     assert not bool(ws.view(torch.int32)[-n_slots:].any())  # the flags of the largest layout are left cleared
 
 
+def test_workspace_needs_no_zero_fill_and_is_reusable(D):
+    # bytes that are not the "ready" value are as good as zeros, and a workspace serves call after call
+    q, k, m, H, H_kv = [1, 1], [3000, 1234], [700, 1025], 64, 8
+    need = D.dodo_nugget_attention_workspace_bytes_grouped(2, H, H_kv, 128, 1, max(k), max(m), D.BF16)
+    assert need > D.dodo_nugget_attention_workspace_bytes(2, H, 128, 1, max(k), max(m), D.BF16)
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=dev())
+    for seed in (790, 791, 792):
+        host, t = make_attention_case(seed, q, k, m, H, H_kv, 128, BF, dev())
+        O_ref, lse_ref = oracle.attention(host["Q"], host["Kn"], host["Vn"], host["Kl"], host["Vl"], host["cu_q"],
+                                          host["cu_nuggets"], host["cu_local"], default_scale(128))
+        O, lse = D.dodo_nugget_attention(t["Q"], t["Kn"], t["Vn"], t["Kl"], t["Vl"], t["cu_q"], t["cu_nuggets"],
+                                         t["cu_local"], 1, max(k), max(m), default_scale(128), 0, want_lse=True, ws=ws)
+        check_attention(O, O_ref, BF)
+        check_lse(lse, lse_ref, BF)
+
+
 def test_caches_with_room_to_grow_and_segment_ranges(D):
     # start + length ranges for the nuggets (cached form) and for both kinds of rows (segment form)
     rng = np.random.default_rng(11)
